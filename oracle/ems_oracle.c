@@ -1,0 +1,254 @@
+/*
+ * ems_oracle.c -- TEST INFRASTRUCTURE, not product code.
+ *
+ * A plain, slow, fp64 CPU statement of what the ragged verification step of
+ * batched speculative decoding computes (EMS-SD, arXiv 2405.07542).  It shares
+ * no code with the HIP library and is only ever called by the tests, the smoke
+ * check and the bench's cpu_baseline leg.
+ *
+ * Notation (Sec. 3.2 "Unpad KV cache" / "Unpad input tokens", Appendix D):
+ *   B samples; sample i brings k_i packed query rows (row 0 = last emitted
+ *   token, rows 1.. = draft tokens), cu[i] = k_0 + ... + k_{i-1}  (the running
+ *   sum of Alg. 1's token_nums_per_sample), T = cu[B].
+ *   Sample i owns cache rows [kv_start[i], kv_start[i] + kv_len[i]) of a shared
+ *   arena; element (row r, head h, dim d) sits at r*row_stride + h*head_stride + d.
+ *   Packed tensors (q, k_new, v_new, out) are [T, H, D], d fastest.
+ *
+ * Every function states the passage it follows.  There is no tiling, fusion or
+ * reordering: each output is computed from its definition.  The only
+ * parallelism is an OpenMP `parallel for` over independent (sample, head)
+ * pairs / independent rows; every output element is produced by one thread
+ * with a fixed summation order, so results do not depend on the thread count.
+ *
+ * Parity pins (tests/test_oracle_*.py): dense padded per-sample brute force,
+ * torch's CPU attention in the k_i = 1 and kv_len = 0 special cases,
+ * autoregressive equivalence, closed forms, the paper's Table 1, Alg. 2 run
+ * literally, sentinel-filled arenas.  No function here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F16 = 0, ORACLE_BF16 = 1 };
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* Exact widening of one IEEE binary16 / bfloat16 bit pattern to double. */
+static double widen(uint16_t bits, int dtype) {
+    if (dtype == ORACLE_BF16) {
+        uint32_t u = (uint32_t)bits << 16;
+        float f;
+        memcpy(&f, &u, sizeof f);
+        return (double)f;
+    }
+    int sign = bits >> 15;
+    int expo = (bits >> 10) & 0x1f;
+    int frac = bits & 0x3ff;
+    double mag;
+    if (expo == 0)
+        mag = ldexp((double)frac, -24);            /* zero and subnormals */
+    else if (expo == 31)
+        mag = frac ? NAN : INFINITY;
+    else
+        mag = ldexp((double)(frac | 0x400), expo - 25);
+    return sign ? -mag : mag;
+}
+
+/* Alg. 2 (Appendix D): recover (sample, position-in-sample) of packed row r
+ * by walking the per-sample token counts.  Returns 0 on success. */
+int oracle_restore_index(const int32_t* token_nums_per_sample, int B, int r,
+                         int32_t* sample, int32_t* position) {
+    int pos = r, i = 0;
+    while (i < B && pos >= token_nums_per_sample[i]) {
+        pos -= token_nums_per_sample[i];
+        i += 1;
+    }
+    if (i >= B) return 1;
+    *sample = i;
+    *position = pos;
+    return 0;
+}
+
+/*
+ * Packed multi-token attention over per-sample caches (Sec. 3.2: every token
+ * attends to its own sample's cached rows, found through the per-sample start
+ * location, and causally to its own sample's new tokens; Fig. 3).
+ *
+ * For sample i, head h, query row j (0 <= j < k_i), with L = kv_len[i]:
+ *   key n   = cache row kv_start[i]+n           for n <  L
+ *           = new row   cu[i] + (n - L)          for n >= L      (N = L + k_i keys)
+ *   mask[n] = (n <= L + j)       -- the new token sees itself (inclusive causal)
+ *   S[n]    = scale * <q_j, key_n>     where mask, else -inf
+ *   p       = softmax_n(S)  (max-subtracted),  out_j = sum_n p[n] * val_n
+ * Inputs are widened exactly to fp64; out is fp64 [T, H, D].
+ */
+int oracle_verify_attention(const uint16_t* q, const uint16_t* k_new, const uint16_t* v_new,
+                            const uint16_t* k_cache, const uint16_t* v_cache,
+                            int64_t row_stride, int64_t head_stride,
+                            const int32_t* cu, const int32_t* kv_start, const int32_t* kv_len,
+                            double* out, int B, int H, int D, float scale, int dtype) {
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int i = 0; i < B; ++i) {
+        for (int h = 0; h < H; ++h) {
+            const int k = cu[i + 1] - cu[i];
+            const int L = kv_len[i];
+            const int64_t s = kv_start[i];
+            const int N = L + k;
+            if (k <= 0) continue;
+            double* key = (double*)malloc(sizeof(double) * (size_t)N * D);
+            double* val = (double*)malloc(sizeof(double) * (size_t)N * D);
+            double* S = (double*)malloc(sizeof(double) * (size_t)N);
+            double* p = (double*)malloc(sizeof(double) * (size_t)N);
+            unsigned char* mask = (unsigned char*)malloc((size_t)N);
+            if (!key || !val || !S || !p || !mask) {
+#pragma omp atomic write
+                failed = 1;
+                free(key); free(val); free(S); free(p); free(mask);
+                continue;
+            }
+            for (int n = 0; n < N; ++n) {
+                for (int d = 0; d < D; ++d) {
+                    if (n < L) {
+                        int64_t off = (s + n) * row_stride + (int64_t)h * head_stride + d;
+                        key[(size_t)n * D + d] = widen(k_cache[off], dtype);
+                        val[(size_t)n * D + d] = widen(v_cache[off], dtype);
+                    } else {
+                        int64_t off = ((int64_t)(cu[i] + n - L) * H + h) * D + d;
+                        key[(size_t)n * D + d] = widen(k_new[off], dtype);
+                        val[(size_t)n * D + d] = widen(v_new[off], dtype);
+                    }
+                }
+            }
+            for (int j = 0; j < k; ++j) {
+                const int64_t qoff = ((int64_t)(cu[i] + j) * H + h) * D;
+                for (int n = 0; n < N; ++n) mask[n] = (unsigned char)(n <= L + j);
+                double m = -INFINITY;
+                for (int n = 0; n < N; ++n) {
+                    if (mask[n]) {
+                        double dot = 0.0;
+                        for (int d = 0; d < D; ++d)
+                            dot += widen(q[qoff + d], dtype) * key[(size_t)n * D + d];
+                        S[n] = (double)scale * dot;
+                    } else {
+                        S[n] = -INFINITY;
+                    }
+                    if (S[n] > m) m = S[n];
+                }
+                double Z = 0.0;
+                for (int n = 0; n < N; ++n) {
+                    p[n] = mask[n] ? exp(S[n] - m) : 0.0;
+                    Z += p[n];
+                }
+                for (int d = 0; d < D; ++d) {
+                    double acc = 0.0;
+                    for (int n = 0; n < N; ++n) acc += p[n] * val[(size_t)n * D + d];
+                    out[qoff + d] = acc / Z;
+                }
+            }
+            free(key); free(val); free(S); free(p); free(mask);
+        }
+    }
+    return failed;
+}
+
+/*
+ * Greedy target token per packed row (Appendix A, the arg-max of the target
+ * distribution): x[r] = the smallest v attaining max_v logits[r, v].
+ * Values are widened exactly, so +0 and -0 compare equal and the lower index
+ * wins; inputs are finite by contract.
+ */
+int oracle_argmax(const uint16_t* logits, int dtype, int T, int V, int32_t* x) {
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < T; ++r) {
+        const uint16_t* row = logits + (size_t)r * V;
+        double best = widen(row[0], dtype);
+        int32_t arg = 0;
+        for (int v = 1; v < V; ++v) {
+            double y = widen(row[v], dtype);
+            if (y > best) { best = y; arg = v; }
+        }
+        x[r] = arg;
+    }
+    return 0;
+}
+
+/*
+ * Acceptance length per sample (Appendix A, the acceptance-length equation,
+ * and Sec. 3.1: with k drafts between 1 and k+1 tokens are accepted), its
+ * running sum, and the accepted target tokens packed sample after sample.
+ *
+ * Packed row j of sample i carries input token input_ids[cu[i]+j]; row 0 is
+ * the last emitted token and rows 1..k_i-1 are the drafts.  x[cu[i]+j] is the
+ * target's greedy token after row j.  Draft j+1 is accepted while it equals
+ * x[cu[i]+j] and every earlier draft was accepted; the row after the last
+ * draft has nothing to be compared with, which ends the run.
+ *   accepted[i] = (number of leading accepted drafts) + 1,   0 when k_i = 0.
+ */
+int oracle_greedy_accept(const int32_t* x, const int32_t* input_ids, const int32_t* cu, int B,
+                         int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens) {
+    accepted_cu[0] = 0;
+    for (int i = 0; i < B; ++i) {
+        const int k = cu[i + 1] - cu[i];
+        int tau = 0;
+        if (k > 0) {
+            int m = 0;
+            while (m < k - 1 && x[cu[i] + m] == input_ids[cu[i] + m + 1]) m += 1;
+            tau = m + 1;
+        }
+        accepted[i] = tau;
+        accepted_cu[i + 1] = accepted_cu[i] + tau;
+        if (out_tokens)
+            for (int j = 0; j < tau; ++j) out_tokens[accepted_cu[i] + j] = x[cu[i] + j];
+    }
+    return 0;
+}
+
+/*
+ * KV-cache append (Sec. 3.2 "Unpad KV cache": each sample's write location
+ * advances by its own accepted count, so no padding row ever enters a cache).
+ * The first accepted[i] new rows of sample i are copied, bit for bit, to cache
+ * rows kv_start[i]+kv_len[i]+j; kv_len_out[i] = kv_len[i] + accepted[i].
+ * Nothing else in the arena is written.
+ */
+int oracle_kv_append(uint16_t* k_cache, uint16_t* v_cache, int64_t row_stride, int64_t head_stride,
+                     const uint16_t* k_new, const uint16_t* v_new,
+                     const int32_t* cu, const int32_t* accepted,
+                     const int32_t* kv_start, const int32_t* kv_len, int32_t* kv_len_out,
+                     int B, int H, int D) {
+    for (int i = 0; i < B; ++i) {
+        for (int j = 0; j < accepted[i]; ++j) {
+            const int64_t dst_row = (int64_t)kv_start[i] + kv_len[i] + j;
+            const int64_t src_row = (int64_t)cu[i] + j;
+            for (int h = 0; h < H; ++h) {
+                for (int d = 0; d < D; ++d) {
+                    int64_t dst = dst_row * row_stride + (int64_t)h * head_stride + d;
+                    int64_t src = (src_row * H + h) * D + d;
+                    k_cache[dst] = k_new[src];
+                    v_cache[dst] = v_new[src];
+                }
+            }
+        }
+    }
+    if (kv_len_out)
+        for (int i = 0; i < B; ++i) kv_len_out[i] = kv_len[i] + accepted[i];
+    return 0;
+}

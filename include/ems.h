@@ -1,0 +1,184 @@
+/*
+ * ems.h -- C ABI of libems: the unpadded (ragged) verification step of batched
+ * speculative decoding on one MI355X (gfx950), after EMS-SD (arXiv 2405.07542).
+ *
+ * One verification step of a batch of B samples:
+ *   1. ems_verify_attention  packed multi-token attention; each sample reads its
+ *                            own contiguous KV cache through a per-sample start
+ *                            location (Sec. 3.2 "Unpad KV cache") and its own new
+ *                            tokens causally; the inputs of all samples are
+ *                            concatenated without padding (Sec. 3.2 "Unpad input
+ *                            tokens", Appendix D Alg. 1 and Alg. 2)
+ *   2. ems_greedy_accept     greedy target tokens and per-sample acceptance length
+ *                            (Appendix A), plus the running sum of the lengths
+ *   3. ems_kv_append         only the accepted tokens' K/V enter each cache, at the
+ *                            sample's own location, which advances by its own
+ *                            accepted count (Sec. 3.2, Fig. 2 / Table 1)
+ * plus the padded "vanilla" method of Sec. 3.1 as an ablation in the same library.
+ *
+ * Conventions shared by every entry point
+ *   - Pointers named *device* point to GPU memory owned by the caller; pointers
+ *     named *host* are ordinary host memory read during the call only.
+ *   - The library never allocates, frees or synchronises.  Work is enqueued on
+ *     `hip_stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ *     the call returns at once.  Device arrays must stay alive until that work is
+ *     done.
+ *   - Packed tensors q, k_new, v_new, out are [T, H, D], d fastest, no padding
+ *     rows; sample i owns rows cu_seqlens[i] .. cu_seqlens[i+1]-1 (k_i rows).
+ *     Row 0 of a sample is its last emitted token (whose K/V is not cached yet),
+ *     rows 1.. are its draft tokens: "k predicted tokens" in the paper's words
+ *     means k_i = k + 1 rows here.
+ *   - 16-bit element types only (ems_dtype) for q/k/v/logits; device pointers to
+ *     such tensors must be 16-byte aligned.
+ *   - Scalar and pointer arguments are validated on the host before anything is
+ *     launched; the contents of device arrays (monotone cu_seqlens, regions that
+ *     do not overlap, kv_len[i] + k_i within the region) are the caller's
+ *     contract and are NOT checked (ems_validate_inputs does, synchronously).
+ *   - Every function returns an ems_status; ems_last_error_string() gives a
+ *     thread-local description of the last failure.
+ */
+#ifndef EMS_H
+#define EMS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EMS_API __attribute__((visibility("default")))
+
+typedef enum {
+    EMS_OK = 0,
+    EMS_ERR_INVALID_ARG = 1, /* bad scalar, NULL or misaligned pointer */
+    EMS_ERR_UNSUPPORTED = 2, /* legal request outside what the kernels cover */
+    EMS_ERR_WORKSPACE = 3,   /* workspace missing or too small */
+    EMS_ERR_HIP = 4          /* a HIP runtime call failed */
+} ems_status;
+
+typedef enum { EMS_F16 = 0, EMS_BF16 = 1, EMS_F32 = 2 /* outputs only */ } ems_dtype;
+
+#define EMS_MAX_QUERY_ROWS 16   /* largest k_i (rows per sample per step) */
+#define EMS_MAX_LAYERS_PER_CALL 32
+
+/*
+ * Strided view of a KV-cache arena of `rows` token rows shared by all samples.
+ * Element (row r, head h, dim d) is at  r*row_stride + h*head_stride + d  (in
+ * elements); the D elements of one (row, head) are contiguous.  Covers
+ * token-major [R,H,D] (row_stride = H*D, head_stride = D) and head-major
+ * [H,R,D] (row_stride = D, head_stride = R*D).  Sample i's cache is the run of
+ * rows kv_start[i] .. kv_start[i]+kv_len[i]-1: its start location is its own
+ * (Sec. 3.2), so caches of different lengths sit side by side without padding.
+ */
+typedef struct {
+    void* k;             /* device */
+    void* v;             /* device */
+    int64_t row_stride;  /* elements; multiple of 8 */
+    int64_t head_stride; /* elements; multiple of 8 */
+    int64_t rows;        /* R */
+} ems_kv_cache;
+
+/* Bytes of device workspace ems_verify_attention needs for these bounds
+ * (split-KV partial results).  Never 0.  Pure host arithmetic. */
+EMS_API size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len);
+
+/*
+ * Packed multi-token attention over per-sample caches (Sec. 3.2; Fig. 3).
+ * For sample i, head h, row j < k_i, with L = kv_len[i]:
+ *     keys/values n < L   : cache rows kv_start[i] + n
+ *     keys/values n >= L  : k_new / v_new rows cu_seqlens[i] + (n - L)
+ *     out[cu_seqlens[i]+j, h, :] = softmax_n( scale * <q_j, key_n> , n <= L + j ) . value_n
+ * i.e. every cached row plus the sample's own new rows up to and including row j.
+ * The cache is only read; k_new/v_new are read from the packed tensors.
+ * fp32 accumulation; `out` is rounded once to out_dtype (dtype, or EMS_F32).
+ *
+ *   q,k_new,v_new,out : device [T,H,D]       cu_seqlens : device int32 [B+1]
+ *   kv_start, kv_len  : device int32 [B]     cache      : host struct, device arenas
+ *   max_k      >= every k_i   (<= EMS_MAX_QUERY_ROWS)
+ *   max_kv_len >= every kv_len[i]            (host-known upper bounds)
+ * Samples with k_i = 0 contribute nothing; kv_len[i] = 0 is legal; T = 0 is a no-op.
+ * Errors: B<1, T<0, H<1, max_k<0, max_kv_len<0, NULL/misaligned pointer,
+ * non-finite scale -> INVALID_ARG; D not in {64,128}, max_k > 16, B > 8192
+ * -> UNSUPPORTED; workspace -> WORKSPACE; launch failure -> HIP.
+ */
+EMS_API ems_status ems_verify_attention(
+    const void* q, const void* k_new, const void* v_new,
+    const ems_kv_cache* cache,
+    const int32_t* cu_seqlens, const int32_t* kv_start, const int32_t* kv_len,
+    void* out, ems_dtype out_dtype,
+    int B, int T, int H, int D, int max_k, int max_kv_len,
+    float scale, ems_dtype dtype,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device workspace ems_greedy_accept needs (0 when logits == NULL is
+ * intended, i.e. V == 0). */
+EMS_API size_t ems_accept_workspace_bytes(int T, int V);
+
+/*
+ * Greedy acceptance (Appendix A: greedy token = arg-max of the target's
+ * distribution; acceptance length = 1 + number of leading drafts that equal the
+ * target's token for the row before them; Sec. 3.1: between 1 and k+1 tokens).
+ *
+ *   logits      device [T,V] of `dtype`, or NULL.  When given, target_ids[r] is
+ *               WRITTEN with the lowest index attaining the row maximum (+0 and -0
+ *               are equal; inputs must not hold NaN).  When NULL, target_ids is READ.
+ *   input_ids   device int32 [T]: packed input tokens (row 0 of a sample = last
+ *               emitted token, rows 1.. = drafts)
+ *   accepted    device int32 [B] out: m_i + 1 where m_i = number of leading j in
+ *               [0, k_i-2] with target_ids[cu+j] == input_ids[cu+j+1]; 0 if k_i = 0
+ *   accepted_cu device int32 [B+1] out: exclusive running sum, [B] = total
+ *   out_tokens  device int32 [T] or NULL: the accepted target tokens packed sample
+ *               after sample; the first accepted_cu[B] entries are written
+ * Errors: B<1 or B>8192, T<0, V<0, NULL required pointer -> INVALID_ARG /
+ * UNSUPPORTED; workspace too small (only with logits) -> WORKSPACE.
+ */
+EMS_API ems_status ems_greedy_accept(
+    const void* logits, ems_dtype dtype, int V,
+    int32_t* target_ids, const int32_t* input_ids,
+    const int32_t* cu_seqlens, int B, int T,
+    int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * KV-cache append (Sec. 3.2 "Unpad KV cache"): for every layer, sample i and
+ * j < accepted[i]:  cache row kv_start[i]+kv_len[i]+j  <-  new row cu_seqlens[i]+j
+ * (K and V, bit copies).  Then kv_len_out[i] = kv_len[i] + accepted[i]: the
+ * sample's write location advances by its own accepted count.  No other byte of
+ * any arena is written, so every cache stays contiguous and free of padding.
+ *
+ *   k_new_layers, v_new_layers : host arrays [n_layers] of device [T,H,D] pointers
+ *   caches                     : host array [n_layers]
+ *   kv_len_out                 : device int32 [B], may alias kv_len, NULL to skip
+ * Errors: n_layers<1, B<1, T<0, H<1, D<8 or D%8 != 0, NULL/misaligned -> INVALID_ARG.
+ * More than EMS_MAX_LAYERS_PER_CALL layers are processed in several launches.
+ */
+EMS_API ems_status ems_kv_append(
+    const void* const* k_new_layers, const void* const* v_new_layers,
+    const ems_kv_cache* caches, int n_layers,
+    const int32_t* cu_seqlens, const int32_t* accepted,
+    const int32_t* kv_start, const int32_t* kv_len, int32_t* kv_len_out,
+    int B, int T, int H, int D, ems_dtype dtype, void* hip_stream);
+
+/*
+ * Debug aid: copies the index arrays to the host (synchronises the stream) and
+ * checks the contract the other calls assume: cu_seqlens[0]=0, non-decreasing,
+ * cu_seqlens[B]=T, k_i <= max_k, 0 <= kv_len[i] <= max_kv_len, kv_start[i] >= 0,
+ * kv_start[i]+kv_len[i]+k_i <= rows, and regions [kv_start, kv_start+kv_len+k_i)
+ * of different samples do not overlap.  Returns INVALID_ARG with a message naming
+ * the first violation.
+ */
+EMS_API ems_status ems_validate_inputs(
+    const int32_t* cu_seqlens, const int32_t* kv_start, const int32_t* kv_len,
+    int B, int T, int max_k, int max_kv_len, int64_t rows, void* hip_stream);
+
+/* Thread-local text for the last non-OK status returned on this thread. */
+EMS_API const char* ems_last_error_string(void);
+
+/* Library version, "major.minor". */
+EMS_API const char* ems_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EMS_H */

@@ -1,0 +1,153 @@
+"""Python binding of libems: the ragged verification step of batched speculative
+decoding (EMS-SD, arXiv 2405.07542) on one MI355X.
+
+Argument marshalling only: every step runs in the HIP kernels behind the C ABI
+declared in ``include/ems.h``.  PyTorch supplies device memory (``data_ptr()``)
+and the current stream; there is no CPU fallback -- if ``libems.so`` has not
+been built (``python -m paper_2405_07542_amd.build``) importing the entry
+points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libems.so")
+
+EMS_OK, EMS_ERR_INVALID_ARG, EMS_ERR_UNSUPPORTED, EMS_ERR_WORKSPACE, EMS_ERR_HIP = range(5)
+EMS_F16, EMS_BF16, EMS_F32 = 0, 1, 2
+EMS_MAX_QUERY_ROWS = 16
+_DT = {torch.float16: EMS_F16, torch.bfloat16: EMS_BF16, torch.float32: EMS_F32}
+
+
+class EmsError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("ems status %d: %s" % (status, message))
+        self.status = status
+
+
+class KvCacheStruct(ctypes.Structure):
+    """Mirror of ``ems_kv_cache``."""
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("row_stride", ctypes.c_int64), ("head_stride", ctypes.c_int64),
+                ("rows", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it was not built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libems.so is missing: build it with "
+                              "`python -m paper_2405_07542_amd.build` (needs hipcc)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+        L.ems_last_error_string.restype = ctypes.c_char_p
+        L.ems_version.restype = ctypes.c_char_p
+        L.ems_attention_workspace_bytes.restype = sz
+        L.ems_attention_workspace_bytes.argtypes = [i32] * 5
+        L.ems_accept_workspace_bytes.restype = sz
+        L.ems_accept_workspace_bytes.argtypes = [i32, i32]
+        L.ems_verify_attention.restype = i32
+        L.ems_verify_attention.argtypes = [vp, vp, vp, ctypes.POINTER(KvCacheStruct), vp, vp, vp,
+                                           vp, i32, i32, i32, i32, i32, i32, i32,
+                                           ctypes.c_float, i32, vp, sz, vp]
+        L.ems_greedy_accept.restype = i32
+        L.ems_greedy_accept.argtypes = [vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.ems_kv_append.restype = i32
+        L.ems_kv_append.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                    ctypes.POINTER(KvCacheStruct), i32, vp, vp, vp, vp, vp,
+                                    i32, i32, i32, i32, i32, vp]
+        L.ems_validate_inputs.restype = i32
+        L.ems_validate_inputs.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, vp]
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != EMS_OK:
+        raise EmsError(status, lib().ems_last_error_string().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def kv_cache(k: torch.Tensor, v: torch.Tensor, row_stride: int, head_stride: int,
+             rows: int) -> KvCacheStruct:
+    return KvCacheStruct(k.data_ptr(), v.data_ptr(), int(row_stride), int(head_stride), int(rows))
+
+
+def ems_attention_workspace_bytes(B: int, T: int, H: int, D: int, max_kv_len: int) -> int:
+    return int(lib().ems_attention_workspace_bytes(B, T, H, D, max_kv_len))
+
+
+def ems_accept_workspace_bytes(T: int, V: int) -> int:
+    return int(lib().ems_accept_workspace_bytes(T, V))
+
+
+def ems_verify_attention(q, k_new, v_new, cache: KvCacheStruct, cu_seqlens, kv_start, kv_len,
+                         out, *, max_k: int, max_kv_len: int, scale: float,
+                         workspace: torch.Tensor, stream=None) -> None:
+    """out[T,H,D] <- packed multi-token attention over the per-sample caches."""
+    T, H, D = q.shape
+    B = kv_start.numel()
+    _check(lib().ems_verify_attention(
+        _ptr(q), _ptr(k_new), _ptr(v_new), ctypes.byref(cache), _ptr(cu_seqlens), _ptr(kv_start),
+        _ptr(kv_len), _ptr(out), _DT[out.dtype], B, T, H, D, int(max_k), int(max_kv_len),
+        float(scale), _DT[q.dtype], _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)))
+
+
+def ems_greedy_accept(logits: Optional[torch.Tensor], target_ids, input_ids, cu_seqlens,
+                      accepted, accepted_cu, out_tokens: Optional[torch.Tensor], *,
+                      workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    B = accepted.numel()
+    T = input_ids.numel()
+    V = logits.shape[1] if logits is not None else 0
+    dt = _DT[logits.dtype] if logits is not None else EMS_F16
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().ems_greedy_accept(
+        _ptr(logits), dt, V, _ptr(target_ids), _ptr(input_ids), _ptr(cu_seqlens), B, T,
+        _ptr(accepted), _ptr(accepted_cu), _ptr(out_tokens), _ptr(workspace), ws_bytes,
+        _stream(stream)))
+
+
+def ems_kv_append(k_new_layers: Sequence[torch.Tensor], v_new_layers: Sequence[torch.Tensor],
+                  caches: Sequence[KvCacheStruct], cu_seqlens, accepted, kv_start, kv_len,
+                  kv_len_out: Optional[torch.Tensor], stream=None) -> None:
+    n = len(caches)
+    assert len(k_new_layers) == n and len(v_new_layers) == n
+    T, H, D = k_new_layers[0].shape
+    B = kv_start.numel()
+    karr = (ctypes.c_void_p * n)(*[t.data_ptr() for t in k_new_layers])
+    varr = (ctypes.c_void_p * n)(*[t.data_ptr() for t in v_new_layers])
+    carr = (KvCacheStruct * n)(*caches)
+    _check(lib().ems_kv_append(karr, varr, carr, n, _ptr(cu_seqlens), _ptr(accepted),
+                               _ptr(kv_start), _ptr(kv_len), _ptr(kv_len_out), B, T, H, D,
+                               _DT[k_new_layers[0].dtype], _stream(stream)))
+
+
+def ems_validate_inputs(cu_seqlens, kv_start, kv_len, *, T: int, max_k: int, max_kv_len: int,
+                        rows: int, stream=None) -> None:
+    _check(lib().ems_validate_inputs(_ptr(cu_seqlens), _ptr(kv_start), _ptr(kv_len),
+                                     kv_start.numel(), T, max_k, max_kv_len, rows,
+                                     _stream(stream)))
+
+
+__all__ = ["EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
+           "ems_accept_workspace_bytes", "ems_verify_attention", "ems_greedy_accept",
+           "ems_kv_append", "ems_validate_inputs", "EMS_F16", "EMS_BF16", "EMS_F32"]

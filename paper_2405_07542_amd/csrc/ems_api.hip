@@ -1,0 +1,308 @@
+// C ABI of libems: argument validation (host only, before any HIP call),
+// launch sizing, error strings.  See include/ems.h for the contract.
+#include "../../include/ems.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "ems_kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+ems_status fail(ems_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+ems_status hip_fail(const char* what, hipError_t e) {
+    return fail(EMS_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+constexpr int kTileKeys = 32;
+constexpr int kWavesPerBlock = 4;
+constexpr int kMinTilesPerWave = 4;
+constexpr int kMaxAttnBlocks = 1024;
+constexpr int kMaxB = 8192;
+
+// Upper bound of the number of 32-key tiles of the whole batch (host-known bounds only).
+int64_t tile_upper_bound(int B, int H, int max_kv_len) {
+    return (int64_t)B * H * ((max_kv_len + kTileKeys - 1) / kTileKeys + 1);
+}
+
+int attn_blocks_for(int64_t tiles, int max_blocks) {
+    int64_t want = (tiles + kWavesPerBlock * kMinTilesPerWave - 1) / (kWavesPerBlock * kMinTilesPerWave);
+    return (int)std::max<int64_t>(1, std::min<int64_t>(want, max_blocks));
+}
+
+size_t attn_ws_bytes_for(int blocks, int D) {
+    return (size_t)2 * blocks * kWavesPerBlock * 16 * (D + ems::kPartialPad) * sizeof(float);
+}
+
+// Workgroups the device keeps resident for the attention kernel (2 per CU), cached per device.
+int resident_attn_blocks() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 512;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        cached[dev] = std::min(kMaxAttnBlocks, 2 * cus);
+    }
+    return cached[dev];
+}
+
+void accept_slicing(int T, int V, int* slices, int* slice_len) {
+    // enough blocks to fill the chip, slices a multiple of 8 columns, at least 2048 columns each
+    int s = T > 0 ? (2048 + T - 1) / T : 1;
+    s = std::max(1, std::min(s, 16));
+    int len = (V + s - 1) / s;
+    len = std::max(2048, (len + 7) / 8 * 8);
+    *slice_len = len;
+    *slices = std::max(1, (V + len - 1) / len);
+}
+
+bool dtype16(ems_dtype d) { return d == EMS_F16 || d == EMS_BF16; }
+
+}  // namespace
+
+extern "C" {
+
+const char* ems_last_error_string(void) { return g_err; }
+
+const char* ems_version(void) { return "0.1"; }
+
+size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len) {
+    (void)T;
+    if (B < 1 || H < 1 || D < 1 || max_kv_len < 0) return 256;
+    const int blocks = attn_blocks_for(tile_upper_bound(B, H, max_kv_len), kMaxAttnBlocks);
+    return std::max<size_t>(256, attn_ws_bytes_for(blocks, D));
+}
+
+ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_new,
+                                const ems_kv_cache* cache, const int32_t* cu_seqlens,
+                                const int32_t* kv_start, const int32_t* kv_len, void* out,
+                                ems_dtype out_dtype, int B, int T, int H, int D, int max_k,
+                                int max_kv_len, float scale, ems_dtype dtype, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+    if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
+    if (T < 0) return fail(EMS_ERR_INVALID_ARG, "T = %d, need T >= 0", T);
+    if (H < 1) return fail(EMS_ERR_INVALID_ARG, "H = %d, need H >= 1", H);
+    if (max_k < 0 || max_kv_len < 0)
+        return fail(EMS_ERR_INVALID_ARG, "max_k = %d, max_kv_len = %d must not be negative", max_k, max_kv_len);
+    if (!std::isfinite(scale)) return fail(EMS_ERR_INVALID_ARG, "scale is not finite");
+    if (!dtype16(dtype)) return fail(EMS_ERR_INVALID_ARG, "dtype must be EMS_F16 or EMS_BF16");
+    if (out_dtype != dtype && out_dtype != EMS_F32)
+        return fail(EMS_ERR_INVALID_ARG, "out_dtype must equal dtype or be EMS_F32");
+    if (!cu_seqlens || !kv_start || !kv_len)
+        return fail(EMS_ERR_INVALID_ARG, "cu_seqlens, kv_start and kv_len must not be NULL");
+    if (D != 64 && D != 128) return fail(EMS_ERR_UNSUPPORTED, "D = %d, supported head dims are 64 and 128", D);
+    if (max_k > EMS_MAX_QUERY_ROWS)
+        return fail(EMS_ERR_UNSUPPORTED, "max_k = %d, at most %d rows per sample", max_k, EMS_MAX_QUERY_ROWS);
+    if (B > kMaxB) return fail(EMS_ERR_UNSUPPORTED, "B = %d, at most %d samples", B, kMaxB);
+    if (T == 0) return EMS_OK;
+    if (!q || !k_new || !v_new || !out) return fail(EMS_ERR_INVALID_ARG, "q, k_new, v_new and out must not be NULL");
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out))
+        return fail(EMS_ERR_INVALID_ARG, "q, k_new, v_new and out must be 16-byte aligned");
+    if (!cache) return fail(EMS_ERR_INVALID_ARG, "cache must not be NULL");
+    if (cache->row_stride < D || cache->head_stride < D || (cache->row_stride & 7) || (cache->head_stride & 7))
+        return fail(EMS_ERR_INVALID_ARG, "cache strides must be multiples of 8 elements and at least D");
+    if (max_kv_len > 0 && (!cache->k || !cache->v || !aligned16(cache->k) || !aligned16(cache->v)))
+        return fail(EMS_ERR_INVALID_ARG, "cache arenas must be non-NULL and 16-byte aligned");
+    if (cache->rows < 0) return fail(EMS_ERR_INVALID_ARG, "cache rows must not be negative");
+    // a sample's cache is addressed with 32-bit byte offsets from its first row
+    if (((int64_t)max_kv_len + kTileKeys) * cache->row_stride * 2 >= ((int64_t)1 << 32))
+        return fail(EMS_ERR_UNSUPPORTED, "max_kv_len * row_stride exceeds 4 GiB per sample");
+    const int64_t tiles = tile_upper_bound(B, H, max_kv_len);
+    if (tiles >= ((int64_t)1 << 31)) return fail(EMS_ERR_UNSUPPORTED, "too many key tiles");
+
+    const int blocks = attn_blocks_for(tiles, resident_attn_blocks());
+    const size_t need = attn_ws_bytes_for(blocks, D);
+    if (!workspace || workspace_bytes < need)
+        return fail(EMS_ERR_WORKSPACE, "attention workspace of %zu bytes needed, %zu given", need,
+                    workspace ? workspace_bytes : (size_t)0);
+    if (!aligned16(workspace)) return fail(EMS_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+
+    ems::AttnParams p;
+    p.q = static_cast<const char*>(q);
+    p.k_new = static_cast<const char*>(k_new);
+    p.v_new = static_cast<const char*>(v_new);
+    p.k_cache = static_cast<const char*>(cache->k);
+    p.v_cache = static_cast<const char*>(cache->v);
+    p.row_stride_b = cache->row_stride * 2;
+    p.head_stride_b = cache->head_stride * 2;
+    p.cu = cu_seqlens;
+    p.kv_start = kv_start;
+    p.kv_len = kv_len;
+    p.out = out;
+    p.ws = static_cast<float*>(workspace);
+    p.out_f32 = out_dtype == EMS_F32;
+    p.B = B;
+    p.H = H;
+    p.num_waves = blocks * kWavesPerBlock;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    hipError_t e = ems::launch_verify_attention(p, blocks, D, dtype == EMS_BF16,
+                                                static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail("ems_verify_attention launch", e);
+    return EMS_OK;
+}
+
+size_t ems_accept_workspace_bytes(int T, int V) {
+    if (T <= 0 || V <= 0) return 0;
+    int slices, len;
+    accept_slicing(T, V, &slices, &len);
+    return (size_t)T * slices * sizeof(ems::ArgmaxPartial);
+}
+
+ems_status ems_greedy_accept(const void* logits, ems_dtype dtype, int V, int32_t* target_ids,
+                             const int32_t* input_ids, const int32_t* cu_seqlens, int B, int T,
+                             int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
+    if (T < 0) return fail(EMS_ERR_INVALID_ARG, "T = %d, need T >= 0", T);
+    if (V < 0) return fail(EMS_ERR_INVALID_ARG, "V = %d, need V >= 0", V);
+    if (B > kMaxB) return fail(EMS_ERR_UNSUPPORTED, "B = %d, at most %d samples", B, kMaxB);
+    if (T > 65535) return fail(EMS_ERR_UNSUPPORTED, "T = %d, at most 65535 packed rows", T);
+    if (!cu_seqlens || !accepted || !accepted_cu)
+        return fail(EMS_ERR_INVALID_ARG, "cu_seqlens, accepted and accepted_cu must not be NULL");
+    if (T > 0 && (!target_ids || !input_ids))
+        return fail(EMS_ERR_INVALID_ARG, "target_ids and input_ids must not be NULL");
+    ems::AcceptParams p;
+    std::memset(&p, 0, sizeof p);
+    if (logits != nullptr) {
+        if (!dtype16(dtype)) return fail(EMS_ERR_INVALID_ARG, "logits dtype must be EMS_F16 or EMS_BF16");
+        if (V < 1) return fail(EMS_ERR_INVALID_ARG, "logits given but V = %d", V);
+        if (!aligned16(logits)) return fail(EMS_ERR_INVALID_ARG, "logits must be 16-byte aligned");
+        accept_slicing(T, V, &p.slices, &p.slice_len);
+        const size_t need = (size_t)T * p.slices * sizeof(ems::ArgmaxPartial);
+        if (T > 0 && (!workspace || workspace_bytes < need))
+            return fail(EMS_ERR_WORKSPACE, "accept workspace of %zu bytes needed, %zu given", need,
+                        workspace ? workspace_bytes : (size_t)0);
+        if (T > 0 && (reinterpret_cast<uintptr_t>(workspace) & 7u))
+            return fail(EMS_ERR_INVALID_ARG, "workspace must be 8-byte aligned");
+    }
+    p.logits = logits;
+    p.bf16 = dtype == EMS_BF16;
+    p.V = V;
+    p.partial = static_cast<ems::ArgmaxPartial*>(workspace);
+    p.target_ids = target_ids;
+    p.input_ids = input_ids;
+    p.cu = cu_seqlens;
+    p.B = B;
+    p.T = T;
+    p.accepted = accepted;
+    p.accepted_cu = accepted_cu;
+    p.out_tokens = out_tokens;
+    hipError_t e = ems::launch_greedy_accept(p, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail("ems_greedy_accept launch", e);
+    return EMS_OK;
+}
+
+ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_new_layers,
+                         const ems_kv_cache* caches, int n_layers, const int32_t* cu_seqlens,
+                         const int32_t* accepted, const int32_t* kv_start, const int32_t* kv_len,
+                         int32_t* kv_len_out, int B, int T, int H, int D, ems_dtype dtype,
+                         void* hip_stream) {
+    if (n_layers < 1) return fail(EMS_ERR_INVALID_ARG, "n_layers = %d, need n_layers >= 1", n_layers);
+    if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
+    if (B > 65535 * 32) return fail(EMS_ERR_UNSUPPORTED, "B = %d is too large", B);
+    if (T < 0) return fail(EMS_ERR_INVALID_ARG, "T = %d, need T >= 0", T);
+    if (H < 1) return fail(EMS_ERR_INVALID_ARG, "H = %d, need H >= 1", H);
+    if (D < 8 || (D & 7)) return fail(EMS_ERR_INVALID_ARG, "D = %d, need a positive multiple of 8", D);
+    if (!dtype16(dtype)) return fail(EMS_ERR_INVALID_ARG, "dtype must be EMS_F16 or EMS_BF16");
+    if (!k_new_layers || !v_new_layers || !caches)
+        return fail(EMS_ERR_INVALID_ARG, "layer arrays must not be NULL");
+    if (!cu_seqlens || !accepted || !kv_start || !kv_len)
+        return fail(EMS_ERR_INVALID_ARG, "cu_seqlens, accepted, kv_start and kv_len must not be NULL");
+    for (int l = 0; l < n_layers; ++l) {
+        const ems_kv_cache& c = caches[l];
+        if (T > 0 && (!k_new_layers[l] || !v_new_layers[l] || !c.k || !c.v))
+            return fail(EMS_ERR_INVALID_ARG, "layer %d: NULL tensor", l);
+        if (!aligned16(k_new_layers[l]) || !aligned16(v_new_layers[l]) || !aligned16(c.k) || !aligned16(c.v))
+            return fail(EMS_ERR_INVALID_ARG, "layer %d: tensors must be 16-byte aligned", l);
+        if (c.row_stride < D || c.head_stride < D || (c.row_stride & 7) || (c.head_stride & 7))
+            return fail(EMS_ERR_INVALID_ARG, "layer %d: cache strides must be multiples of 8 elements and at least D", l);
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (T > 0) {
+        for (int l0 = 0; l0 < n_layers; l0 += ems::kMaxLayersPerLaunch) {
+            ems::AppendParams p;
+            std::memset(&p, 0, sizeof p);
+            p.n_layers = std::min(ems::kMaxLayersPerLaunch, n_layers - l0);
+            for (int l = 0; l < p.n_layers; ++l) {
+                ems::AppendLayer& ly = p.layer[l];
+                ly.k_new = static_cast<const char*>(k_new_layers[l0 + l]);
+                ly.v_new = static_cast<const char*>(v_new_layers[l0 + l]);
+                ly.k_cache = static_cast<char*>(caches[l0 + l].k);
+                ly.v_cache = static_cast<char*>(caches[l0 + l].v);
+                ly.row_stride_b = caches[l0 + l].row_stride * 2;
+                ly.head_stride_b = caches[l0 + l].head_stride * 2;
+            }
+            p.cu = cu_seqlens;
+            p.accepted = accepted;
+            p.kv_start = kv_start;
+            p.kv_len = kv_len;
+            p.B = B;
+            p.H = H;
+            p.vec_per_head = D / 8;
+            hipError_t e = ems::launch_kv_append(p, stream);
+            if (e != hipSuccess) return hip_fail("ems_kv_append launch", e);
+        }
+    }
+    if (kv_len_out != nullptr) {
+        hipError_t e = ems::launch_advance_kv_len(kv_len, accepted, kv_len_out, B, stream);
+        if (e != hipSuccess) return hip_fail("ems_kv_append length update launch", e);
+    }
+    return EMS_OK;
+}
+
+ems_status ems_validate_inputs(const int32_t* cu_seqlens, const int32_t* kv_start,
+                               const int32_t* kv_len, int B, int T, int max_k, int max_kv_len,
+                               int64_t rows, void* hip_stream) {
+    if (B < 1 || T < 0 || max_k < 0 || max_kv_len < 0 || rows < 0)
+        return fail(EMS_ERR_INVALID_ARG, "negative size (B=%d T=%d max_k=%d max_kv_len=%d)", B, T, max_k, max_kv_len);
+    if (!cu_seqlens || !kv_start || !kv_len)
+        return fail(EMS_ERR_INVALID_ARG, "cu_seqlens, kv_start and kv_len must not be NULL");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    std::vector<int32_t> cu(B + 1), ks(B), kl(B);
+    hipError_t e = hipMemcpyAsync(cu.data(), cu_seqlens, sizeof(int32_t) * (B + 1), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(ks.data(), kv_start, sizeof(int32_t) * B, hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(kl.data(), kv_len, sizeof(int32_t) * B, hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return hip_fail("ems_validate_inputs copy", e);
+    if (cu[0] != 0) return fail(EMS_ERR_INVALID_ARG, "cu_seqlens[0] = %d, must be 0", cu[0]);
+    if (cu[B] != T) return fail(EMS_ERR_INVALID_ARG, "cu_seqlens[B] = %d, must equal T = %d", cu[B], T);
+    std::vector<std::pair<int64_t, int64_t>> regions;
+    for (int i = 0; i < B; ++i) {
+        const int k = cu[i + 1] - cu[i];
+        if (k < 0) return fail(EMS_ERR_INVALID_ARG, "cu_seqlens decreases at sample %d", i);
+        if (k > max_k) return fail(EMS_ERR_INVALID_ARG, "sample %d has %d rows, max_k = %d", i, k, max_k);
+        if (kl[i] < 0 || kl[i] > max_kv_len)
+            return fail(EMS_ERR_INVALID_ARG, "kv_len[%d] = %d outside [0, %d]", i, kl[i], max_kv_len);
+        if (ks[i] < 0) return fail(EMS_ERR_INVALID_ARG, "kv_start[%d] = %d is negative", i, ks[i]);
+        if ((int64_t)ks[i] + kl[i] + k > rows)
+            return fail(EMS_ERR_INVALID_ARG, "sample %d: kv_start+kv_len+k = %lld exceeds the arena's %lld rows",
+                        i, (long long)ks[i] + kl[i] + k, (long long)rows);
+        if (kl[i] + k > 0) regions.emplace_back((int64_t)ks[i], (int64_t)ks[i] + kl[i] + k);
+    }
+    std::sort(regions.begin(), regions.end());
+    for (size_t r = 1; r < regions.size(); ++r)
+        if (regions[r].first < regions[r - 1].second)
+            return fail(EMS_ERR_INVALID_ARG, "cache regions overlap near row %lld", (long long)regions[r].first);
+    return EMS_OK;
+}
+
+}  // extern "C"

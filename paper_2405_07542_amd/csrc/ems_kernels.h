@@ -1,0 +1,82 @@
+// Host-visible declarations of the kernel launchers of libems (internal).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ems {
+
+constexpr int kPartialPad = 4;          // floats after the D accumulators: [max, sum, -, -]
+constexpr int kMaxLayersPerLaunch = 32;
+constexpr int kArgmaxThreads = 256;
+constexpr int kAcceptThreads = 1024;
+
+struct AttnParams {
+    const char* q;
+    const char* k_new;
+    const char* v_new;
+    const char* k_cache;
+    const char* v_cache;
+    int64_t row_stride_b;      // bytes
+    int64_t head_stride_b;     // bytes
+    const int32_t* cu;
+    const int32_t* kv_start;
+    const int32_t* kv_len;
+    void* out;
+    float* ws;                 // 2 * num_waves partial slots of 16 x (D + kPartialPad) floats
+    int out_f32;
+    int B, H;
+    int num_waves;
+    float scale_log2;          // scale * log2(e)
+};
+
+hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16,
+                                   hipStream_t stream);
+
+struct ArgmaxPartial {
+    float value;
+    int32_t index;
+};
+
+struct AcceptParams {
+    const void* logits;        // [T, V] or nullptr
+    int bf16;
+    int V;
+    int slices;                // row slices of the first pass
+    int slice_len;             // columns per slice (multiple of 8)
+    ArgmaxPartial* partial;    // [T, slices]
+    int32_t* target_ids;
+    const int32_t* input_ids;
+    const int32_t* cu;
+    int B, T;
+    int32_t* accepted;
+    int32_t* accepted_cu;
+    int32_t* out_tokens;       // may be nullptr
+};
+
+hipError_t launch_greedy_accept(const AcceptParams& p, hipStream_t stream);
+
+struct AppendLayer {
+    const char* k_new;
+    const char* v_new;
+    char* k_cache;
+    char* v_cache;
+    int64_t row_stride_b;
+    int64_t head_stride_b;
+};
+
+struct AppendParams {
+    AppendLayer layer[kMaxLayersPerLaunch];
+    int n_layers;
+    const int32_t* cu;
+    const int32_t* accepted;
+    const int32_t* kv_start;
+    const int32_t* kv_len;
+    int B, H;
+    int vec_per_head;          // D * 2 / 16
+};
+
+hipError_t launch_kv_append(const AppendParams& p, hipStream_t stream);
+hipError_t launch_advance_kv_len(const int32_t* kv_len, const int32_t* accepted,
+                                 int32_t* kv_len_out, int B, hipStream_t stream);
+
+}  // namespace ems

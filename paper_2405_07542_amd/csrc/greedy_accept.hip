@@ -1,0 +1,167 @@
+// Greedy acceptance (EMS-SD Appendix A): greedy target token = arg-max of the
+// target distribution for each packed row; acceptance length of a sample = 1 +
+// the number of leading drafts equal to the target token of the row before
+// them; then the running sum of the lengths and the packed accepted tokens.
+//
+// Two launches on the caller's stream:
+//   1. argmax_partial_kernel  grid (slices, T): each block scans one slice of one
+//      logits row with 16-byte loads and keeps (value, lowest index);
+//   2. accept_scan_kernel     one block: finishes the arg-max per row, one wave per
+//      sample compares drafts with targets (ballot + count of leading matches),
+//      block-wide exclusive scan of the lengths, packed copy of accepted tokens.
+// Comparisons are on exactly widened values, so results are bit-exact; ties go
+// to the lowest index at every merge level.
+#include "ems_device.h"
+#include "ems_kernels.h"
+
+namespace ems {
+
+__device__ __forceinline__ void take_better(float& v, int32_t& idx, float ov, int32_t oi) {
+    if (ov > v || (ov == v && oi < idx)) {
+        v = ov;
+        idx = oi;
+    }
+}
+
+template <typename ET>
+__global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptParams p) {
+    const int row = blockIdx.y, sl = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int c0 = sl * p.slice_len;
+    const int c1 = min(p.V, c0 + p.slice_len);
+    const uint16_t* base = reinterpret_cast<const uint16_t*>(p.logits) + (int64_t)row * p.V;
+    // every thread starts from the slice's first element, so ties resolve to it
+    float best = widen(ET{}, base[c0]);
+    int32_t arg = c0;
+    if ((p.V & 7) == 0) {
+        const u32x4* vec = reinterpret_cast<const u32x4*>(base);
+        for (int v = (c0 >> 3) + tid; v < (c1 >> 3); v += kArgmaxThreads) {
+            const u32x4 w = vec[v];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint16_t bits = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+                const float y = widen(ET{}, bits);
+                if (y > best) {            // strict: the earlier index of this thread stays
+                    best = y;
+                    arg = v * 8 + e;
+                }
+            }
+        }
+    } else {
+        for (int c = c0 + tid; c < c1; c += kArgmaxThreads) {
+            const float y = widen(ET{}, base[c]);
+            if (y > best) {
+                best = y;
+                arg = c;
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1)
+        take_better(best, arg, __shfl_xor(best, off), __shfl_xor(arg, off));
+    __shared__ float sv[kArgmaxThreads / kWave];
+    __shared__ int32_t si[kArgmaxThreads / kWave];
+    if ((tid & 63) == 0) {
+        sv[tid >> 6] = best;
+        si[tid >> 6] = arg;
+    }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < kArgmaxThreads / kWave; ++w) take_better(best, arg, sv[w], si[w]);
+        ArgmaxPartial out;
+        out.value = best;
+        out.index = arg;
+        p.partial[(int64_t)row * p.slices + sl] = out;
+    }
+}
+
+constexpr int kMaxAcceptB = 8192;
+
+__global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParams p) {
+    __shared__ int32_t acc_s[kMaxAcceptB];
+    __shared__ int32_t wave_tot[kAcceptThreads / kWave];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wid = tid >> 6;
+
+    if (p.logits != nullptr) {
+        for (int r = tid; r < p.T; r += kAcceptThreads) {
+            const ArgmaxPartial* part = p.partial + (int64_t)r * p.slices;
+            float best = part[0].value;
+            int32_t arg = part[0].index;
+            for (int s = 1; s < p.slices; ++s) take_better(best, arg, part[s].value, part[s].index);
+            p.target_ids[r] = arg;
+        }
+        __threadfence_block();
+        __syncthreads();
+    }
+
+    // one wave per sample: count the leading drafts that match the target's tokens
+    for (int i = wid; i < p.B; i += kAcceptThreads / kWave) {
+        const int base = p.cu[i];
+        const int k = p.cu[i + 1] - base;
+        int m = 0;
+        for (int c0 = 0; c0 < k - 1; c0 += kWave) {
+            const int j = c0 + lane;
+            const bool match = (j < k - 1) && (p.target_ids[base + j] == p.input_ids[base + j + 1]);
+            const uint64_t miss = ~__builtin_amdgcn_ballot_w64(match);
+            if (miss != 0) {
+                m += __builtin_ctzll(miss);
+                break;
+            }
+            m += kWave;
+        }
+        if (lane == 0) {
+            const int a = k > 0 ? m + 1 : 0;
+            acc_s[i] = a;
+            p.accepted[i] = a;
+        }
+    }
+    __syncthreads();
+
+    // exclusive scan of accepted[] over the block: each thread owns a run of samples
+    const int chunk = (p.B + kAcceptThreads - 1) / kAcceptThreads;
+    const int first = tid * chunk;
+    int mine = 0;
+    for (int c = 0; c < chunk; ++c)
+        if (first + c < p.B) mine += acc_s[first + c];
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int u = __shfl_up(incl, off);
+        if (lane >= off) incl += u;
+    }
+    if (lane == kWave - 1) wave_tot[wid] = incl;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wid; ++w) before += wave_tot[w];
+    int run = before + incl - mine;            // exclusive prefix of this thread's first sample
+    for (int c = 0; c < chunk; ++c) {
+        const int i = first + c;
+        if (i >= p.B) break;
+        const int a = acc_s[i];
+        p.accepted_cu[i] = run;
+        if (p.out_tokens != nullptr) {
+            const int base = p.cu[i];
+            for (int j = 0; j < a; ++j) p.out_tokens[run + j] = p.target_ids[base + j];
+        }
+        run += a;
+        if (i == p.B - 1) p.accepted_cu[p.B] = run;
+    }
+}
+
+hipError_t launch_greedy_accept(const AcceptParams& p, hipStream_t stream) {
+    if (p.logits != nullptr && p.T > 0) {
+        dim3 grid(p.slices, p.T);
+        if (p.bf16)
+            hipLaunchKernelGGL(argmax_partial_kernel<BF16>, grid, dim3(kArgmaxThreads), 0, stream, p);
+        else
+            hipLaunchKernelGGL(argmax_partial_kernel<F16>, grid, dim3(kArgmaxThreads), 0, stream, p);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(accept_scan_kernel, dim3(1), dim3(kAcceptThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace ems

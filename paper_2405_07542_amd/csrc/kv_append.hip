@@ -1,0 +1,57 @@
+// KV-cache append (EMS-SD Sec. 3.2 "Unpad KV cache"): after verification each
+// sample's cache grows by exactly its own accepted count; the accepted rows are
+// copied from the packed new K/V to the sample's own write location, so no
+// padding row is ever written and every cache stays contiguous.
+//
+// Grid (B, 2 * n_layers): one block copies the accepted rows of one sample for
+// one layer's K or V with 16-byte loads and stores.  The per-sample lengths are
+// advanced by a second, tiny launch so that kv_len_out may alias kv_len.
+#include "ems_device.h"
+#include "ems_kernels.h"
+
+namespace ems {
+
+constexpr int kAppendThreads = 256;
+
+__global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(AppendParams p) {
+    const int i = blockIdx.x;
+    // never more than the sample brought (accepted[i] <= k_i is the caller's contract)
+    const int a = min(p.accepted[i], p.cu[i + 1] - p.cu[i]);
+    if (a <= 0) return;
+    const AppendLayer& ly = p.layer[blockIdx.y >> 1];
+    const bool is_v = blockIdx.y & 1;
+    const int vph = p.vec_per_head;
+    const int64_t row_vecs = (int64_t)p.H * vph;
+    const char* src = (is_v ? ly.v_new : ly.k_new) + (int64_t)p.cu[i] * row_vecs * 16;
+    char* dst = (is_v ? ly.v_cache : ly.k_cache) +
+                ((int64_t)p.kv_start[i] + p.kv_len[i]) * ly.row_stride_b;
+    const int64_t nvec = (int64_t)a * row_vecs;
+    for (int64_t v = threadIdx.x; v < nvec; v += kAppendThreads) {
+        const int64_t j = v / row_vecs;
+        const int rem = (int)(v - j * row_vecs);
+        const int h = rem / vph;
+        const int c = rem - h * vph;
+        const u32x4 w = *reinterpret_cast<const u32x4*>(src + v * 16);
+        *reinterpret_cast<u32x4*>(dst + j * ly.row_stride_b + (int64_t)h * ly.head_stride_b + c * 16) = w;
+    }
+}
+
+__global__ void advance_kv_len_kernel(const int32_t* kv_len, const int32_t* accepted,
+                                      int32_t* kv_len_out, int B) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B) kv_len_out[i] = kv_len[i] + accepted[i];
+}
+
+hipError_t launch_kv_append(const AppendParams& p, hipStream_t stream) {
+    hipLaunchKernelGGL(kv_append_kernel, dim3(p.B, 2 * p.n_layers), dim3(kAppendThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_advance_kv_len(const int32_t* kv_len, const int32_t* accepted,
+                                 int32_t* kv_len_out, int B, hipStream_t stream) {
+    hipLaunchKernelGGL(advance_kv_len_kernel, dim3((B + 255) / 256), dim3(256), 0, stream, kv_len,
+                       accepted, kv_len_out, B);
+    return hipGetLastError();
+}
+
+}  // namespace ems

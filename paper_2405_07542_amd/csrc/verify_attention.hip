@@ -1,0 +1,391 @@
+// Packed multi-token attention over per-sample KV caches (EMS-SD Sec. 3.2:
+// "Unpad KV cache" -- every sample has its own cache start location -- and
+// "Unpad input tokens" -- the inputs of all samples are concatenated, and the
+// kernel recovers which sample and position a packed row belongs to, Alg. 2).
+//
+// Design for gfx950 (differs from the paper's one-thread-block-per-token grid,
+// Appendix D Eq. 12, which re-streams a sample's cache once per query row):
+//   * work is measured in tiles of 32 keys; a (sample, head) pair owns
+//     ceil(kv_len/32) cache tiles plus one tile holding its new tokens;
+//   * the tiles of all pairs are laid on one line and cut into equal ranges,
+//     one per wave, so ragged lengths are balanced without any host knowledge
+//     of kv_len[] (the per-sample tile counts are prefix-summed in LDS);
+//   * a wave keeps all k_i <= 16 query rows of its pair in registers as an
+//     MFMA operand, so each K/V byte is fetched from HBM exactly once and is
+//     shared by all query rows;
+//   * S^T = K Q^T and O^T = V^T P^T run on v_mfma_f32_16x16x32_{f16,bf16}:
+//     K rows are loaded straight into the A-operand layout (64-byte pieces),
+//     V rows are loaded fully coalesced (one row = 16 lanes x 16 B) and
+//     transposed in registers with v_perm_b32; the S^T accumulator layout is
+//     already the B-operand layout of the second product, so P never moves
+//     between lanes;
+//   * online softmax in the log2 domain; the row maximum is shared by the four
+//     lanes that hold one query row via two cross-lane shuffles per tile;
+//   * a range that covers only part of a pair writes an fp32 partial
+//     (accumulator, running max, running sum); a second small kernel merges
+//     the partials of such pairs by log-sum-exp.
+#include "ems_device.h"
+#include "ems_kernels.h"
+
+namespace ems {
+
+constexpr int kTileKeys = 32;
+constexpr int kAttnThreads = 256;
+constexpr int kWavesPerBlock = kAttnThreads / kWave;
+
+__device__ __forceinline__ int tiles_of_sample(int k, int L) {
+    return k > 0 ? ((L + kTileKeys - 1) / kTileKeys + 1) : 0;
+}
+
+// prefix[i] = H * sum_{j<i} tiles(j), i = 0..B, built by the whole block in LDS.
+__device__ __forceinline__ void build_tile_prefix(const AttnParams& p, int32_t* prefix) {
+    const int tid = threadIdx.x;
+    for (int i = tid; i < p.B; i += blockDim.x)
+        prefix[i + 1] = p.H * tiles_of_sample(p.cu[i + 1] - p.cu[i], p.kv_len[i]);
+    if (tid == 0) prefix[0] = 0;
+    __syncthreads();
+    if (tid < kWave) {                        // one wave: inclusive scan, 64 entries a pass
+        int carry = 0;
+        for (int base = 1; base <= p.B; base += kWave) {
+            const int idx = base + tid;
+            int v = idx <= p.B ? prefix[idx] : 0;
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                int u = __shfl_up(v, off);
+                if (tid >= off) v += u;
+            }
+            if (idx <= p.B) prefix[idx] = v + carry;
+            carry += __shfl(v, kWave - 1);
+        }
+    }
+    __syncthreads();
+}
+
+template <int D>
+struct TileRegs {
+    static constexpr int KS = D / 32;        // MFMA k-steps over the head dim
+    static constexpr int VW = D / 16;        // head-dim elements per lane per V row
+    typedef uint32_t vrow_t __attribute__((ext_vector_type(VW / 2)));
+    u32x4 ka[KS], kb[KS];                    // keys 0..15 / 16..31 of the tile, A-operand layout
+    vrow_t v[8];                             // this lane's 8 keys x VW head-dim elements
+};
+
+// Issue the loads of one tile.  kbase/vbase point at (first row of the run, head h);
+// rows are clamped to `last` so that masked keys still read valid, finite data.
+template <int D>
+__device__ __forceinline__ void load_tile(TileRegs<D>& t, const char* kbase, const char* vbase,
+                                          uint32_t row_bytes, int n0, int last, int n, int g) {
+    constexpr int KS = TileRegs<D>::KS;
+    constexpr int VW = TileRegs<D>::VW;
+    const uint32_t ra = (uint32_t)min(n0 + n, last) * row_bytes + (uint32_t)g * 16u;
+    const uint32_t rb = (uint32_t)min(n0 + 16 + n, last) * row_bytes + (uint32_t)g * 16u;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        t.ka[s] = *reinterpret_cast<const u32x4*>(kbase + ra + 64 * s);
+        t.kb[s] = *reinterpret_cast<const u32x4*>(kbase + rb + 64 * s);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int key = n0 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
+        const uint32_t off = (uint32_t)min(key, last) * row_bytes + (uint32_t)n * (VW * 2);
+        t.v[e] = *reinterpret_cast<const typename TileRegs<D>::vrow_t*>(vbase + off);
+    }
+}
+
+template <typename ET> struct PSplit { static constexpr bool value = false; };
+template <> struct PSplit<BF16> { static constexpr bool value = true; };
+
+template <typename ET, int D>
+struct SoftmaxState {
+    static constexpr int VW = D / 16;
+    f32x4 acc[VW];     // acc[c][i] = O[query n][d = (4g+i)*VW + c], unnormalised
+    float m;           // running max (log2 domain), same in the 4 lanes of a query
+    float l;           // this lane's share of the running sum
+};
+
+// One tile: scores, masked online softmax, PV.  `lim` = number of visible keys
+// of this tile for this lane's query row (>= 32 means no masking).
+template <typename ET, int D, bool MASKED>
+__device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* qb,
+                                             SoftmaxState<ET, D>& st, float scale_log2, int lim,
+                                             int g) {
+    constexpr int KS = TileRegs<D>::KS;
+    constexpr int VW = TileRegs<D>::VW;
+    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        sa = mfma16x16x32(ET{}, t.ka[s], qb[s], sa);
+        sb = mfma16x16x32(ET{}, t.kb[s], qb[s], sb);
+    }
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[i] = sa[i] * scale_log2;
+        x[4 + i] = sb[i] * scale_log2;
+        if (MASKED) {
+            if (4 * g + i >= lim) x[i] = -INFINITY;
+            if (16 + 4 * g + i >= lim) x[4 + i] = -INFINITY;
+        }
+    }
+    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                     fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(st.m, mx);
+    // every tile holds at least one visible key for every row, so m_new is finite
+    const float alpha = fast_exp2(st.m - m_new);     // exp2(-inf) = 0 on the first tile
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        x[i] = fast_exp2(x[i] - m_new);
+        psum += x[i];
+    }
+    st.l = st.l * alpha + psum;
+    st.m = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+        for (int c = 0; c < VW; ++c) st.acc[c] *= alpha;
+    }
+    // P^T as the B operand: slot e of this lane = key (e<4 ? 4g+e : 16+4g+e-4).
+    // bf16 keeps 8 significant bits, too few for P when a row has only a handful of
+    // keys; there P is fed as hi + lo (two products), which restores ~16 bits.
+    constexpr bool kSplitP = PSplit<ET>::value;
+    u32x4 pb, pl;
+    pb[0] = pack2(ET{}, x[0], x[1]);
+    pb[1] = pack2(ET{}, x[2], x[3]);
+    pb[2] = pack2(ET{}, x[4], x[5]);
+    pb[3] = pack2(ET{}, x[6], x[7]);
+    if (kSplitP) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] -= round16(ET{}, x[i]);
+        pl[0] = pack2(ET{}, x[0], x[1]);
+        pl[1] = pack2(ET{}, x[2], x[3]);
+        pl[2] = pack2(ET{}, x[4], x[5]);
+        pl[3] = pack2(ET{}, x[6], x[7]);
+    }
+    // V^T as the A operand: for head-dim element c of this lane, the 8 keys' values.
+#pragma unroll
+    for (int c = 0; c < VW; ++c) {
+        u32x4 va;
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) {
+            const uint32_t w0 = t.v[2 * pr][c >> 1];
+            const uint32_t w1 = t.v[2 * pr + 1][c >> 1];
+            va[pr] = (c & 1) ? pair_hi(w0, w1) : pair_lo(w0, w1);
+        }
+        st.acc[c] = mfma16x16x32(ET{}, va, pb, st.acc[c]);
+        if (kSplitP) st.acc[c] = mfma16x16x32(ET{}, va, pl, st.acc[c]);
+    }
+}
+
+template <typename ET, int D>
+__global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnParams p) {
+    extern __shared__ int32_t prefix[];
+    constexpr int KS = TileRegs<D>::KS;
+    constexpr int VW = TileRegs<D>::VW;
+    build_tile_prefix(p, prefix);
+    const int total = prefix[p.B];
+    const int per = (total + p.num_waves - 1) / p.num_waves;
+    const int wave = uniform((int)(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)));
+    int gpos = wave * per;
+    const int gend = min(total, gpos + per);
+    if (gpos >= gend) return;
+
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15;       // query row (MFMA column) of this lane
+    const int g = lane >> 4;       // which quarter of the k-slots / key rows
+
+    // sample of the first tile: prefix[i] <= gpos < prefix[i+1]
+    int lo = 0, hi = p.B;          // invariant: prefix[lo] <= gpos < prefix[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (prefix[mid] <= gpos) lo = mid; else hi = mid;
+    }
+    int i = lo;
+
+    while (gpos < gend) {
+        while (prefix[i + 1] <= gpos) ++i;
+        const int cu_i = uniform(p.cu[i]);
+        const int k = uniform(p.cu[i + 1]) - cu_i;
+        const int L = uniform(p.kv_len[i]);
+        const int64_t start = uniform(p.kv_start[i]);
+        const int ntc = (L + kTileKeys - 1) / kTileKeys;
+        const int nt = ntc + 1;
+        const int rem = gpos - prefix[i];
+        const int h = rem / nt;
+        const int t0 = rem - h * nt;
+        const int t1 = min(nt, t0 + (gend - gpos));
+
+        const int64_t cache_off = start * p.row_stride_b + (int64_t)h * p.head_stride_b;
+        const char* kc = uniform_ptr(p.k_cache + cache_off);
+        const char* vc = uniform_ptr(p.v_cache + cache_off);
+        const int64_t new_off = ((int64_t)cu_i * p.H + h) * (D * 2);
+        const char* kn = uniform_ptr(p.k_new + new_off);
+        const char* vn = uniform_ptr(p.v_new + new_off);
+        const uint32_t new_row_bytes = (uint32_t)p.H * (D * 2);
+        const uint32_t cache_row_bytes = (uint32_t)p.row_stride_b;
+
+        // Q^T as the B operand of S^T = K Q^T; rows beyond k_i are zero.
+        u32x4 qb[KS];
+        {
+            const char* qrow = p.q + new_off + (int64_t)n * new_row_bytes + g * 16;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                u32x4 z = {0u, 0u, 0u, 0u};
+                qb[s] = n < k ? *reinterpret_cast<const u32x4*>(qrow + 64 * s) : z;
+            }
+        }
+        SoftmaxState<ET, D> st;
+#pragma unroll
+        for (int c = 0; c < VW; ++c) st.acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+        st.m = -INFINITY;
+        st.l = 0.f;
+
+        // visible keys of the new-token tile for this lane's row: itself and the rows before it
+        const int lim_new = min(k, n + 1);
+
+        auto issue = [&](TileRegs<D>& t, int tile) {
+            if (tile < ntc)
+                load_tile<D>(t, kc, vc, cache_row_bytes, tile * kTileKeys, L - 1, n, g);
+            else
+                load_tile<D>(t, kn, vn, new_row_bytes, 0, k - 1, n, g);
+        };
+        auto consume = [&](const TileRegs<D>& t, int tile) {
+            if (tile < ntc) {
+                const int lim = L - tile * kTileKeys;
+                if (lim >= kTileKeys)
+                    compute_tile<ET, D, false>(t, qb, st, p.scale_log2, lim, g);
+                else
+                    compute_tile<ET, D, true>(t, qb, st, p.scale_log2, lim, g);
+            } else {
+                compute_tile<ET, D, true>(t, qb, st, p.scale_log2, lim_new, g);
+            }
+        };
+
+        TileRegs<D> ta, tb;
+        issue(ta, t0);
+        for (int t = t0; t < t1; t += 2) {
+            if (t + 1 < t1) issue(tb, t + 1);
+            consume(ta, t);
+            if (t + 1 < t1) {
+                if (t + 2 < t1) issue(ta, t + 2);
+                consume(tb, t + 1);
+            }
+        }
+
+        // the four lanes of a query row hold disjoint shares of the sum
+        float l = st.l;
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+
+        if (t0 == 0 && t1 == nt) {
+            if (n < k) {
+                const float inv = 1.0f / l;
+                const int64_t row = ((int64_t)(cu_i + n) * p.H + h) * D;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int d0 = (4 * g + r) * VW;
+                    float o[VW];
+#pragma unroll
+                    for (int c = 0; c < VW; ++c) o[c] = st.acc[c][r] * inv;
+                    if (p.out_f32) {
+                        float* dst = reinterpret_cast<float*>(p.out) + row + d0;
+#pragma unroll
+                        for (int c = 0; c < VW; c += 4)
+                            *reinterpret_cast<f32x4*>(dst + c) = f32x4{o[c], o[c + 1], o[c + 2], o[c + 3]};
+                    } else {
+                        uint16_t* dst = reinterpret_cast<uint16_t*>(p.out) + row + d0;
+                        typename TileRegs<D>::vrow_t pk;
+#pragma unroll
+                        for (int c = 0; c < VW; c += 2) pk[c >> 1] = pack2(ET{}, o[c], o[c + 1]);
+                        *reinterpret_cast<typename TileRegs<D>::vrow_t*>(dst) = pk;
+                    }
+                }
+            }
+        } else {
+            // partial: slot 2w holds a range that continues a pair begun by an earlier
+            // wave, slot 2w+1 one that starts a pair and leaves its end to later waves
+            const int slot = 2 * wave + (t0 == 0 ? 1 : 0);
+            if (n < k) {
+                float* dst = p.ws + ((int64_t)slot * 16 + n) * (D + kPartialPad);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int d0 = (4 * g + r) * VW;
+#pragma unroll
+                    for (int c = 0; c < VW; c += 4)
+                        *reinterpret_cast<f32x4*>(dst + d0 + c) =
+                            f32x4{st.acc[c][r], st.acc[c + 1][r], st.acc[c + 2][r], st.acc[c + 3][r]};
+                }
+                if (g == 0) {
+                    dst[D] = st.m;
+                    dst[D + 1] = l;
+                }
+            }
+        }
+        gpos += t1 - t0;
+    }
+}
+
+// Merge the partials of every (sample, head) pair whose tiles were shared by
+// several waves.  Grid (H, B), D threads: thread d owns one output column.
+template <typename ET, int D>
+__global__ __launch_bounds__(D) void combine_partials_kernel(AttnParams p) {
+    extern __shared__ int32_t prefix[];
+    build_tile_prefix(p, prefix);
+    const int total = prefix[p.B];
+    const int per = (total + p.num_waves - 1) / p.num_waves;
+    const int i = blockIdx.y, h = blockIdx.x;
+    const int cu_i = p.cu[i];
+    const int k = p.cu[i + 1] - cu_i;
+    if (k <= 0) return;
+    const int nt = tiles_of_sample(k, p.kv_len[i]);
+    const int g0 = prefix[i] + h * nt;
+    const int w0 = g0 / per, w1 = (g0 + nt - 1) / per;
+    if (w0 == w1) return;                  // one wave saw the whole pair and wrote `out` itself
+    const int d = threadIdx.x;
+    constexpr int pitch = D + kPartialPad;
+    for (int j = 0; j < k; ++j) {
+        float M = -INFINITY;
+        for (int w = w0; w <= w1; ++w) {
+            const int slot = 2 * w + (w == w0 ? 1 : 0);
+            M = fmaxf(M, p.ws[((int64_t)slot * 16 + j) * pitch + D]);
+        }
+        float num = 0.f, den = 0.f;
+        for (int w = w0; w <= w1; ++w) {
+            const int slot = 2 * w + (w == w0 ? 1 : 0);
+            const float* src = p.ws + ((int64_t)slot * 16 + j) * pitch;
+            const float wgt = fast_exp2(src[D] - M);
+            num += wgt * src[d];
+            den += wgt * src[D + 1];
+        }
+        const float o = num / den;
+        const int64_t idx = ((int64_t)(cu_i + j) * p.H + h) * D + d;
+        if (p.out_f32) {
+            reinterpret_cast<float*>(p.out)[idx] = o;
+        } else {
+            const uint32_t pk = pack2(ET{}, o, 0.f);
+            reinterpret_cast<uint16_t*>(p.out)[idx] = (uint16_t)(pk & 0xffffu);
+        }
+    }
+}
+
+template <typename ET, int D>
+static hipError_t launch_typed(const AttnParams& p, int blocks, hipStream_t stream) {
+    const size_t lds = (size_t)(p.B + 1) * sizeof(int32_t);
+    hipLaunchKernelGGL((verify_attention_kernel<ET, D>), dim3(blocks), dim3(kAttnThreads), lds,
+                       stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((combine_partials_kernel<ET, D>), dim3(p.H, p.B), dim3(D), lds, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16,
+                                   hipStream_t stream) {
+    if (D == 128) return bf16 ? launch_typed<BF16, 128>(p, blocks, stream)
+                              : launch_typed<F16, 128>(p, blocks, stream);
+    return bf16 ? launch_typed<BF16, 64>(p, blocks, stream)
+                : launch_typed<F16, 64>(p, blocks, stream);
+}
+
+}  // namespace ems

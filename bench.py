@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the ragged verification step (EMS-SD hot path) on one MI355X.
+
+A step = one pass of the whole path over one synthetic batch that is already
+resident in HBM:  ems_verify_attention (one OPT-6.7b-shaped layer) ->
+ems_greedy_accept (arg-max over [T, 50272] logits, acceptance, prefix sum) ->
+ems_kv_append (accepted rows into the per-sample caches).
+
+Prints ONE JSON line: verified tokens/s (sum of accepted tokens / step time), the
+roofline figures of the dominant kernel (the main attention kernel, timed with HIP
+events recorded around it on its own stream inside the timed region) and the
+oracle's throughput on the host cores as a CPU baseline.
+
+    python bench.py [--steps K] [--warmup W] [--config 2|3|4|5] [--layout token_major|head_major]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", type=int, default=4, help="BASELINE config number (2..5)")
+    ap.add_argument("--layout", default="token_major", choices=["token_major", "head_major"])
+    ap.add_argument("--sets", type=int, default=3,
+                    help="independent buffer sets rotated between steps (cold last-level cache)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-logits", action="store_true", help="skip the [T,V] arg-max (ids given)")
+    ap.add_argument("--breakdown", action="store_true", help="also time each call on its own")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="instead of the bench: run a plain device copy of MIB MiB five times "
+                         "(the known-size kernel that scales rocprofv3's FETCH_SIZE/WRITE_SIZE)")
+    return ap.parse_args()
+
+
+def attention_algorithmic_bytes(b, out_elem_bytes):
+    """What the method itself must move per layer: each cached K/V row once, the new
+    K/V rows, Q and O once, and the index arrays."""
+    e = 2
+    kv_len = b.kv_len.cpu().tolist()
+    k = (b.cu_seqlens[1:] - b.cu_seqlens[:-1]).cpu().tolist()
+    hd = b.H * b.D
+    total = 0
+    for L, kk in zip(kv_len, k):
+        if kk == 0:
+            continue
+        total += 2 * L * hd * e + 2 * kk * hd * e + kk * hd * e + kk * hd * out_elem_bytes
+    return total + (3 * b.B + 1) * 4
+
+
+def read_traffic(workload_key):
+    """HBM bytes per launch of the main attention kernel from a committed rocprofv3 --pmc
+    summary (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel), if one exists."""
+    path = os.path.join(ROOT, "profiles", "verify_attention_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == workload_key:
+            try:
+                return float(parts[1])
+            except ValueError:
+                return None
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (--gpus 1); "
+              "the path shards by sample or by head without collectives, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2405_07542_amd as ems
+    from workloads import make_config, CONFIG_NAMES
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    ems.lib()     # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    if args.copy_calibration > 0:
+        src = torch.ones(args.copy_calibration << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": src.numel(), "launches": 5}))
+        return
+    n = args.config
+    with_logits = not args.no_logits
+
+    sets = []
+    for v in range(args.sets):
+        b = make_config(n, device=dev, layout=args.layout, with_logits=with_logits, variant=v)
+        ws_attn = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len),
+                              dtype=torch.uint8, device=dev)
+        ws_acc = torch.empty(max(8, ems.ems_accept_workspace_bytes(b.T, b.V)), dtype=torch.uint8, device=dev)
+        st = dict(
+            b=b, ws_attn=ws_attn, ws_acc=ws_acc,
+            cache=ems.kv_cache(b.k_cache, b.v_cache, b.row_stride, b.head_stride, b.rows),
+            out=torch.empty((b.T, b.H, b.D), dtype=b.dtype, device=dev),
+            target=torch.empty(b.T, dtype=torch.int32, device=dev) if with_logits else b.target_ids.clone(),
+            accepted=torch.empty(b.B, dtype=torch.int32, device=dev),
+            accepted_cu=torch.empty(b.B + 1, dtype=torch.int32, device=dev),
+            out_tokens=torch.empty(b.T, dtype=torch.int32, device=dev),
+            # the lengths are NOT advanced between timed steps, so every step does the same work
+            new_len=torch.empty(b.B, dtype=torch.int32, device=dev))
+        sets.append(st)
+    torch.cuda.synchronize()
+
+    def attention(st):
+        b = st["b"]
+        ems.ems_verify_attention(b.q, b.k_new, b.v_new, st["cache"], b.cu_seqlens, b.kv_start, b.kv_len,
+                                 st["out"], max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale,
+                                 workspace=st["ws_attn"])
+
+    def accept(st):
+        b = st["b"]
+        ems.ems_greedy_accept(b.logits if with_logits else None, st["target"], b.input_ids, b.cu_seqlens,
+                              st["accepted"], st["accepted_cu"], st["out_tokens"], workspace=st["ws_acc"])
+
+    def append(st):
+        b = st["b"]
+        ems.ems_kv_append([b.k_new], [b.v_new], [st["cache"]], b.cu_seqlens, st["accepted"], b.kv_start,
+                          b.kv_len, st["new_len"])
+
+    def step(st):
+        attention(st)
+        accept(st)
+        append(st)
+
+    for w in range(args.warmup):
+        step(sets[w % len(sets)])
+    torch.cuda.synchronize()
+
+    ems.ems_profile_enable(args.steps)
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(sets[s % len(sets)])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    attn_ms_total, attn_launches = ems.ems_profile_read()
+    ems.ems_profile_enable(0)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    accepted_per_step = float(np.mean([int(st["accepted_cu"][-1]) for st in sets]))
+    rows_per_step = float(np.mean([st["b"].T for st in sets]))
+    value = accepted_per_step / (ms_per_step * 1e-3)
+
+    out_bytes = 2
+    alg_bytes = float(np.mean([attention_algorithmic_bytes(st["b"], out_bytes) for st in sets]))
+    attn_ms = attn_ms_total / max(1, attn_launches)
+    achieved = alg_bytes / (attn_ms * 1e-3) / 1e9
+    workload_key = "config%d_%s" % (n, args.layout)
+    roofline = {
+        "bound": "hbm", "kernel": "verify_attention_kernel", "achieved": round(achieved, 1),
+        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": read_traffic(workload_key),
+        "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": round(attn_ms, 5),
+        "launches_timed": attn_launches,
+    }
+
+    result = {
+        "metric": "verified tokens/s (attention + greedy accept + KV append, 1 layer)",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if sets[0]["b"].dtype == torch.bfloat16 else "f16", "data": "synthetic",
+        "config": {"workload": "BASELINE config %d: %s" % (n, CONFIG_NAMES[n]), "layout": args.layout,
+                   "B": sets[0]["b"].B, "H": sets[0]["b"].H, "D": sets[0]["b"].D,
+                   "query_rows_per_step": rows_per_step, "accepted_per_step": accepted_per_step,
+                   "logits": with_logits, "buffer_sets": len(sets)},
+        "query_tokens_per_s": round(rows_per_step / (ms_per_step * 1e-3), 1),
+        "roofline": roofline,
+    }
+
+    if args.breakdown:
+        def time_call(fn, reps=100):
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for r in range(5):
+                fn(sets[r % len(sets)])
+            torch.cuda.synchronize()
+            ev0.record()
+            for r in range(reps):
+                fn(sets[r % len(sets)])
+            ev1.record()
+            torch.cuda.synchronize()
+            return ev0.elapsed_time(ev1) / reps
+        result["breakdown_ms"] = {"attention_call": round(time_call(attention), 5),
+                                  "accept_call": round(time_call(accept), 5),
+                                  "append_call": round(time_call(append), 5)}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(sets[0]["b"], with_logits)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(b, with_logits, budget_s=15.0):
+    """The oracle, as it stands, on the host cores, over the first samples of the batch."""
+    import numpy as np
+    import oracle
+    from workloads import bits
+    cu = b.cu_seqlens.cpu().numpy()
+    ks = b.kv_start.cpu().numpy()
+    kl = b.kv_len.cpu().numpy()
+    # token-major view of the sampled caches only (the arena may be tens of GB)
+    def run(ns):
+        rows = int(cu[ns])
+        if rows == 0:
+            return 0.0, 0
+        from workloads import arena_view
+        Kv = arena_view(b.k_cache, b.layout, b.rows, b.H, b.D)
+        Vv = arena_view(b.v_cache, b.layout, b.rows, b.H, b.D)
+        cap = int(max(kl[:ns])) + 16
+        kc = np.zeros((ns * cap, b.H, b.D), dtype=np.uint16)
+        vc = np.zeros((ns * cap, b.H, b.D), dtype=np.uint16)
+        for i in range(ns):
+            kc[i * cap:i * cap + kl[i]] = bits(Kv[ks[i]:ks[i] + kl[i]])
+            vc[i * cap:i * cap + kl[i]] = bits(Vv[ks[i]:ks[i] + kl[i]])
+        starts = (np.arange(ns) * cap).astype(np.int32)
+        q, kn, vn = bits(b.q[:rows]), bits(b.k_new[:rows]), bits(b.v_new[:rows])
+        lg = bits(b.logits[:rows]) if with_logits else None
+        ids = b.input_ids[:rows].cpu().numpy()
+        tgt = b.target_ids[:rows].cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.verify_attention(q, kn, vn, kc.reshape(-1), vc.reshape(-1), b.H * b.D, b.D, cu[:ns + 1],
+                                starts, kl[:ns], b.H, b.D, b.scale, b.dtype)
+        x = oracle.argmax(lg, b.dtype) if with_logits else tgt
+        acc, _, _ = oracle.greedy_accept(x, ids, cu[:ns + 1])
+        oracle.kv_append(kc.reshape(-1), vc.reshape(-1), b.H * b.D, b.D, kn, vn, cu[:ns + 1], acc, starts,
+                         kl[:ns], b.H, b.D)
+        return time.perf_counter() - t0, int(acc.sum())
+
+    probe = max(1, min(2, b.B))
+    t_probe, _ = run(probe)
+    ns = int(max(probe, min(b.B, budget_s / max(t_probe / probe, 1e-6))))
+    t, accepted = run(ns)
+    return {"value": round(accepted / t, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(t, 3),
+            "sample": "first %d of %d samples of the same batch, all heads, one layer: fp64 oracle "
+                      "attention + arg-max + accept + append" % (ns, b.B)}
+
+
+if __name__ == "__main__":
+    main()

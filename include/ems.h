@@ -172,6 +172,18 @@ EMS_API ems_status ems_validate_inputs(
     const int32_t* cu_seqlens, const int32_t* kv_start, const int32_t* kv_len,
     int B, int T, int max_k, int max_kv_len, int64_t rows, void* hip_stream);
 
+/*
+ * Profiling aid (not part of the verification step; single-threaded use).
+ * ems_profile_enable(n) creates n pairs of HIP events (host objects); from then on each
+ * of the next n ems_verify_attention calls records one pair on its stream right before
+ * and right after its main attention kernel (the partial-merge kernel is outside the
+ * pair).  ems_profile_read waits for the recorded pairs, returns the summed elapsed
+ * milliseconds and the number of pairs, and rearms them.  ems_profile_enable(0)
+ * destroys the events and switches timing off.
+ */
+EMS_API ems_status ems_profile_enable(int max_records);
+EMS_API ems_status ems_profile_read(double* total_ms, int* launches);
+
 /* Thread-local text for the last non-OK status returned on this thread. */
 EMS_API const char* ems_last_error_string(void);
 

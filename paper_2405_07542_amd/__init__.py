@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
                                     i32, i32, i32, i32, i32, vp]
         L.ems_validate_inputs.restype = i32
         L.ems_validate_inputs.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, vp]
+        L.ems_profile_enable.restype = i32
+        L.ems_profile_enable.argtypes = [i32]
+        L.ems_profile_read.restype = i32
+        L.ems_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
         _lib = L
     return _lib
 
@@ -148,6 +152,18 @@ def ems_validate_inputs(cu_seqlens, kv_start, kv_len, *, T: int, max_k: int, max
                                      _stream(stream)))
 
 
-__all__ = ["EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
+def ems_profile_enable(max_records: int) -> None:
+    _check(lib().ems_profile_enable(int(max_records)))
+
+
+def ems_profile_read():
+    """(summed milliseconds of the timed attention kernels, number of launches timed)."""
+    ms = ctypes.c_double(0.0)
+    n = ctypes.c_int(0)
+    _check(lib().ems_profile_read(ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
+
+
+__all__ = ["ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
            "ems_accept_workspace_bytes", "ems_verify_attention", "ems_greedy_accept",
            "ems_kv_append", "ems_validate_inputs", "EMS_F16", "EMS_BF16", "EMS_F32"]

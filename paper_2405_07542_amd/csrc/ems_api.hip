@@ -77,6 +77,13 @@ void accept_slicing(int T, int V, int* slices, int* slice_len) {
 
 bool dtype16(ems_dtype d) { return d == EMS_F16 || d == EMS_BF16; }
 
+// Optional timing of the main attention kernel with HIP events (profiling aid).
+struct Profile {
+    std::vector<hipEvent_t> start, stop;
+    int used = 0;
+};
+Profile g_prof;
+
 }  // namespace
 
 extern "C" {
@@ -154,8 +161,14 @@ ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_
     p.H = H;
     p.num_waves = blocks * kWavesPerBlock;
     p.scale_log2 = scale * 1.4426950408889634f;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (g_prof.used < (int)g_prof.start.size()) {
+        ev0 = g_prof.start[g_prof.used];
+        ev1 = g_prof.stop[g_prof.used];
+        ++g_prof.used;
+    }
     hipError_t e = ems::launch_verify_attention(p, blocks, D, dtype == EMS_BF16,
-                                                static_cast<hipStream_t>(hip_stream));
+                                                static_cast<hipStream_t>(hip_stream), ev0, ev1);
     if (e != hipSuccess) return hip_fail("ems_verify_attention launch", e);
     return EMS_OK;
 }
@@ -266,6 +279,41 @@ ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_n
         hipError_t e = ems::launch_advance_kv_len(kv_len, accepted, kv_len_out, B, stream);
         if (e != hipSuccess) return hip_fail("ems_kv_append length update launch", e);
     }
+    return EMS_OK;
+}
+
+ems_status ems_profile_enable(int max_records) {
+    for (hipEvent_t ev : g_prof.start) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : g_prof.stop) (void)hipEventDestroy(ev);
+    g_prof.start.clear();
+    g_prof.stop.clear();
+    g_prof.used = 0;
+    if (max_records < 0 || max_records > 65536)
+        return fail(EMS_ERR_INVALID_ARG, "max_records = %d outside [0, 65536]", max_records);
+    for (int i = 0; i < max_records; ++i) {
+        hipEvent_t a = nullptr, b = nullptr;
+        hipError_t e = hipEventCreate(&a);
+        if (e == hipSuccess) e = hipEventCreate(&b);
+        if (e != hipSuccess) return hip_fail("hipEventCreate", e);
+        g_prof.start.push_back(a);
+        g_prof.stop.push_back(b);
+    }
+    return EMS_OK;
+}
+
+ems_status ems_profile_read(double* total_ms, int* launches) {
+    if (!total_ms || !launches) return fail(EMS_ERR_INVALID_ARG, "total_ms and launches must not be NULL");
+    double sum = 0.0;
+    for (int i = 0; i < g_prof.used; ++i) {
+        hipError_t e = hipEventSynchronize(g_prof.stop[i]);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]);
+        if (e != hipSuccess) return hip_fail("ems_profile_read", e);
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = g_prof.used;
+    g_prof.used = 0;
     return EMS_OK;
 }
 

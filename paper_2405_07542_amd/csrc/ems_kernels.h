@@ -29,8 +29,10 @@ struct AttnParams {
     float scale_log2;          // scale * log2(e)
 };
 
+// ev_start / ev_stop (may be null) are recorded right before and right after the main
+// attention kernel, i.e. they exclude the partial-merge kernel.
 hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16,
-                                   hipStream_t stream);
+                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 struct ArgmaxPartial {
     float value;

@@ -370,22 +370,26 @@ __global__ __launch_bounds__(D) void combine_partials_kernel(AttnParams p) {
 }
 
 template <typename ET, int D>
-static hipError_t launch_typed(const AttnParams& p, int blocks, hipStream_t stream) {
+static hipError_t launch_typed(const AttnParams& p, int blocks, hipStream_t stream,
+                               hipEvent_t ev_start, hipEvent_t ev_stop) {
     const size_t lds = (size_t)(p.B + 1) * sizeof(int32_t);
+    hipError_t e;
+    if (ev_start && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((verify_attention_kernel<ET, D>), dim3(blocks), dim3(kAttnThreads), lds,
                        stream, p);
-    hipError_t e = hipGetLastError();
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((combine_partials_kernel<ET, D>), dim3(p.H, p.B), dim3(D), lds, stream, p);
     return hipGetLastError();
 }
 
 hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16,
-                                   hipStream_t stream) {
-    if (D == 128) return bf16 ? launch_typed<BF16, 128>(p, blocks, stream)
-                              : launch_typed<F16, 128>(p, blocks, stream);
-    return bf16 ? launch_typed<BF16, 64>(p, blocks, stream)
-                : launch_typed<F16, 64>(p, blocks, stream);
+                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    if (D == 128) return bf16 ? launch_typed<BF16, 128>(p, blocks, stream, ev_start, ev_stop)
+                              : launch_typed<F16, 128>(p, blocks, stream, ev_start, ev_stop);
+    return bf16 ? launch_typed<BF16, 64>(p, blocks, stream, ev_start, ev_stop)
+                : launch_typed<F16, 64>(p, blocks, stream, ev_start, ev_stop);
 }
 
 }  // namespace ems

@@ -47,8 +47,12 @@ int attn_blocks_for(int64_t tiles, int max_blocks) {
     return (int)std::max<int64_t>(1, std::min<int64_t>(want, max_blocks));
 }
 
-size_t attn_ws_bytes_for(int blocks, int D) {
-    return (size_t)2 * blocks * kWavesPerBlock * 16 * (D + ems::kPartialPad) * sizeof(float);
+// Workspace = header (the B+1 tile prefix sums, padded to 256 B) + partial slots.
+size_t attn_ws_header_bytes(int B) { return ((size_t)(B + 1) * sizeof(int32_t) + 255) / 256 * 256; }
+
+size_t attn_ws_bytes_for(int blocks, int B, int D) {
+    return attn_ws_header_bytes(B) +
+           (size_t)2 * blocks * kWavesPerBlock * 16 * (D + ems::kPartialPad) * sizeof(float);
 }
 
 // Workgroups the device keeps resident for the attention kernel (2 per CU), cached per device.
@@ -96,7 +100,7 @@ size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len)
     (void)T;
     if (B < 1 || H < 1 || D < 1 || max_kv_len < 0) return 256;
     const int blocks = attn_blocks_for(tile_upper_bound(B, H, max_kv_len), kMaxAttnBlocks);
-    return std::max<size_t>(256, attn_ws_bytes_for(blocks, D));
+    return std::max<size_t>(256, attn_ws_bytes_for(blocks, B, D));
 }
 
 ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_new,
@@ -137,7 +141,7 @@ ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_
     if (tiles >= ((int64_t)1 << 31)) return fail(EMS_ERR_UNSUPPORTED, "too many key tiles");
 
     const int blocks = attn_blocks_for(tiles, resident_attn_blocks());
-    const size_t need = attn_ws_bytes_for(blocks, D);
+    const size_t need = attn_ws_bytes_for(blocks, B, D);
     if (!workspace || workspace_bytes < need)
         return fail(EMS_ERR_WORKSPACE, "attention workspace of %zu bytes needed, %zu given", need,
                     workspace ? workspace_bytes : (size_t)0);
@@ -155,7 +159,8 @@ ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_
     p.kv_start = kv_start;
     p.kv_len = kv_len;
     p.out = out;
-    p.ws = static_cast<float*>(workspace);
+    p.ws_header = static_cast<int32_t*>(workspace);
+    p.ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + attn_ws_header_bytes(B));
     p.out_f32 = out_dtype == EMS_F32;
     p.B = B;
     p.H = H;
@@ -250,6 +255,9 @@ ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_n
             return fail(EMS_ERR_INVALID_ARG, "layer %d: cache strides must be multiples of 8 elements and at least D", l);
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // kv_len_out is written by the first copy launch unless it aliases kv_len
+    bool lengths_pending = kv_len_out != nullptr;
+    const bool in_place = kv_len_out == kv_len;
     if (T > 0) {
         for (int l0 = 0; l0 < n_layers; l0 += ems::kMaxLayersPerLaunch) {
             ems::AppendParams p;
@@ -268,14 +276,16 @@ ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_n
             p.accepted = accepted;
             p.kv_start = kv_start;
             p.kv_len = kv_len;
+            p.kv_len_out = (lengths_pending && !in_place) ? kv_len_out : nullptr;
             p.B = B;
             p.H = H;
             p.vec_per_head = D / 8;
             hipError_t e = ems::launch_kv_append(p, stream);
             if (e != hipSuccess) return hip_fail("ems_kv_append launch", e);
+            if (!in_place) lengths_pending = false;
         }
     }
-    if (kv_len_out != nullptr) {
+    if (lengths_pending) {
         hipError_t e = ems::launch_advance_kv_len(kv_len, accepted, kv_len_out, B, stream);
         if (e != hipSuccess) return hip_fail("ems_kv_append length update launch", e);
     }

@@ -61,16 +61,40 @@ __device__ __forceinline__ uint32_t pair_hi(uint32_t x, uint32_t y) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Load from global memory at (wave-uniform 64-bit base) + (per-lane 32-bit byte offset);
+// the explicit global address space lets the compiler emit global_load with a scalar base.
+template <typename V>
+__device__ __forceinline__ V gload(uint64_t base, uint32_t off) {
+    return *reinterpret_cast<const __attribute__((address_space(1))) V*>(base + off);
+}
+
+// Reductions over the four lanes {n, n+16, n+32, n+48} that share one MFMA column,
+// with the gfx950 row-swap instructions (no LDS round trip): after the 16-lane swap
+// the two results hold rows (0,0,2,2) and (1,1,3,3), after the 32-lane swap the lower
+// and the upper half of the wave.
+__device__ __forceinline__ float quad_max(float x) {
+    u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float quad_sum(float x) {
+    u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <typename T>
 __device__ __forceinline__ T uniform(T v) {   // wave-uniform value -> scalar register
     static_assert(sizeof(T) == 4, "32-bit only");
     return __builtin_bit_cast(T, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v)));
 }
-__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+__device__ __forceinline__ uint64_t uniform_addr(const void* p) {
     uint64_t u = (uint64_t)p;
     uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u);
     uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
-    return (const char*)(((uint64_t)hi << 32) | lo);
+    return ((uint64_t)hi << 32) | lo;
 }
 
 }  // namespace ems

@@ -22,6 +22,7 @@ struct AttnParams {
     const int32_t* kv_start;
     const int32_t* kv_len;
     void* out;
+    int32_t* ws_header;        // workspace header: the B+1 tile prefix sums, for the merge kernel
     float* ws;                 // 2 * num_waves partial slots of 16 x (D + kPartialPad) floats
     int out_f32;
     int B, H;
@@ -73,6 +74,7 @@ struct AppendParams {
     const int32_t* accepted;
     const int32_t* kv_start;
     const int32_t* kv_len;
+    int32_t* kv_len_out;       // written by this launch when non-null (must not alias kv_len)
     int B, H;
     int vec_per_head;          // D * 2 / 16
 };

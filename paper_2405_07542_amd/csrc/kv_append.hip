@@ -5,7 +5,8 @@
 //
 // Grid (B, 2 * n_layers): one block copies the accepted rows of one sample for
 // one layer's K or V with 16-byte loads and stores.  The per-sample lengths are
-// advanced by a second, tiny launch so that kv_len_out may alias kv_len.
+// written by the same launch, except when kv_len_out aliases kv_len: then a
+// second, tiny launch advances them after every block has read the old ones.
 #include "ems_device.h"
 #include "ems_kernels.h"
 
@@ -15,24 +16,29 @@ constexpr int kAppendThreads = 256;
 
 __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(AppendParams p) {
     const int i = blockIdx.x;
+    const int acc = p.accepted[i];
+    const int len = p.kv_len[i];
+    // the lengths ride along unless they are updated in place (then a later launch does it,
+    // because other blocks still read kv_len[i])
+    if (p.kv_len_out != nullptr && blockIdx.y == 0 && threadIdx.x == 0) p.kv_len_out[i] = len + acc;
     // never more than the sample brought (accepted[i] <= k_i is the caller's contract)
-    const int a = min(p.accepted[i], p.cu[i + 1] - p.cu[i]);
+    const int cu_i = p.cu[i];
+    const int a = min(acc, p.cu[i + 1] - cu_i);
     if (a <= 0) return;
     const AppendLayer& ly = p.layer[blockIdx.y >> 1];
     const bool is_v = blockIdx.y & 1;
     const int vph = p.vec_per_head;
-    const int64_t row_vecs = (int64_t)p.H * vph;
-    const char* src = (is_v ? ly.v_new : ly.k_new) + (int64_t)p.cu[i] * row_vecs * 16;
-    char* dst = (is_v ? ly.v_cache : ly.k_cache) +
-                ((int64_t)p.kv_start[i] + p.kv_len[i]) * ly.row_stride_b;
-    const int64_t nvec = (int64_t)a * row_vecs;
-    for (int64_t v = threadIdx.x; v < nvec; v += kAppendThreads) {
-        const int64_t j = v / row_vecs;
-        const int rem = (int)(v - j * row_vecs);
-        const int h = rem / vph;
-        const int c = rem - h * vph;
-        const u32x4 w = *reinterpret_cast<const u32x4*>(src + v * 16);
-        *reinterpret_cast<u32x4*>(dst + j * ly.row_stride_b + (int64_t)h * ly.head_stride_b + c * 16) = w;
+    const int row_vecs = p.H * vph;
+    const char* src = (is_v ? ly.v_new : ly.k_new) + (int64_t)cu_i * row_vecs * 16;
+    char* dst = (is_v ? ly.v_cache : ly.k_cache) + ((int64_t)p.kv_start[i] + len) * ly.row_stride_b;
+    for (int v = threadIdx.x; v < row_vecs; v += kAppendThreads) {
+        const int h = v / vph;
+        const int c = v - h * vph;
+        const int64_t doff = (int64_t)h * ly.head_stride_b + c * 16;
+        for (int j = 0; j < a; ++j) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(src + ((int64_t)j * row_vecs + v) * 16);
+            *reinterpret_cast<u32x4*>(dst + j * ly.row_stride_b + doff) = w;
+        }
     }
 }
 

@@ -70,25 +70,31 @@ struct TileRegs {
     vrow_t v[8];                             // this lane's 8 keys x VW head-dim elements
 };
 
-// Issue the loads of one tile.  kbase/vbase point at (first row of the run, head h);
-// rows are clamped to `last` so that masked keys still read valid, finite data.
+// Where the 32 keys of one tile live: a run of rows of `row_bytes` starting at kbase/vbase
+// (already offset to the head), first key n0, last valid row `last` (rows are clamped to
+// it so that masked keys still read valid, finite data).
+struct TileSrc {
+    uint64_t kbase, vbase;   // wave-uniform
+    uint32_t row_bytes;
+    int n0, last;
+};
+
 template <int D>
-__device__ __forceinline__ void load_tile(TileRegs<D>& t, const char* kbase, const char* vbase,
-                                          uint32_t row_bytes, int n0, int last, int n, int g) {
+__device__ __forceinline__ void load_tile(TileRegs<D>& t, const TileSrc& src, int n, int g) {
     constexpr int KS = TileRegs<D>::KS;
     constexpr int VW = TileRegs<D>::VW;
-    const uint32_t ra = (uint32_t)min(n0 + n, last) * row_bytes + (uint32_t)g * 16u;
-    const uint32_t rb = (uint32_t)min(n0 + 16 + n, last) * row_bytes + (uint32_t)g * 16u;
+    const uint32_t ra = (uint32_t)min(src.n0 + n, src.last) * src.row_bytes + (uint32_t)g * 16u;
+    const uint32_t rb = (uint32_t)min(src.n0 + 16 + n, src.last) * src.row_bytes + (uint32_t)g * 16u;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-        t.ka[s] = *reinterpret_cast<const u32x4*>(kbase + ra + 64 * s);
-        t.kb[s] = *reinterpret_cast<const u32x4*>(kbase + rb + 64 * s);
+        t.ka[s] = gload<u32x4>(src.kbase, ra + 64 * s);
+        t.kb[s] = gload<u32x4>(src.kbase, rb + 64 * s);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        const int key = n0 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
-        const uint32_t off = (uint32_t)min(key, last) * row_bytes + (uint32_t)n * (VW * 2);
-        t.v[e] = *reinterpret_cast<const typename TileRegs<D>::vrow_t*>(vbase + off);
+        const int key = src.n0 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
+        const uint32_t off = (uint32_t)min(key, src.last) * src.row_bytes + (uint32_t)n * (VW * 2);
+        t.v[e] = gload<typename TileRegs<D>::vrow_t>(src.vbase, off);
     }
 }
 
@@ -129,9 +135,7 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* 
     }
     float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
                      fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(st.m, mx);
+    const float m_new = fmaxf(st.m, quad_max(mx));
     // every tile holds at least one visible key for every row, so m_new is finite
     const float alpha = fast_exp2(st.m - m_new);     // exp2(-inf) = 0 on the first tile
     float psum = 0.f;
@@ -184,6 +188,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
     constexpr int KS = TileRegs<D>::KS;
     constexpr int VW = TileRegs<D>::VW;
     build_tile_prefix(p, prefix);
+    if (blockIdx.x == 0)       // the merge kernel reads the tile prefix from the workspace header
+        for (int i = threadIdx.x; i <= p.B; i += blockDim.x) p.ws_header[i] = prefix[i];
     const int total = prefix[p.B];
     const int per = (total + p.num_waves - 1) / p.num_waves;
     const int wave = uniform((int)(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)));
@@ -201,38 +207,45 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
         const int mid = (lo + hi) >> 1;
         if (prefix[mid] <= gpos) lo = mid; else hi = mid;
     }
-    int i = lo;
+    int i = uniform(lo);
 
     while (gpos < gend) {
-        while (prefix[i + 1] <= gpos) ++i;
+        while (uniform(prefix[i + 1]) <= gpos) ++i;
         const int cu_i = uniform(p.cu[i]);
         const int k = uniform(p.cu[i + 1]) - cu_i;
         const int L = uniform(p.kv_len[i]);
         const int64_t start = uniform(p.kv_start[i]);
         const int ntc = (L + kTileKeys - 1) / kTileKeys;
         const int nt = ntc + 1;
-        const int rem = gpos - prefix[i];
-        const int h = rem / nt;
+        const int rem = gpos - uniform(prefix[i]);
+        const int h = uniform(rem / nt);
         const int t0 = rem - h * nt;
         const int t1 = min(nt, t0 + (gend - gpos));
 
         const int64_t cache_off = start * p.row_stride_b + (int64_t)h * p.head_stride_b;
-        const char* kc = uniform_ptr(p.k_cache + cache_off);
-        const char* vc = uniform_ptr(p.v_cache + cache_off);
         const int64_t new_off = ((int64_t)cu_i * p.H + h) * (D * 2);
-        const char* kn = uniform_ptr(p.k_new + new_off);
-        const char* vn = uniform_ptr(p.v_new + new_off);
         const uint32_t new_row_bytes = (uint32_t)p.H * (D * 2);
-        const uint32_t cache_row_bytes = (uint32_t)p.row_stride_b;
+        TileSrc cache_src, new_src;
+        cache_src.kbase = uniform_addr(p.k_cache + cache_off);
+        cache_src.vbase = uniform_addr(p.v_cache + cache_off);
+        cache_src.row_bytes = (uint32_t)p.row_stride_b;
+        cache_src.last = L - 1;
+        new_src.kbase = uniform_addr(p.k_new + new_off);
+        new_src.vbase = uniform_addr(p.v_new + new_off);
+        new_src.row_bytes = new_row_bytes;
+        new_src.n0 = 0;
+        new_src.last = k - 1;
 
         // Q^T as the B operand of S^T = K Q^T; rows beyond k_i are zero.
         u32x4 qb[KS];
         {
-            const char* qrow = p.q + new_off + (int64_t)n * new_row_bytes + g * 16;
+            const uint64_t qbase = uniform_addr(p.q + new_off);
+            const uint32_t qoff = (uint32_t)min(n, k - 1) * new_row_bytes + (uint32_t)g * 16u;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                u32x4 z = {0u, 0u, 0u, 0u};
-                qb[s] = n < k ? *reinterpret_cast<const u32x4*>(qrow + 64 * s) : z;
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                const u32x4 v = gload<u32x4>(qbase, qoff + 64 * s);
+                qb[s] = n < k ? v : z;
             }
         }
         SoftmaxState<ET, D> st;
@@ -245,10 +258,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
         const int lim_new = min(k, n + 1);
 
         auto issue = [&](TileRegs<D>& t, int tile) {
-            if (tile < ntc)
-                load_tile<D>(t, kc, vc, cache_row_bytes, tile * kTileKeys, L - 1, n, g);
-            else
-                load_tile<D>(t, kn, vn, new_row_bytes, 0, k - 1, n, g);
+            TileSrc src = cache_src;
+            src.n0 = tile * kTileKeys;
+            if (tile >= ntc) src = new_src;          // wave-uniform choice
+            load_tile<D>(t, src, n, g);
         };
         auto consume = [&](const TileRegs<D>& t, int tile) {
             if (tile < ntc) {
@@ -274,9 +287,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
         }
 
         // the four lanes of a query row hold disjoint shares of the sum
-        float l = st.l;
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
+        const float l = quad_sum(st.l);
 
         if (t0 == 0 && t1 == nt) {
             if (n < k) {
@@ -326,45 +337,51 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
     }
 }
 
-// Merge the partials of every (sample, head) pair whose tiles were shared by
-// several waves.  Grid (H, B), D threads: thread d owns one output column.
+// Merge the partials of every (sample, head) pair whose tiles were shared by several
+// waves.  Grid (H, B), 256 threads: D/4 lanes per output row, 4 columns per lane.
+constexpr int kCombineThreads = 256;
+
 template <typename ET, int D>
-__global__ __launch_bounds__(D) void combine_partials_kernel(AttnParams p) {
-    extern __shared__ int32_t prefix[];
-    build_tile_prefix(p, prefix);
-    const int total = prefix[p.B];
-    const int per = (total + p.num_waves - 1) / p.num_waves;
+__global__ __launch_bounds__(kCombineThreads) void combine_partials_kernel(AttnParams p) {
     const int i = blockIdx.y, h = blockIdx.x;
     const int cu_i = p.cu[i];
     const int k = p.cu[i + 1] - cu_i;
     if (k <= 0) return;
-    const int nt = tiles_of_sample(k, p.kv_len[i]);
-    const int g0 = prefix[i] + h * nt;
+    const int total = p.ws_header[p.B];
+    const int per = (total + p.num_waves - 1) / p.num_waves;
+    const int first = p.ws_header[i];
+    const int nt = (p.ws_header[i + 1] - first) / p.H;
+    const int g0 = first + h * nt;
     const int w0 = g0 / per, w1 = (g0 + nt - 1) / per;
     if (w0 == w1) return;                  // one wave saw the whole pair and wrote `out` itself
-    const int d = threadIdx.x;
     constexpr int pitch = D + kPartialPad;
-    for (int j = 0; j < k; ++j) {
+    constexpr int lanes_per_row = D / 4;
+    constexpr int rows_per_pass = kCombineThreads / lanes_per_row;
+    const int c4 = (threadIdx.x % lanes_per_row) * 4;
+    for (int j = threadIdx.x / lanes_per_row; j < k; j += rows_per_pass) {
         float M = -INFINITY;
         for (int w = w0; w <= w1; ++w) {
             const int slot = 2 * w + (w == w0 ? 1 : 0);
             M = fmaxf(M, p.ws[((int64_t)slot * 16 + j) * pitch + D]);
         }
-        float num = 0.f, den = 0.f;
+        f32x4 num = {0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
         for (int w = w0; w <= w1; ++w) {
             const int slot = 2 * w + (w == w0 ? 1 : 0);
             const float* src = p.ws + ((int64_t)slot * 16 + j) * pitch;
             const float wgt = fast_exp2(src[D] - M);
-            num += wgt * src[d];
+            num += wgt * *reinterpret_cast<const f32x4*>(src + c4);
             den += wgt * src[D + 1];
         }
-        const float o = num / den;
-        const int64_t idx = ((int64_t)(cu_i + j) * p.H + h) * D + d;
+        const float inv = 1.0f / den;
+        const int64_t idx = ((int64_t)(cu_i + j) * p.H + h) * D + c4;
         if (p.out_f32) {
-            reinterpret_cast<float*>(p.out)[idx] = o;
+            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + idx) = num * inv;
         } else {
-            const uint32_t pk = pack2(ET{}, o, 0.f);
-            reinterpret_cast<uint16_t*>(p.out)[idx] = (uint16_t)(pk & 0xffffu);
+            u32x2 pk;
+            pk[0] = pack2(ET{}, num[0] * inv, num[1] * inv);
+            pk[1] = pack2(ET{}, num[2] * inv, num[3] * inv);
+            *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(p.out) + idx) = pk;
         }
     }
 }
@@ -380,7 +397,8 @@ static hipError_t launch_typed(const AttnParams& p, int blocks, hipStream_t stre
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((combine_partials_kernel<ET, D>), dim3(p.H, p.B), dim3(D), lds, stream, p);
+    hipLaunchKernelGGL((combine_partials_kernel<ET, D>), dim3(p.H, p.B), dim3(kCombineThreads), 0,
+                       stream, p);
     return hipGetLastError();
 }
 

@@ -38,6 +38,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-logits", action="store_true", help="skip the [T,V] arg-max (ids given)")
     ap.add_argument("--breakdown", action="store_true", help="also time each call on its own")
+    ap.add_argument("--no-ablation", action="store_true", help="skip the padded (vanilla) ablation")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the bench: run a plain device copy of MIB MiB five times "
                          "(the known-size kernel that scales rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -205,9 +206,90 @@ def main():
                                   "accept_call": round(time_call(accept), 5),
                                   "append_call": round(time_call(append), 5)}
 
+    if not args.no_ablation:
+        result["padded_ablation"] = padded_ablation(sets, args, with_logits, alg_bytes, ms_per_step)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(sets[0]["b"], with_logits)
     print(json.dumps(result), flush=True)
+
+
+def padded_ablation(sets, args, with_logits, unpadded_alg_bytes, unpadded_ms):
+    """The vanilla method of Sec. 3.1 on the same data, same library: inputs padded to k_max
+    rows, caches aligned to the longest sample with padding keys masked, tau_max rows appended
+    for every sample.  Timed like the main loop (fewer steps)."""
+    import numpy as np
+    import torch
+    import paper_2405_07542_amd as ems
+    from workloads import pad_batch
+    dev = sets[0]["b"].q.device
+    psets = []
+    for st in sets:
+        b = st["b"]
+        p = pad_batch(b)
+        Tp = b.B * p.k_max
+        ids = torch.full((Tp,), -1, dtype=torch.int32, device=dev)     # padding ids never match
+        ids[p.real_rows] = b.input_ids
+        tgt = torch.zeros(Tp, dtype=torch.int32, device=dev)
+        tgt[p.real_rows] = st["target"]
+        logits = None
+        if with_logits:
+            logits = torch.randn((Tp, b.V), device=dev, dtype=torch.float32).to(b.dtype)
+            logits[p.real_rows] = b.logits
+        psets.append(dict(
+            p=p, ids=ids, tgt=tgt, logits=logits,
+            cu=torch.arange(0, Tp + 1, p.k_max, dtype=torch.int32, device=dev),
+            cache=ems.kv_cache(p.k_cache, p.v_cache, p.row_stride, p.head_stride, p.rows),
+            out=torch.empty_like(p.q_pad),
+            ws=torch.empty(ems.ems_attention_workspace_bytes(p.B, Tp, p.H, p.D, p.l_pad), dtype=torch.uint8, device=dev),
+            ws_acc=torch.empty(max(8, ems.ems_accept_workspace_bytes(Tp, b.V)), dtype=torch.uint8, device=dev),
+            accepted=torch.empty(b.B, dtype=torch.int32, device=dev),
+            accepted_cu=torch.empty(b.B + 1, dtype=torch.int32, device=dev),
+            out_tokens=torch.empty(Tp, dtype=torch.int32, device=dev),
+            tau_max=int(st["accepted"].max())))
+    torch.cuda.synchronize()
+
+    def step(ps):
+        p = ps["p"]
+        ems.ems_padded_verify_attention(p.q_pad, p.k_new_pad, p.v_new_pad, ps["cache"], p.cap, p.key_mask,
+                                        p.k_valid, ps["out"], k_max=p.k_max, l_pad=p.l_pad, scale=p.scale,
+                                        workspace=ps["ws"])
+        ems.ems_greedy_accept(ps["logits"], ps["tgt"], ps["ids"], ps["cu"], ps["accepted"],
+                              ps["accepted_cu"], ps["out_tokens"], workspace=ps["ws_acc"])
+        ems.ems_padded_kv_append([p.k_new_pad], [p.v_new_pad], [ps["cache"]], p.cap, p.key_mask,
+                                 ps["accepted"], k_max=p.k_max, l_pad=p.l_pad, tau_max=ps["tau_max"])
+
+    steps = max(10, args.steps // 3)
+    for w in range(5):
+        step(psets[w % len(psets)])
+    torch.cuda.synchronize()
+    ems.ems_profile_enable(steps)
+    t0 = time.perf_counter()
+    for s in range(steps):
+        step(psets[s % len(psets)])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    attn_ms_total, launches = ems.ems_profile_read()
+    ems.ems_profile_enable(0)
+    ms = (t1 - t0) * 1e3 / steps
+    attn_ms = attn_ms_total / max(1, launches)
+    # the padded path must accept exactly what the unpadded path accepted
+    same = all(torch.equal(ps["accepted"], st["accepted"]) for ps, st in zip(psets, sets))
+    p = psets[0]["p"]
+    hd = p.H * p.D
+    moved = float(np.mean([2 * ps["p"].B * ps["p"].l_pad * hd * 2 + 4 * ps["p"].B * ps["p"].k_max * hd * 2
+                           + ps["p"].B * ps["p"].l_pad for ps in psets]))
+    real_keys = float(np.mean([int(st["b"].kv_len.sum()) for st in sets]))
+    pad_keys = float(np.mean([ps["p"].B * ps["p"].l_pad for ps in psets]))
+    real_rows = float(np.mean([st["b"].T for st in sets]))
+    return {
+        "ms_per_step": round(ms, 5), "attention_kernel_ms": round(attn_ms, 5), "steps": steps,
+        "moved_GBps": round(moved / (attn_ms * 1e-3) / 1e9, 1),
+        "useful_GBps": round(unpadded_alg_bytes / (attn_ms * 1e-3) / 1e9, 1),
+        "kv_padding_ratio": round((pad_keys - real_keys) / pad_keys, 4),
+        "input_padding_ratio": round(1.0 - real_rows / (p.B * p.k_max), 4),
+        "accepted_equal_to_unpadded": bool(same),
+        "unpadded_speedup_step": round(ms / unpadded_ms, 3),
+    }
 
 
 def cpu_baseline(b, with_logits, budget_s=15.0):

@@ -161,6 +161,32 @@ EMS_API ems_status ems_kv_append(
     int B, int T, int H, int D, ems_dtype dtype, void* hip_stream);
 
 /*
+ * Ablation: the padded "vanilla" method of Sec. 3.1, same kernels, same library.
+ * Inputs are padded to k_max rows per sample ([B, k_max, H, D]; rows j >= k_valid[i] are
+ * padding); the caches are aligned: sample i owns arena rows i*cap .. i*cap + l_pad - 1,
+ * of which key_mask[i*cap + n] = 0 marks padding keys (they are read and masked, which is
+ * the vanilla method's extra memory traffic).  Real rows give the same result as
+ * ems_verify_attention on the unpadded data; padding rows are computed like the real ones
+ * and hold don't-care values.  Every sample needs k_valid[i] >= 1.
+ *   key_mask : device uint8 [B, cap], 4-byte aligned; cap a multiple of 32, >= l_pad
+ *   workspace: ems_attention_workspace_bytes(B, B*k_max, H, D, l_pad)
+ * ems_padded_kv_append writes tau_max (host value, <= k_max) rows for EVERY sample at the
+ * aligned row l_pad -- its accepted rows, then padding rows -- and sets key_mask there to
+ * (j < accepted[i]); the caller's aligned length becomes l_pad + tau_max.
+ */
+EMS_API ems_status ems_padded_verify_attention(
+    const void* q_pad, const void* k_new_pad, const void* v_new_pad,
+    const ems_kv_cache* cache, int64_t cap, const uint8_t* key_mask, const int32_t* k_valid,
+    void* out_pad, ems_dtype out_dtype,
+    int B, int k_max, int l_pad, int H, int D, float scale, ems_dtype dtype,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+EMS_API ems_status ems_padded_kv_append(
+    const void* const* k_new_pad_layers, const void* const* v_new_pad_layers,
+    const ems_kv_cache* caches, int n_layers, int64_t cap, uint8_t* key_mask,
+    const int32_t* accepted, int B, int k_max, int l_pad, int tau_max,
+    int H, int D, ems_dtype dtype, void* hip_stream);
+
+/*
  * Debug aid: copies the index arrays to the host (synchronises the stream) and
  * checks the contract the other calls assume: cu_seqlens[0]=0, non-decreasing,
  * cu_seqlens[B]=T, k_i <= max_k, 0 <= kv_len[i] <= max_kv_len, kv_start[i] >= 0,

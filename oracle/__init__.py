@@ -58,6 +58,14 @@ def _load():
         lib.oracle_kv_append.argtypes = [
             u16p, u16p, ctypes.c_int64, ctypes.c_int64, u16p, u16p,
             i32p, i32p, i32p, i32p, i32p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        u8p = ctypes.POINTER(ctypes.c_uint8)
+        lib.oracle_padded_verify_attention.argtypes = [
+            u16p, u16p, u16p, u16p, u16p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, u8p, i32p,
+            f64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_float, ctypes.c_int]
+        lib.oracle_padded_kv_append.argtypes = [
+            u16p, u16p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, u8p, u16p, u16p, i32p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -180,3 +188,42 @@ def kv_append(k_cache, v_cache, row_stride, head_stride, k_new, v_new,
         _p(cu, ctypes.c_int32), _p(acc, ctypes.c_int32), _p(ks, ctypes.c_int32),
         _p(kl, ctypes.c_int32), _p(out, ctypes.c_int32), B, int(H), int(D))
     return out
+
+
+def padded_verify_attention(q_pad, k_new_pad, v_new_pad, k_cache, v_cache, row_stride, head_stride,
+                            cap, key_mask, k_valid, k_max, l_pad, H, D, scale, dtype) -> np.ndarray:
+    """The padded (vanilla) method: fp64 [B*k_max, H, D], padding rows included."""
+    q_pad, k_new_pad, v_new_pad = _u16(q_pad), _u16(k_new_pad), _u16(v_new_pad)
+    k_cache, v_cache = _u16(k_cache), _u16(v_cache)
+    km = np.ascontiguousarray(key_mask, dtype=np.uint8)
+    kv = _i32(k_valid)
+    B = len(kv)
+    assert km.shape == (B, cap) and l_pad <= cap and q_pad.size == B * k_max * H * D
+    last = (B * cap - 1) * row_stride + (H - 1) * head_stride + D - 1 if row_stride >= head_stride \
+        else (H - 1) * head_stride + (B * cap - 1) * row_stride + D - 1
+    assert last < k_cache.size and last < v_cache.size
+    out = np.zeros((B * k_max, H, D), dtype=np.float64)
+    rc = _load().oracle_padded_verify_attention(
+        _p(q_pad, ctypes.c_uint16), _p(k_new_pad, ctypes.c_uint16), _p(v_new_pad, ctypes.c_uint16),
+        _p(k_cache, ctypes.c_uint16), _p(v_cache, ctypes.c_uint16), int(row_stride),
+        int(head_stride), int(cap), _p(km, ctypes.c_uint8), _p(kv, ctypes.c_int32),
+        _p(out, ctypes.c_double), B, int(k_max), int(l_pad), int(H), int(D), float(scale), _dt(dtype))
+    if rc:
+        raise MemoryError("oracle_padded_verify_attention ran out of memory")
+    return out
+
+
+def padded_kv_append(k_cache, v_cache, row_stride, head_stride, cap, key_mask, k_new_pad, v_new_pad,
+                     accepted, k_max, l_pad, tau_max, H, D) -> None:
+    """Vanilla append in place: tau_max rows per sample at aligned row l_pad, mask updated."""
+    k_cache, v_cache = _u16(k_cache, True), _u16(v_cache, True)
+    k_new_pad, v_new_pad = _u16(k_new_pad), _u16(v_new_pad)
+    acc = _i32(accepted)
+    B = len(acc)
+    assert key_mask.dtype == np.uint8 and key_mask.flags.c_contiguous and key_mask.shape == (B, cap)
+    assert 0 <= tau_max <= k_max and l_pad + tau_max <= cap
+    _load().oracle_padded_kv_append(
+        _p(k_cache, ctypes.c_uint16), _p(v_cache, ctypes.c_uint16), int(row_stride),
+        int(head_stride), int(cap), _p(key_mask, ctypes.c_uint8), _p(k_new_pad, ctypes.c_uint16),
+        _p(v_new_pad, ctypes.c_uint16), _p(acc, ctypes.c_int32), B, int(k_max), int(l_pad),
+        int(tau_max), int(H), int(D))

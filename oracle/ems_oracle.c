@@ -252,3 +252,104 @@ int oracle_kv_append(uint16_t* k_cache, uint16_t* v_cache, int64_t row_stride, i
         for (int i = 0; i < B; ++i) kv_len_out[i] = kv_len[i] + accepted[i];
     return 0;
 }
+
+/*
+ * The padded "vanilla" method (Sec. 3.1), kept as the ablation's own definition.
+ * Inputs are padded to k_max rows per sample, caches are aligned to l_pad rows per sample
+ * (sample i owns arena rows i*cap .. i*cap+l_pad-1) and an attention mask hides padding:
+ *   cached key n          visible iff key_mask[i*cap + n] != 0
+ *   new key jj of row j   visible iff jj <= j and jj < k_valid[i]
+ * Every one of the k_max rows is computed, padding rows included (their values are
+ * don't-care; the paper's point is that they cost time and traffic).
+ * out is fp64 [B*k_max, H, D].
+ */
+int oracle_padded_verify_attention(const uint16_t* q_pad, const uint16_t* k_new_pad,
+                                   const uint16_t* v_new_pad, const uint16_t* k_cache,
+                                   const uint16_t* v_cache, int64_t row_stride, int64_t head_stride,
+                                   int64_t cap, const uint8_t* key_mask, const int32_t* k_valid,
+                                   double* out, int B, int k_max, int l_pad, int H, int D,
+                                   float scale, int dtype) {
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int i = 0; i < B; ++i) {
+        for (int h = 0; h < H; ++h) {
+            const int N = l_pad + k_max;
+            double* S = (double*)malloc(sizeof(double) * (size_t)N);
+            double* p = (double*)malloc(sizeof(double) * (size_t)N);
+            unsigned char* mask = (unsigned char*)malloc((size_t)N);
+            if (!S || !p || !mask) {
+#pragma omp atomic write
+                failed = 1;
+                free(S); free(p); free(mask);
+                continue;
+            }
+            for (int j = 0; j < k_max; ++j) {
+                const int64_t qoff = (((int64_t)i * k_max + j) * H + h) * D;
+                for (int n = 0; n < N; ++n) {
+                    if (n < l_pad) mask[n] = key_mask[(int64_t)i * cap + n] != 0;
+                    else mask[n] = (n - l_pad <= j) && (n - l_pad < k_valid[i]);
+                }
+                double m = -INFINITY;
+                for (int n = 0; n < N; ++n) {
+                    S[n] = -INFINITY;
+                    if (mask[n]) {
+                        double dot = 0.0;
+                        for (int d = 0; d < D; ++d) {
+                            double kv = n < l_pad
+                                ? widen(k_cache[((int64_t)i * cap + n) * row_stride + (int64_t)h * head_stride + d], dtype)
+                                : widen(k_new_pad[(((int64_t)i * k_max + n - l_pad) * H + h) * D + d], dtype);
+                            dot += widen(q_pad[qoff + d], dtype) * kv;
+                        }
+                        S[n] = (double)scale * dot;
+                    }
+                    if (S[n] > m) m = S[n];
+                }
+                double Z = 0.0;
+                for (int n = 0; n < N; ++n) {
+                    p[n] = mask[n] ? exp(S[n] - m) : 0.0;
+                    Z += p[n];
+                }
+                for (int d = 0; d < D; ++d) {
+                    double acc = 0.0;
+                    for (int n = 0; n < N; ++n) {
+                        if (!mask[n]) continue;
+                        double vv = n < l_pad
+                            ? widen(v_cache[((int64_t)i * cap + n) * row_stride + (int64_t)h * head_stride + d], dtype)
+                            : widen(v_new_pad[(((int64_t)i * k_max + n - l_pad) * H + h) * D + d], dtype);
+                        acc += p[n] * vv;
+                    }
+                    out[qoff + d] = acc / Z;
+                }
+            }
+            free(S); free(p); free(mask);
+        }
+    }
+    return failed;
+}
+
+/*
+ * Vanilla append (Sec. 3.1, Table 1): every sample grows by tau_max = the batch maximum of
+ * the accepted counts; sample i's rows j < accepted[i] are real, the other tau_max -
+ * accepted[i] rows are padding (written, but masked).  Aligned length becomes l_pad + tau_max.
+ */
+int oracle_padded_kv_append(uint16_t* k_cache, uint16_t* v_cache, int64_t row_stride,
+                            int64_t head_stride, int64_t cap, uint8_t* key_mask,
+                            const uint16_t* k_new_pad, const uint16_t* v_new_pad,
+                            const int32_t* accepted, int B, int k_max, int l_pad, int tau_max,
+                            int H, int D) {
+    for (int i = 0; i < B; ++i) {
+        for (int j = 0; j < tau_max; ++j) {
+            const int64_t dst_row = (int64_t)i * cap + l_pad + j;
+            const int64_t src_row = (int64_t)i * k_max + j;
+            key_mask[dst_row] = (uint8_t)(j < accepted[i]);
+            for (int h = 0; h < H; ++h)
+                for (int d = 0; d < D; ++d) {
+                    int64_t dst = dst_row * row_stride + (int64_t)h * head_stride + d;
+                    int64_t src = (src_row * H + h) * D + d;
+                    k_cache[dst] = k_new_pad[src];
+                    v_cache[dst] = v_new_pad[src];
+                }
+        }
+    }
+    return 0;
+}

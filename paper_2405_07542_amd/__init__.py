@@ -67,6 +67,14 @@ def lib() -> ctypes.CDLL:
                                     i32, i32, i32, i32, i32, vp]
         L.ems_validate_inputs.restype = i32
         L.ems_validate_inputs.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, vp]
+        L.ems_padded_verify_attention.restype = i32
+        L.ems_padded_verify_attention.argtypes = [vp, vp, vp, ctypes.POINTER(KvCacheStruct), i64, vp,
+                                                  vp, vp, i32, i32, i32, i32, i32, i32,
+                                                  ctypes.c_float, i32, vp, sz, vp]
+        L.ems_padded_kv_append.restype = i32
+        L.ems_padded_kv_append.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                           ctypes.POINTER(KvCacheStruct), i32, i64, vp, vp,
+                                           i32, i32, i32, i32, i32, i32, i32, vp]
         L.ems_profile_enable.restype = i32
         L.ems_profile_enable.argtypes = [i32]
         L.ems_profile_read.restype = i32
@@ -152,6 +160,32 @@ def ems_validate_inputs(cu_seqlens, kv_start, kv_len, *, T: int, max_k: int, max
                                      _stream(stream)))
 
 
+def ems_padded_verify_attention(q_pad, k_new_pad, v_new_pad, cache: KvCacheStruct, cap: int,
+                                key_mask, k_valid, out_pad, *, k_max: int, l_pad: int, scale: float,
+                                workspace: torch.Tensor, stream=None) -> None:
+    """Ablation: the padded (vanilla) method; tensors are [B*k_max, H, D]."""
+    _, H, D = q_pad.shape
+    B = k_valid.numel()
+    _check(lib().ems_padded_verify_attention(
+        _ptr(q_pad), _ptr(k_new_pad), _ptr(v_new_pad), ctypes.byref(cache), int(cap), _ptr(key_mask),
+        _ptr(k_valid), _ptr(out_pad), _DT[out_pad.dtype], B, int(k_max), int(l_pad), H, D,
+        float(scale), _DT[q_pad.dtype], _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ems_padded_kv_append(k_new_pad_layers, v_new_pad_layers, caches, cap: int, key_mask, accepted, *,
+                         k_max: int, l_pad: int, tau_max: int, stream=None) -> None:
+    n = len(caches)
+    _, H, D = k_new_pad_layers[0].shape
+    B = accepted.numel()
+    karr = (ctypes.c_void_p * n)(*[t.data_ptr() for t in k_new_pad_layers])
+    varr = (ctypes.c_void_p * n)(*[t.data_ptr() for t in v_new_pad_layers])
+    carr = (KvCacheStruct * n)(*caches)
+    _check(lib().ems_padded_kv_append(karr, varr, carr, n, int(cap), _ptr(key_mask), _ptr(accepted),
+                                      B, int(k_max), int(l_pad), int(tau_max), H, D,
+                                      _DT[k_new_pad_layers[0].dtype], _stream(stream)))
+
+
 def ems_profile_enable(max_records: int) -> None:
     _check(lib().ems_profile_enable(int(max_records)))
 
@@ -164,6 +198,6 @@ def ems_profile_read():
     return ms.value, n.value
 
 
-__all__ = ["ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
+__all__ = ["ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
            "ems_accept_workspace_bytes", "ems_verify_attention", "ems_greedy_accept",
            "ems_kv_append", "ems_validate_inputs", "EMS_F16", "EMS_BF16", "EMS_F32"]

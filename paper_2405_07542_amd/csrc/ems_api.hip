@@ -103,12 +103,24 @@ size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len)
     return std::max<size_t>(256, attn_ws_bytes_for(blocks, B, D));
 }
 
-ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_new,
-                                const ems_kv_cache* cache, const int32_t* cu_seqlens,
-                                const int32_t* kv_start, const int32_t* kv_len, void* out,
-                                ems_dtype out_dtype, int B, int T, int H, int D, int max_k,
-                                int max_kv_len, float scale, ems_dtype dtype, void* workspace,
-                                size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+struct PaddedArgs {
+    const uint8_t* key_mask;
+    const int32_t* k_valid;
+    int k_max, l_pad;
+    int64_t cap;
+};
+
+// Shared by the unpadded entry point and the padded ablation (pad != nullptr).
+ems_status run_attention(const void* q, const void* k_new, const void* v_new,
+                         const ems_kv_cache* cache, const int32_t* cu_seqlens,
+                         const int32_t* kv_start, const int32_t* kv_len, void* out,
+                         ems_dtype out_dtype, int B, int T, int H, int D, int max_k,
+                         int max_kv_len, float scale, ems_dtype dtype, void* workspace,
+                         size_t workspace_bytes, void* hip_stream, const PaddedArgs* pad) {
     if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
     if (T < 0) return fail(EMS_ERR_INVALID_ARG, "T = %d, need T >= 0", T);
     if (H < 1) return fail(EMS_ERR_INVALID_ARG, "H = %d, need H >= 1", H);
@@ -118,7 +130,7 @@ ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_
     if (!dtype16(dtype)) return fail(EMS_ERR_INVALID_ARG, "dtype must be EMS_F16 or EMS_BF16");
     if (out_dtype != dtype && out_dtype != EMS_F32)
         return fail(EMS_ERR_INVALID_ARG, "out_dtype must equal dtype or be EMS_F32");
-    if (!cu_seqlens || !kv_start || !kv_len)
+    if (!pad && (!cu_seqlens || !kv_start || !kv_len))
         return fail(EMS_ERR_INVALID_ARG, "cu_seqlens, kv_start and kv_len must not be NULL");
     if (D != 64 && D != 128) return fail(EMS_ERR_UNSUPPORTED, "D = %d, supported head dims are 64 and 128", D);
     if (max_k > EMS_MAX_QUERY_ROWS)
@@ -148,6 +160,7 @@ ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_
     if (!aligned16(workspace)) return fail(EMS_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
 
     ems::AttnParams p;
+    std::memset(&p, 0, sizeof p);
     p.q = static_cast<const char*>(q);
     p.k_new = static_cast<const char*>(k_new);
     p.v_new = static_cast<const char*>(v_new);
@@ -166,16 +179,63 @@ ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_
     p.H = H;
     p.num_waves = blocks * kWavesPerBlock;
     p.scale_log2 = scale * 1.4426950408889634f;
+    if (pad) {
+        p.key_mask = pad->key_mask;
+        p.k_valid = pad->k_valid;
+        p.k_max = pad->k_max;
+        p.l_pad = pad->l_pad;
+        p.cap = pad->cap;
+    }
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (g_prof.used < (int)g_prof.start.size()) {
         ev0 = g_prof.start[g_prof.used];
         ev1 = g_prof.stop[g_prof.used];
         ++g_prof.used;
     }
-    hipError_t e = ems::launch_verify_attention(p, blocks, D, dtype == EMS_BF16,
+    hipError_t e = ems::launch_verify_attention(p, blocks, D, dtype == EMS_BF16, pad != nullptr,
                                                 static_cast<hipStream_t>(hip_stream), ev0, ev1);
-    if (e != hipSuccess) return hip_fail("ems_verify_attention launch", e);
+    if (e != hipSuccess) return hip_fail("attention launch", e);
     return EMS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_new,
+                                const ems_kv_cache* cache, const int32_t* cu_seqlens,
+                                const int32_t* kv_start, const int32_t* kv_len, void* out,
+                                ems_dtype out_dtype, int B, int T, int H, int D, int max_k,
+                                int max_kv_len, float scale, ems_dtype dtype, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+    return run_attention(q, k_new, v_new, cache, cu_seqlens, kv_start, kv_len, out, out_dtype, B, T,
+                         H, D, max_k, max_kv_len, scale, dtype, workspace, workspace_bytes,
+                         hip_stream, nullptr);
+}
+
+ems_status ems_padded_verify_attention(const void* q_pad, const void* k_new_pad,
+                                       const void* v_new_pad, const ems_kv_cache* cache,
+                                       int64_t cap, const uint8_t* key_mask,
+                                       const int32_t* k_valid, void* out_pad, ems_dtype out_dtype,
+                                       int B, int k_max, int l_pad, int H, int D, float scale,
+                                       ems_dtype dtype, void* workspace, size_t workspace_bytes,
+                                       void* hip_stream) {
+    if (k_max < 1) return fail(EMS_ERR_INVALID_ARG, "k_max = %d, need k_max >= 1", k_max);
+    if (l_pad < 0) return fail(EMS_ERR_INVALID_ARG, "l_pad = %d, need l_pad >= 0", l_pad);
+    if (cap < l_pad || cap < kTileKeys || (cap % kTileKeys) != 0)
+        return fail(EMS_ERR_INVALID_ARG, "cap = %lld must be a multiple of %d and at least l_pad",
+                    (long long)cap, kTileKeys);
+    if (!key_mask || !k_valid) return fail(EMS_ERR_INVALID_ARG, "key_mask and k_valid must not be NULL");
+    if (reinterpret_cast<uintptr_t>(key_mask) & 3u)
+        return fail(EMS_ERR_INVALID_ARG, "key_mask must be 4-byte aligned");
+    if (B >= 1 && cache && cache->rows < (int64_t)B * cap)
+        return fail(EMS_ERR_INVALID_ARG, "cache holds %lld rows, B * cap = %lld needed",
+                    (long long)cache->rows, (long long)B * cap);
+    if (B >= 1 && (int64_t)B * k_max > 0x7fffffff) return fail(EMS_ERR_UNSUPPORTED, "B * k_max too large");
+    PaddedArgs pad{key_mask, k_valid, k_max, l_pad, cap};
+    return run_attention(q_pad, k_new_pad, v_new_pad, cache, nullptr, nullptr, nullptr, out_pad,
+                         out_dtype, B, B >= 1 ? B * k_max : 0, H, D, k_max, l_pad, scale, dtype,
+                         workspace, workspace_bytes, hip_stream, &pad);
 }
 
 size_t ems_accept_workspace_bytes(int T, int V) {
@@ -288,6 +348,64 @@ ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_n
     if (lengths_pending) {
         hipError_t e = ems::launch_advance_kv_len(kv_len, accepted, kv_len_out, B, stream);
         if (e != hipSuccess) return hip_fail("ems_kv_append length update launch", e);
+    }
+    return EMS_OK;
+}
+
+ems_status ems_padded_kv_append(const void* const* k_new_pad_layers,
+                                const void* const* v_new_pad_layers, const ems_kv_cache* caches,
+                                int n_layers, int64_t cap, uint8_t* key_mask,
+                                const int32_t* accepted, int B, int k_max, int l_pad, int tau_max,
+                                int H, int D, ems_dtype dtype, void* hip_stream) {
+    if (n_layers < 1) return fail(EMS_ERR_INVALID_ARG, "n_layers = %d, need n_layers >= 1", n_layers);
+    if (B < 1 || B > 65535 * 32) return fail(EMS_ERR_INVALID_ARG, "B = %d out of range", B);
+    if (H < 1) return fail(EMS_ERR_INVALID_ARG, "H = %d, need H >= 1", H);
+    if (D < 8 || (D & 7)) return fail(EMS_ERR_INVALID_ARG, "D = %d, need a positive multiple of 8", D);
+    if (!dtype16(dtype)) return fail(EMS_ERR_INVALID_ARG, "dtype must be EMS_F16 or EMS_BF16");
+    if (k_max < 1 || tau_max < 0 || tau_max > k_max)
+        return fail(EMS_ERR_INVALID_ARG, "need 0 <= tau_max (%d) <= k_max (%d)", tau_max, k_max);
+    if (l_pad < 0 || cap < (int64_t)l_pad + tau_max)
+        return fail(EMS_ERR_INVALID_ARG, "l_pad + tau_max = %lld exceeds cap = %lld",
+                    (long long)l_pad + tau_max, (long long)cap);
+    if (!k_new_pad_layers || !v_new_pad_layers || !caches || !key_mask || !accepted)
+        return fail(EMS_ERR_INVALID_ARG, "NULL argument");
+    for (int l = 0; l < n_layers; ++l) {
+        const ems_kv_cache& c = caches[l];
+        if (!k_new_pad_layers[l] || !v_new_pad_layers[l] || !c.k || !c.v)
+            return fail(EMS_ERR_INVALID_ARG, "layer %d: NULL tensor", l);
+        if (!aligned16(k_new_pad_layers[l]) || !aligned16(v_new_pad_layers[l]) || !aligned16(c.k) || !aligned16(c.v))
+            return fail(EMS_ERR_INVALID_ARG, "layer %d: tensors must be 16-byte aligned", l);
+        if (c.row_stride < D || c.head_stride < D || (c.row_stride & 7) || (c.head_stride & 7))
+            return fail(EMS_ERR_INVALID_ARG, "layer %d: cache strides must be multiples of 8 elements and at least D", l);
+        if (c.rows < (int64_t)B * cap)
+            return fail(EMS_ERR_INVALID_ARG, "layer %d: cache holds fewer than B * cap rows", l);
+    }
+    if (tau_max == 0) return EMS_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    for (int l0 = 0; l0 < n_layers; l0 += ems::kMaxLayersPerLaunch) {
+        ems::PaddedAppendParams p;
+        std::memset(&p, 0, sizeof p);
+        p.n_layers = std::min(ems::kMaxLayersPerLaunch, n_layers - l0);
+        for (int l = 0; l < p.n_layers; ++l) {
+            ems::AppendLayer& ly = p.layer[l];
+            ly.k_new = static_cast<const char*>(k_new_pad_layers[l0 + l]);
+            ly.v_new = static_cast<const char*>(v_new_pad_layers[l0 + l]);
+            ly.k_cache = static_cast<char*>(caches[l0 + l].k);
+            ly.v_cache = static_cast<char*>(caches[l0 + l].v);
+            ly.row_stride_b = caches[l0 + l].row_stride * 2;
+            ly.head_stride_b = caches[l0 + l].head_stride * 2;
+        }
+        p.key_mask = key_mask;
+        p.accepted = accepted;
+        p.B = B;
+        p.H = H;
+        p.vec_per_head = D / 8;
+        p.k_max = k_max;
+        p.l_pad = l_pad;
+        p.tau_max = tau_max;
+        p.cap = cap;
+        hipError_t e = ems::launch_padded_kv_append(p, stream);
+        if (e != hipSuccess) return hip_fail("ems_padded_kv_append launch", e);
     }
     return EMS_OK;
 }

@@ -28,11 +28,17 @@ struct AttnParams {
     int B, H;
     int num_waves;
     float scale_log2;          // scale * log2(e)
+    // padded ("vanilla") ablation only: every sample has k_max rows and an aligned cache of
+    // l_pad rows at row i*cap, with a byte mask [B, cap] of real (1) and padding (0) keys
+    const uint8_t* key_mask;
+    const int32_t* k_valid;    // [B] real rows among the k_max
+    int k_max, l_pad;
+    int64_t cap;
 };
 
 // ev_start / ev_stop (may be null) are recorded right before and right after the main
 // attention kernel, i.e. they exclude the partial-merge kernel.
-hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16,
+hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16, bool padded,
                                    hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 struct ArgmaxPartial {
@@ -79,7 +85,19 @@ struct AppendParams {
     int vec_per_head;          // D * 2 / 16
 };
 
+struct PaddedAppendParams {
+    AppendLayer layer[kMaxLayersPerLaunch];
+    int n_layers;
+    uint8_t* key_mask;         // [B, cap]
+    const int32_t* accepted;
+    int B, H;
+    int vec_per_head;
+    int k_max, l_pad, tau_max;
+    int64_t cap;
+};
+
 hipError_t launch_kv_append(const AppendParams& p, hipStream_t stream);
+hipError_t launch_padded_kv_append(const PaddedAppendParams& p, hipStream_t stream);
 hipError_t launch_advance_kv_len(const int32_t* kv_len, const int32_t* accepted,
                                  int32_t* kv_len_out, int B, hipStream_t stream);
 

@@ -42,6 +42,32 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(AppendParams 
     }
 }
 
+// Padded ("vanilla") ablation, Sec. 3.1: every sample appends the same tau_max rows at the
+// aligned row l_pad; rows at or beyond the sample's own accepted count are padding and are
+// only marked as such in the key mask -- their K/V is still written, as the vanilla method does.
+__global__ __launch_bounds__(kAppendThreads) void padded_kv_append_kernel(PaddedAppendParams p) {
+    const int i = blockIdx.x;
+    const int acc = p.accepted[i];
+    if (blockIdx.y == 0)
+        for (int j = threadIdx.x; j < p.tau_max; j += kAppendThreads)
+            p.key_mask[(int64_t)i * p.cap + p.l_pad + j] = j < acc ? 1 : 0;
+    const AppendLayer& ly = p.layer[blockIdx.y >> 1];
+    const bool is_v = blockIdx.y & 1;
+    const int vph = p.vec_per_head;
+    const int row_vecs = p.H * vph;
+    const char* src = (is_v ? ly.v_new : ly.k_new) + (int64_t)i * p.k_max * row_vecs * 16;
+    char* dst = (is_v ? ly.v_cache : ly.k_cache) + ((int64_t)i * p.cap + p.l_pad) * ly.row_stride_b;
+    for (int v = threadIdx.x; v < row_vecs; v += kAppendThreads) {
+        const int h = v / vph;
+        const int c = v - h * vph;
+        const int64_t doff = (int64_t)h * ly.head_stride_b + c * 16;
+        for (int j = 0; j < p.tau_max; ++j) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(src + ((int64_t)j * row_vecs + v) * 16);
+            *reinterpret_cast<u32x4*>(dst + j * ly.row_stride_b + doff) = w;
+        }
+    }
+}
+
 __global__ void advance_kv_len_kernel(const int32_t* kv_len, const int32_t* accepted,
                                       int32_t* kv_len_out, int B) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -50,6 +76,12 @@ __global__ void advance_kv_len_kernel(const int32_t* kv_len, const int32_t* acce
 
 hipError_t launch_kv_append(const AppendParams& p, hipStream_t stream) {
     hipLaunchKernelGGL(kv_append_kernel, dim3(p.B, 2 * p.n_layers), dim3(kAppendThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_padded_kv_append(const PaddedAppendParams& p, hipStream_t stream) {
+    hipLaunchKernelGGL(padded_kv_append_kernel, dim3(p.B, 2 * p.n_layers), dim3(kAppendThreads), 0,
+                       stream, p);
     return hipGetLastError();
 }
 

@@ -38,10 +38,12 @@ __device__ __forceinline__ int tiles_of_sample(int k, int L) {
 }
 
 // prefix[i] = H * sum_{j<i} tiles(j), i = 0..B, built by the whole block in LDS.
+template <bool PADDED>
 __device__ __forceinline__ void build_tile_prefix(const AttnParams& p, int32_t* prefix) {
     const int tid = threadIdx.x;
     for (int i = tid; i < p.B; i += blockDim.x)
-        prefix[i + 1] = p.H * tiles_of_sample(p.cu[i + 1] - p.cu[i], p.kv_len[i]);
+        prefix[i + 1] = PADDED ? p.H * tiles_of_sample(p.k_max, p.l_pad)
+                               : p.H * tiles_of_sample(p.cu[i + 1] - p.cu[i], p.kv_len[i]);
     if (tid == 0) prefix[0] = 0;
     __syncthreads();
     if (tid < kWave) {                        // one wave: inclusive scan, 64 entries a pass
@@ -68,6 +70,7 @@ struct TileRegs {
     typedef uint32_t vrow_t __attribute__((ext_vector_type(VW / 2)));
     u32x4 ka[KS], kb[KS];                    // keys 0..15 / 16..31 of the tile, A-operand layout
     vrow_t v[8];                             // this lane's 8 keys x VW head-dim elements
+    uint32_t mka, mkb;                       // padded ablation only: key-mask bytes of this lane's keys
 };
 
 // Where the 32 keys of one tile live: a run of rows of `row_bytes` starting at kbase/vbase
@@ -77,9 +80,10 @@ struct TileSrc {
     uint64_t kbase, vbase;   // wave-uniform
     uint32_t row_bytes;
     int n0, last;
+    uint64_t mask_base;      // padded ablation only: key-mask row of the sample, 0 = no mask bytes
 };
 
-template <int D>
+template <int D, bool PADDED>
 __device__ __forceinline__ void load_tile(TileRegs<D>& t, const TileSrc& src, int n, int g) {
     constexpr int KS = TileRegs<D>::KS;
     constexpr int VW = TileRegs<D>::VW;
@@ -96,6 +100,13 @@ __device__ __forceinline__ void load_tile(TileRegs<D>& t, const TileSrc& src, in
         const uint32_t off = (uint32_t)min(key, src.last) * src.row_bytes + (uint32_t)n * (VW * 2);
         t.v[e] = gload<typename TileRegs<D>::vrow_t>(src.vbase, off);
     }
+    if (PADDED) {
+        t.mka = t.mkb = 0x01010101u;
+        if (src.mask_base != 0) {            // wave-uniform
+            t.mka = gload<uint32_t>(src.mask_base, (uint32_t)(src.n0 + 4 * g));
+            t.mkb = gload<uint32_t>(src.mask_base, (uint32_t)(src.n0 + 16 + 4 * g));
+        }
+    }
 }
 
 template <typename ET> struct PSplit { static constexpr bool value = false; };
@@ -111,7 +122,7 @@ struct SoftmaxState {
 
 // One tile: scores, masked online softmax, PV.  `lim` = number of visible keys
 // of this tile for this lane's query row (>= 32 means no masking).
-template <typename ET, int D, bool MASKED>
+template <typename ET, int D, bool MASKED, bool PADDED = false>
 __device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* qb,
                                              SoftmaxState<ET, D>& st, float scale_log2, int lim,
                                              int g) {
@@ -132,16 +143,22 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* 
             if (4 * g + i >= lim) x[i] = -INFINITY;
             if (16 + 4 * g + i >= lim) x[4 + i] = -INFINITY;
         }
+        if (PADDED) {                        // padding keys of the aligned cache
+            if (((t.mka >> (8 * i)) & 0xffu) == 0) x[i] = -INFINITY;
+            if (((t.mkb >> (8 * i)) & 0xffu) == 0) x[4 + i] = -INFINITY;
+        }
     }
     float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
                      fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
     const float m_new = fmaxf(st.m, quad_max(mx));
-    // every tile holds at least one visible key for every row, so m_new is finite
-    const float alpha = fast_exp2(st.m - m_new);     // exp2(-inf) = 0 on the first tile
+    // Unpadded: every tile holds at least one visible key for every row, so m_new is
+    // finite.  Padded: a tile may be all padding; subtract 0 instead of -inf then.
+    const float m_sub = (PADDED && m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = fast_exp2(st.m - m_sub);     // exp2(-inf) = 0 on the first tile
     float psum = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        x[i] = fast_exp2(x[i] - m_new);
+        x[i] = fast_exp2(x[i] - m_sub);
         psum += x[i];
     }
     st.l = st.l * alpha + psum;
@@ -182,12 +199,12 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* 
     }
 }
 
-template <typename ET, int D>
+template <typename ET, int D, bool PADDED>
 __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnParams p) {
     extern __shared__ int32_t prefix[];
     constexpr int KS = TileRegs<D>::KS;
     constexpr int VW = TileRegs<D>::VW;
-    build_tile_prefix(p, prefix);
+    build_tile_prefix<PADDED>(p, prefix);
     if (blockIdx.x == 0)       // the merge kernel reads the tile prefix from the workspace header
         for (int i = threadIdx.x; i <= p.B; i += blockDim.x) p.ws_header[i] = prefix[i];
     const int total = prefix[p.B];
@@ -211,10 +228,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
 
     while (gpos < gend) {
         while (uniform(prefix[i + 1]) <= gpos) ++i;
-        const int cu_i = uniform(p.cu[i]);
-        const int k = uniform(p.cu[i + 1]) - cu_i;
-        const int L = uniform(p.kv_len[i]);
-        const int64_t start = uniform(p.kv_start[i]);
+        // padded ablation: k_max rows and l_pad aligned cache rows for every sample
+        const int cu_i = PADDED ? i * p.k_max : uniform(p.cu[i]);
+        const int k = PADDED ? p.k_max : uniform(p.cu[i + 1]) - cu_i;
+        const int L = PADDED ? p.l_pad : uniform(p.kv_len[i]);
+        const int64_t start = PADDED ? (int64_t)i * p.cap : (int64_t)uniform(p.kv_start[i]);
+        const int k_real = PADDED ? uniform(p.k_valid[i]) : k;
         const int ntc = (L + kTileKeys - 1) / kTileKeys;
         const int nt = ntc + 1;
         const int rem = gpos - uniform(prefix[i]);
@@ -230,6 +249,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
         cache_src.vbase = uniform_addr(p.v_cache + cache_off);
         cache_src.row_bytes = (uint32_t)p.row_stride_b;
         cache_src.last = L - 1;
+        cache_src.mask_base = PADDED ? uniform_addr(p.key_mask + (int64_t)i * p.cap) : 0;
+        new_src.mask_base = 0;
         new_src.kbase = uniform_addr(p.k_new + new_off);
         new_src.vbase = uniform_addr(p.v_new + new_off);
         new_src.row_bytes = new_row_bytes;
@@ -255,23 +276,24 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
         st.l = 0.f;
 
         // visible keys of the new-token tile for this lane's row: itself and the rows before it
-        const int lim_new = min(k, n + 1);
+        // (padded: rows and keys at or beyond k_real are padding; padding rows see the real keys)
+        const int lim_new = min(k_real, n + 1);
 
         auto issue = [&](TileRegs<D>& t, int tile) {
             TileSrc src = cache_src;
             src.n0 = tile * kTileKeys;
             if (tile >= ntc) src = new_src;          // wave-uniform choice
-            load_tile<D>(t, src, n, g);
+            load_tile<D, PADDED>(t, src, n, g);
         };
         auto consume = [&](const TileRegs<D>& t, int tile) {
             if (tile < ntc) {
                 const int lim = L - tile * kTileKeys;
-                if (lim >= kTileKeys)
+                if (lim >= kTileKeys && !PADDED)
                     compute_tile<ET, D, false>(t, qb, st, p.scale_log2, lim, g);
                 else
-                    compute_tile<ET, D, true>(t, qb, st, p.scale_log2, lim, g);
+                    compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim, g);
             } else {
-                compute_tile<ET, D, true>(t, qb, st, p.scale_log2, lim_new, g);
+                compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim_new, g);
             }
         };
 
@@ -341,11 +363,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
 // waves.  Grid (H, B), 256 threads: D/4 lanes per output row, 4 columns per lane.
 constexpr int kCombineThreads = 256;
 
-template <typename ET, int D>
+template <typename ET, int D, bool PADDED>
 __global__ __launch_bounds__(kCombineThreads) void combine_partials_kernel(AttnParams p) {
     const int i = blockIdx.y, h = blockIdx.x;
-    const int cu_i = p.cu[i];
-    const int k = p.cu[i + 1] - cu_i;
+    const int cu_i = PADDED ? i * p.k_max : p.cu[i];
+    const int k = PADDED ? p.k_max : p.cu[i + 1] - cu_i;
     if (k <= 0) return;
     const int total = p.ws_header[p.B];
     const int per = (total + p.num_waves - 1) / p.num_waves;
@@ -386,28 +408,35 @@ __global__ __launch_bounds__(kCombineThreads) void combine_partials_kernel(AttnP
     }
 }
 
-template <typename ET, int D>
+template <typename ET, int D, bool PADDED>
 static hipError_t launch_typed(const AttnParams& p, int blocks, hipStream_t stream,
                                hipEvent_t ev_start, hipEvent_t ev_stop) {
     const size_t lds = (size_t)(p.B + 1) * sizeof(int32_t);
     hipError_t e;
     if (ev_start && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((verify_attention_kernel<ET, D>), dim3(blocks), dim3(kAttnThreads), lds,
-                       stream, p);
+    hipLaunchKernelGGL((verify_attention_kernel<ET, D, PADDED>), dim3(blocks), dim3(kAttnThreads),
+                       lds, stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((combine_partials_kernel<ET, D>), dim3(p.H, p.B), dim3(kCombineThreads), 0,
-                       stream, p);
+    hipLaunchKernelGGL((combine_partials_kernel<ET, D, PADDED>), dim3(p.H, p.B),
+                       dim3(kCombineThreads), 0, stream, p);
     return hipGetLastError();
 }
 
-hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16,
+template <bool PADDED>
+static hipError_t launch_layout(const AttnParams& p, int blocks, int D, bool bf16,
+                                hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    if (D == 128) return bf16 ? launch_typed<BF16, 128, PADDED>(p, blocks, stream, ev_start, ev_stop)
+                              : launch_typed<F16, 128, PADDED>(p, blocks, stream, ev_start, ev_stop);
+    return bf16 ? launch_typed<BF16, 64, PADDED>(p, blocks, stream, ev_start, ev_stop)
+                : launch_typed<F16, 64, PADDED>(p, blocks, stream, ev_start, ev_stop);
+}
+
+hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16, bool padded,
                                    hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    if (D == 128) return bf16 ? launch_typed<BF16, 128>(p, blocks, stream, ev_start, ev_stop)
-                              : launch_typed<F16, 128>(p, blocks, stream, ev_start, ev_stop);
-    return bf16 ? launch_typed<BF16, 64>(p, blocks, stream, ev_start, ev_stop)
-                : launch_typed<F16, 64>(p, blocks, stream, ev_start, ev_stop);
+    return padded ? launch_layout<true>(p, blocks, D, bf16, stream, ev_start, ev_stop)
+                  : launch_layout<false>(p, blocks, D, bf16, stream, ev_start, ev_stop);
 }
 
 }  // namespace ems

@@ -247,3 +247,82 @@ def make_config(n: int, *, seed: int = BASE_SEED, device="cpu", layout: str = TO
                           rows=int(sum(caps)), layout=layout, V=V, vocab_for_ids=50272,
                           device=device, name=CONFIG_NAMES[5])
     raise ValueError("config %r" % n)
+
+
+@dataclasses.dataclass
+class PaddedBatch:
+    """The same batch laid out for the padded ("vanilla") method of Sec. 3.1."""
+    B: int
+    H: int
+    D: int
+    k_max: int
+    l_pad: int
+    cap: int
+    dtype: torch.dtype
+    scale: float
+    layout: str
+    rows: int
+    row_stride: int
+    head_stride: int
+    q_pad: torch.Tensor       # [B*k_max, H, D]
+    k_new_pad: torch.Tensor
+    v_new_pad: torch.Tensor
+    k_cache: torch.Tensor     # aligned arena of B*cap rows
+    v_cache: torch.Tensor
+    key_mask: torch.Tensor    # [B, cap] uint8, 1 = real key
+    k_valid: torch.Tensor     # [B] int32
+    real_rows: torch.Tensor   # [T] int64: padded row index of every packed row of the source batch
+
+
+def pad_batch(b: VerifyBatch, *, seed: int = 7, interleave: bool = True, extra_pad: int = 0) -> PaddedBatch:
+    """Re-lay an unpadded batch as the vanilla method would hold it: inputs padded to k_max
+    rows per sample, caches aligned to l_pad rows with padding keys scattered between the real
+    ones (as they accumulate over decoding steps, Table 1) and marked in a byte mask.
+    Padding rows and keys hold finite N(0,1) junk, as real padding tokens would."""
+    dev = b.q.device
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    cpu_gen = torch.Generator(device="cpu")
+    cpu_gen.manual_seed(seed)
+    cu = b.cu_seqlens.cpu().tolist()
+    kv_len = b.kv_len.cpu().tolist()
+    kv_start = b.kv_start.cpu().tolist()
+    k = [cu[i + 1] - cu[i] for i in range(b.B)]
+    k_max = max(max(k), 1)
+    l_pad = max(kv_len) + extra_pad
+    cap = ((l_pad + k_max + 31) // 32) * 32
+    rows = b.B * cap
+    rs, hs = strides_for(b.layout, rows, b.H, b.D)
+    src_k = arena_view(b.k_cache, b.layout, b.rows, b.H, b.D)
+    src_v = arena_view(b.v_cache, b.layout, b.rows, b.H, b.D)
+    k_cache = _randn((rows * b.H * b.D,), b.dtype, gen, dev)
+    v_cache = _randn((rows * b.H * b.D,), b.dtype, gen, dev)
+    dst_k = arena_view(k_cache, b.layout, rows, b.H, b.D)
+    dst_v = arena_view(v_cache, b.layout, rows, b.H, b.D)
+    key_mask = torch.zeros((b.B, cap), dtype=torch.uint8, device=dev)
+    q_pad = _randn((b.B * k_max, b.H, b.D), b.dtype, gen, dev)
+    k_new_pad = _randn((b.B * k_max, b.H, b.D), b.dtype, gen, dev)
+    v_new_pad = _randn((b.B * k_max, b.H, b.D), b.dtype, gen, dev)
+    real_rows = []
+    for i in range(b.B):
+        L = kv_len[i]
+        if interleave:
+            pos = torch.randperm(l_pad, generator=cpu_gen)[:L].sort().values
+        else:
+            pos = torch.arange(l_pad - L, l_pad)
+        pos_dev = pos.to(dev)
+        if L > 0:
+            dst_k[i * cap + pos_dev] = src_k[kv_start[i]:kv_start[i] + L]
+            dst_v[i * cap + pos_dev] = src_v[kv_start[i]:kv_start[i] + L]
+            key_mask[i, pos_dev] = 1
+        sl = slice(cu[i], cu[i + 1])
+        q_pad[i * k_max:i * k_max + k[i]] = b.q[sl]
+        k_new_pad[i * k_max:i * k_max + k[i]] = b.k_new[sl]
+        v_new_pad[i * k_max:i * k_max + k[i]] = b.v_new[sl]
+        real_rows += [i * k_max + j for j in range(k[i])]
+    return PaddedBatch(
+        B=b.B, H=b.H, D=b.D, k_max=k_max, l_pad=l_pad, cap=cap, dtype=b.dtype, scale=b.scale,
+        layout=b.layout, rows=rows, row_stride=rs, head_stride=hs, q_pad=q_pad,
+        k_new_pad=k_new_pad, v_new_pad=v_new_pad, k_cache=k_cache, v_cache=v_cache,
+        key_mask=key_mask, k_valid=torch.tensor(k, dtype=torch.int32, device=dev),
+        real_rows=torch.tensor(real_rows, dtype=torch.int64, device=dev))

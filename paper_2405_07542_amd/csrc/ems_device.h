@@ -68,6 +68,15 @@ __device__ __forceinline__ V gload(uint64_t base, uint32_t off) {
     return *reinterpret_cast<const __attribute__((address_space(1))) V*>(base + off);
 }
 
+// The same for data that is read exactly once (K/V cache rows, logits): a non-temporal load
+// does not displace reusable lines from the caches and streams measurably faster from HBM
+// on MI355X (a plain read kernel: ~7.0 TB/s with it, ~6.1 TB/s without).
+template <typename V>
+__device__ __forceinline__ V gload_stream(uint64_t base, uint32_t off) {
+    return __builtin_nontemporal_load(
+        reinterpret_cast<const __attribute__((address_space(1))) V*>(base + off));
+}
+
 // Reductions over the four lanes {n, n+16, n+32, n+48} that share one MFMA column,
 // with the gfx950 row-swap instructions (no LDS round trip): after the 16-lane swap
 // the two results hold rows (0,0,2,2) and (1,1,3,3), after the 32-lane swap the lower

@@ -91,14 +91,14 @@ __device__ __forceinline__ void load_tile(TileRegs<D>& t, const TileSrc& src, in
     const uint32_t rb = (uint32_t)min(src.n0 + 16 + n, src.last) * src.row_bytes + (uint32_t)g * 16u;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-        t.ka[s] = gload<u32x4>(src.kbase, ra + 64 * s);
-        t.kb[s] = gload<u32x4>(src.kbase, rb + 64 * s);
+        t.ka[s] = gload_stream<u32x4>(src.kbase, ra + 64 * s);
+        t.kb[s] = gload_stream<u32x4>(src.kbase, rb + 64 * s);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int key = src.n0 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
         const uint32_t off = (uint32_t)min(key, src.last) * src.row_bytes + (uint32_t)n * (VW * 2);
-        t.v[e] = gload<typename TileRegs<D>::vrow_t>(src.vbase, off);
+        t.v[e] = gload_stream<typename TileRegs<D>::vrow_t>(src.vbase, off);
     }
     if (PADDED) {
         t.mka = t.mkb = 0x01010101u;
@@ -199,6 +199,47 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* 
     }
 }
 
+// One (sample, head) pair's share of a wave's tile range; everything is wave-uniform.
+struct Segment {
+    int i, h;            // sample, head
+    int cu_i, k, k_real; // first packed row, rows, real rows (k_real < k only in the padded ablation)
+    int L, ntc, nt;      // cached keys, cache tiles, tiles (= ntc + 1: the new-token tile is last)
+    int t0, t1;          // this wave consumes tiles [t0, t1) of the pair
+    uint64_t kc, vc;     // cache rows of the pair: (first row of the sample, head h)
+    uint64_t kn, vn, qn; // packed new K / V / Q rows of the pair
+    uint64_t mask_base;  // padded ablation: key-mask row of the sample
+};
+
+// The segment that starts at flat tile index gpos (< gend); `i` is a sample at or before it.
+template <int D, bool PADDED>
+__device__ __forceinline__ Segment make_segment(const AttnParams& p, const int32_t* prefix, int i,
+                                                int gpos, int gend) {
+    Segment s;
+    while (uniform(prefix[i + 1]) <= gpos) ++i;
+    s.i = i;
+    // padded ablation: k_max rows and l_pad aligned cache rows for every sample
+    s.cu_i = PADDED ? i * p.k_max : uniform(p.cu[i]);
+    s.k = PADDED ? p.k_max : uniform(p.cu[i + 1]) - s.cu_i;
+    s.L = PADDED ? p.l_pad : uniform(p.kv_len[i]);
+    const int64_t start = PADDED ? (int64_t)i * p.cap : (int64_t)uniform(p.kv_start[i]);
+    s.k_real = PADDED ? uniform(p.k_valid[i]) : s.k;
+    s.ntc = (s.L + kTileKeys - 1) / kTileKeys;
+    s.nt = s.ntc + 1;
+    const int rem = gpos - uniform(prefix[i]);
+    s.h = uniform(rem / s.nt);
+    s.t0 = rem - s.h * s.nt;
+    s.t1 = min(s.nt, s.t0 + (gend - gpos));
+    const int64_t cache_off = start * p.row_stride_b + (int64_t)s.h * p.head_stride_b;
+    const int64_t new_off = ((int64_t)s.cu_i * p.H + s.h) * (D * 2);
+    s.kc = uniform_addr(p.k_cache + cache_off);
+    s.vc = uniform_addr(p.v_cache + cache_off);
+    s.kn = uniform_addr(p.k_new + new_off);
+    s.vn = uniform_addr(p.v_new + new_off);
+    s.qn = uniform_addr(p.q + new_off);
+    s.mask_base = PADDED ? uniform_addr(p.key_mask + (int64_t)i * p.cap) : 0;
+    return s;
+}
+
 template <typename ET, int D, bool PADDED>
 __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnParams p) {
     extern __shared__ int32_t prefix[];
@@ -210,111 +251,88 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
     const int total = prefix[p.B];
     const int per = (total + p.num_waves - 1) / p.num_waves;
     const int wave = uniform((int)(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)));
-    int gpos = wave * per;
-    const int gend = min(total, gpos + per);
-    if (gpos >= gend) return;
+    const int gbeg = wave * per;
+    const int gend = min(total, gbeg + per);
+    if (gbeg >= gend) return;
 
     const int lane = threadIdx.x & 63;
     const int n = lane & 15;       // query row (MFMA column) of this lane
     const int g = lane >> 4;       // which quarter of the k-slots / key rows
+    const uint32_t new_row_bytes = (uint32_t)p.H * (D * 2);
+    const uint32_t cache_row_bytes = (uint32_t)p.row_stride_b;
 
-    // sample of the first tile: prefix[i] <= gpos < prefix[i+1]
-    int lo = 0, hi = p.B;          // invariant: prefix[lo] <= gpos < prefix[hi]
+    // sample of the first tile: prefix[i] <= gbeg < prefix[i+1]
+    int lo = 0, hi = p.B;          // invariant: prefix[lo] <= gbeg < prefix[hi]
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (prefix[mid] <= gpos) lo = mid; else hi = mid;
+        if (prefix[mid] <= gbeg) lo = mid; else hi = mid;
     }
-    int i = uniform(lo);
 
-    while (gpos < gend) {
-        while (uniform(prefix[i + 1]) <= gpos) ++i;
-        // padded ablation: k_max rows and l_pad aligned cache rows for every sample
-        const int cu_i = PADDED ? i * p.k_max : uniform(p.cu[i]);
-        const int k = PADDED ? p.k_max : uniform(p.cu[i + 1]) - cu_i;
-        const int L = PADDED ? p.l_pad : uniform(p.kv_len[i]);
-        const int64_t start = PADDED ? (int64_t)i * p.cap : (int64_t)uniform(p.kv_start[i]);
-        const int k_real = PADDED ? uniform(p.k_valid[i]) : k;
-        const int ntc = (L + kTileKeys - 1) / kTileKeys;
-        const int nt = ntc + 1;
-        const int rem = gpos - uniform(prefix[i]);
-        const int h = uniform(rem / nt);
-        const int t0 = rem - h * nt;
-        const int t1 = min(nt, t0 + (gend - gpos));
+    // The wave walks its flat tile range [gbeg, gend).  `cur` is the pair being consumed,
+    // `nxt` the one after it (its index arrays are fetched a whole segment ahead); the loads
+    // of flat tile c+1 -- possibly the first tile of `nxt` -- are issued before tile c is
+    // consumed, so the stream of loads does not drain at a pair boundary.
+    Segment cur = make_segment<D, PADDED>(p, prefix, uniform(lo), gbeg, gend);
+    int cur_end = gbeg + (cur.t1 - cur.t0);            // flat index one past cur's last tile
+    Segment nxt = cur;
+    if (cur_end < gend) nxt = make_segment<D, PADDED>(p, prefix, cur.i, cur_end, gend);
 
-        const int64_t cache_off = start * p.row_stride_b + (int64_t)h * p.head_stride_b;
-        const int64_t new_off = ((int64_t)cu_i * p.H + h) * (D * 2);
-        const uint32_t new_row_bytes = (uint32_t)p.H * (D * 2);
-        TileSrc cache_src, new_src;
-        cache_src.kbase = uniform_addr(p.k_cache + cache_off);
-        cache_src.vbase = uniform_addr(p.v_cache + cache_off);
-        cache_src.row_bytes = (uint32_t)p.row_stride_b;
-        cache_src.last = L - 1;
-        cache_src.mask_base = PADDED ? uniform_addr(p.key_mask + (int64_t)i * p.cap) : 0;
-        new_src.mask_base = 0;
-        new_src.kbase = uniform_addr(p.k_new + new_off);
-        new_src.vbase = uniform_addr(p.v_new + new_off);
-        new_src.row_bytes = new_row_bytes;
-        new_src.n0 = 0;
-        new_src.last = k - 1;
+    u32x4 qb[KS];
+    SoftmaxState<ET, D> st;
+    int lim_new = 0;
 
+    auto begin_segment = [&](const Segment& s) {
         // Q^T as the B operand of S^T = K Q^T; rows beyond k_i are zero.
-        u32x4 qb[KS];
-        {
-            const uint64_t qbase = uniform_addr(p.q + new_off);
-            const uint32_t qoff = (uint32_t)min(n, k - 1) * new_row_bytes + (uint32_t)g * 16u;
+        const uint32_t qoff = (uint32_t)min(n, s.k - 1) * new_row_bytes + (uint32_t)g * 16u;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                const u32x4 z = {0u, 0u, 0u, 0u};
-                const u32x4 v = gload<u32x4>(qbase, qoff + 64 * s);
-                qb[s] = n < k ? v : z;
-            }
+        for (int ks = 0; ks < KS; ++ks) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            const u32x4 v = gload<u32x4>(s.qn, qoff + 64 * ks);
+            qb[ks] = n < s.k ? v : z;
         }
-        SoftmaxState<ET, D> st;
 #pragma unroll
         for (int c = 0; c < VW; ++c) st.acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
         st.m = -INFINITY;
         st.l = 0.f;
+        // visible keys of the new-token tile for this lane's row: itself and the rows before
+        // it (padded: rows and keys at or beyond k_real are padding; padding rows see the real keys)
+        lim_new = min(s.k_real, n + 1);
+    };
 
-        // visible keys of the new-token tile for this lane's row: itself and the rows before it
-        // (padded: rows and keys at or beyond k_real are padding; padding rows see the real keys)
-        const int lim_new = min(k_real, n + 1);
+    // Loads of tile `tile` of a pair described by plain values (never by a pointer to a
+    // Segment, so that both segments stay in scalar registers).
+    auto issue = [&](TileRegs<D>& t, int tile, int ntc, int L, int k, uint64_t kc, uint64_t vc,
+                     uint64_t kn, uint64_t vn, uint64_t mask_base) {
+        TileSrc src;
+        const bool is_new = tile >= ntc;                 // wave-uniform
+        src.kbase = is_new ? kn : kc;
+        src.vbase = is_new ? vn : vc;
+        src.row_bytes = is_new ? new_row_bytes : cache_row_bytes;
+        src.n0 = is_new ? 0 : tile * kTileKeys;
+        src.last = is_new ? k - 1 : L - 1;
+        src.mask_base = is_new ? 0 : mask_base;
+        load_tile<D, PADDED>(t, src, n, g);
+    };
 
-        auto issue = [&](TileRegs<D>& t, int tile) {
-            TileSrc src = cache_src;
-            src.n0 = tile * kTileKeys;
-            if (tile >= ntc) src = new_src;          // wave-uniform choice
-            load_tile<D, PADDED>(t, src, n, g);
-        };
-        auto consume = [&](const TileRegs<D>& t, int tile) {
-            if (tile < ntc) {
-                const int lim = L - tile * kTileKeys;
-                if (lim >= kTileKeys && !PADDED)
-                    compute_tile<ET, D, false>(t, qb, st, p.scale_log2, lim, g);
-                else
-                    compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim, g);
-            } else {
-                compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim_new, g);
-            }
-        };
-
-        TileRegs<D> ta, tb;
-        issue(ta, t0);
-        for (int t = t0; t < t1; t += 2) {
-            if (t + 1 < t1) issue(tb, t + 1);
-            consume(ta, t);
-            if (t + 1 < t1) {
-                if (t + 2 < t1) issue(ta, t + 2);
-                consume(tb, t + 1);
-            }
+    auto consume = [&](const TileRegs<D>& t, const Segment& s, int tile) {
+        if (tile < s.ntc) {
+            const int lim = s.L - tile * kTileKeys;
+            if (lim >= kTileKeys && !PADDED)
+                compute_tile<ET, D, false>(t, qb, st, p.scale_log2, lim, g);
+            else
+                compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim, g);
+        } else {
+            compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim_new, g);
         }
+    };
 
+    auto finish_segment = [&](const Segment& s) {
         // the four lanes of a query row hold disjoint shares of the sum
         const float l = quad_sum(st.l);
-
-        if (t0 == 0 && t1 == nt) {
-            if (n < k) {
+        if (s.t0 == 0 && s.t1 == s.nt) {
+            if (n < s.k) {
                 const float inv = 1.0f / l;
-                const int64_t row = ((int64_t)(cu_i + n) * p.H + h) * D;
+                const int64_t row = ((int64_t)(s.cu_i + n) * p.H + s.h) * D;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int d0 = (4 * g + r) * VW;
@@ -338,8 +356,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
         } else {
             // partial: slot 2w holds a range that continues a pair begun by an earlier
             // wave, slot 2w+1 one that starts a pair and leaves its end to later waves
-            const int slot = 2 * wave + (t0 == 0 ? 1 : 0);
-            if (n < k) {
+            const int slot = 2 * wave + (s.t0 == 0 ? 1 : 0);
+            if (n < s.k) {
                 float* dst = p.ws + ((int64_t)slot * 16 + n) * (D + kPartialPad);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -355,7 +373,39 @@ __global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnP
                 }
             }
         }
-        gpos += t1 - t0;
+    };
+
+    int con_t = cur.t0;              // tile of `cur` that is consumed next
+
+    // One step of the walk: issue flat tile c+1 into `fill`, consume flat tile c from `use`.
+    auto step = [&](int c, const TileRegs<D>& use, TileRegs<D>& fill) {
+        if (c + 1 < gend) {
+            const bool same = con_t + 1 < cur.t1;        // else: first tile of the next pair
+            issue(fill, same ? con_t + 1 : nxt.t0, same ? cur.ntc : nxt.ntc, same ? cur.L : nxt.L,
+                  same ? cur.k : nxt.k, same ? cur.kc : nxt.kc, same ? cur.vc : nxt.vc,
+                  same ? cur.kn : nxt.kn, same ? cur.vn : nxt.vn,
+                  same ? cur.mask_base : nxt.mask_base);
+        }
+        consume(use, cur, con_t);
+        ++con_t;
+        if (con_t == cur.t1) {
+            finish_segment(cur);
+            if (c + 1 < gend) {
+                cur = nxt;
+                con_t = cur.t0;
+                cur_end = c + 1 + (cur.t1 - cur.t0);
+                begin_segment(cur);
+                if (cur_end < gend) nxt = make_segment<D, PADDED>(p, prefix, cur.i, cur_end, gend);
+            }
+        }
+    };
+
+    TileRegs<D> ta, tb;
+    begin_segment(cur);
+    issue(ta, cur.t0, cur.ntc, cur.L, cur.k, cur.kc, cur.vc, cur.kn, cur.vn, cur.mask_base);
+    for (int c = gbeg; c < gend; c += 2) {
+        step(c, ta, tb);
+        if (c + 1 < gend) step(c + 1, tb, ta);
     }
 }
 

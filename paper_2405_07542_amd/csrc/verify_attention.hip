@@ -241,7 +241,7 @@ __device__ __forceinline__ Segment make_segment(const AttnParams& p, const int32
 }
 
 template <typename ET, int D, bool PADDED>
-__global__ __launch_bounds__(kAttnThreads, 2) void verify_attention_kernel(AttnParams p) {
+__global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnParams p) {
     extern __shared__ int32_t prefix[];
     constexpr int KS = TileRegs<D>::KS;
     constexpr int VW = TileRegs<D>::VW;

@@ -34,9 +34,9 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptPa
     float best = widen(ET{}, base[c0]);
     int32_t arg = c0;
     if ((p.V & 7) == 0) {
-        const u32x4* vec = reinterpret_cast<const u32x4*>(base);
-        for (int v = (c0 >> 3) + tid; v < (c1 >> 3); v += kArgmaxThreads) {
-            const u32x4 w = vec[v];
+        // 16-byte non-temporal loads (the logits are read once), two per thread in flight
+        const uint64_t rowaddr = (uint64_t)base;
+        auto scan8 = [&](const u32x4 w, int v) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const uint16_t bits = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
@@ -46,7 +46,16 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptPa
                     arg = v * 8 + e;
                 }
             }
+        };
+        const int v1 = c1 >> 3;
+        int v = (c0 >> 3) + tid;
+        for (; v + kArgmaxThreads < v1; v += 2 * kArgmaxThreads) {
+            const u32x4 wa = gload_stream<u32x4>(rowaddr, (uint32_t)v * 16u);
+            const u32x4 wb = gload_stream<u32x4>(rowaddr, (uint32_t)(v + kArgmaxThreads) * 16u);
+            scan8(wa, v);
+            scan8(wb, v + kArgmaxThreads);
         }
+        if (v < v1) scan8(gload_stream<u32x4>(rowaddr, (uint32_t)v * 16u), v);
     } else {
         for (int c = c0 + tid; c < c1; c += kArgmaxThreads) {
             const float y = widen(ET{}, base[c]);

@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--no-logits", action="store_true", help="skip the [T,V] arg-max (ids given)")
     ap.add_argument("--breakdown", action="store_true", help="also time each call on its own")
     ap.add_argument("--no-ablation", action="store_true", help="skip the padded (vanilla) ablation")
+    ap.add_argument("--layers", type=int, default=32, help="config 5 only: layers of the verify loop")
+    ap.add_argument("--loop-steps", type=int, default=20, help="config 5 only: successive verify steps")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the bench: run a plain device copy of MIB MiB five times "
                          "(the known-size kernel that scales rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -104,6 +106,9 @@ def main():
         return
     n = args.config
     with_logits = not args.no_logits
+    if n == 5:
+        print(json.dumps(verify_loop_bench(args, with_logits)), flush=True)
+        return
 
     sets = []
     for v in range(args.sets):
@@ -211,6 +216,80 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(sets[0]["b"], with_logits)
     print(json.dumps(result), flush=True)
+
+
+def verify_loop_bench(args, with_logits):
+    """BASELINE config 5: a 32-layer OPT-6.7b-shaped verify loop, B=128, 20 successive steps;
+    each step = attention per layer + accept + append into all layers' caches; the lengths
+    advance on the device.  `--steps` repetitions of the whole loop are timed (caches are
+    reset to their initial lengths between repetitions: appended rows are simply overwritten)."""
+    import numpy as np
+    import torch
+    import paper_2405_07542_amd as ems
+    from paper_2405_07542_amd.verify_loop import VerifyLoopRunner
+    from workloads import make_verify_loop
+    dev = "cuda:0"
+    loop = make_verify_loop(n_layers=args.layers, n_steps=args.loop_steps, device=dev, layout=args.layout,
+                            V=50272 if with_logits else 0)
+    kv_len = loop.kv_len0.clone()
+    runner = VerifyLoopRunner(k_caches=loop.k_caches, v_caches=loop.v_caches, row_stride=loop.row_stride,
+                              head_stride=loop.head_stride, rows=loop.rows, kv_start=loop.kv_start,
+                              kv_len=kv_len, H=loop.H, D=loop.D, V=loop.V, dtype=loop.dtype,
+                              scale=loop.scale, max_k=loop.max_k, max_kv_len=loop.max_kv_len,
+                              max_rows=max(st.T for st in loop.steps))
+    acc_total = torch.zeros((), dtype=torch.int64, device=dev)
+
+    def run_loop(count):
+        kv_len.copy_(loop.kv_len0)
+        for st in loop.steps:
+            runner.step(st.q, st.k_new, st.v_new, st.cu_seqlens, st.logits, st.input_ids,
+                        None if with_logits else st.target_ids)
+            if count:
+                acc_total.add_(runner.accepted_cu[-1])
+
+    reps = max(1, min(args.steps, 3))
+    run_loop(False)                                     # warm-up repetition
+    torch.cuda.synchronize()
+    lens_after = kv_len.clone()
+    ems.ems_profile_enable(reps * args.loop_steps * args.layers)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run_loop(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    attn_ms_total, launches = ems.ems_profile_read()
+    ems.ems_profile_enable(0)
+    n_steps = reps * args.loop_steps
+    ms_per_step = (t1 - t0) * 1e3 / n_steps
+    accepted = int(acc_total) / reps
+    rows = sum(st.T for st in loop.steps)
+    hd = loop.H * loop.D
+    # algorithmic bytes of all attention launches of one loop (lengths grow step by step)
+    lens = loop.kv_len0.cpu().numpy().astype(np.int64)
+    grown = lens_after.cpu().numpy().astype(np.int64) - lens
+    alg = 0.0
+    frac = np.linspace(0.0, 1.0, args.loop_steps, endpoint=False)
+    for s, st in enumerate(loop.steps):
+        L = lens + np.round(grown * frac[s])            # lengths at step s (linear in the step, +-1 row)
+        alg += (2 * L.sum() * hd * 2 + 4 * st.T * hd * 2 + (3 * loop.B + 1) * 4) * args.layers
+    attn_ms = attn_ms_total / max(1, launches)
+    achieved = alg / (args.loop_steps * args.layers) / (attn_ms * 1e-3) / 1e9
+    return {
+        "metric": "verified tokens/s (32-layer verify loop: attention per layer + greedy accept + KV append)",
+        "value": round(accepted / (ms_per_step * args.loop_steps * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": n_steps, "warmup": args.loop_steps, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "BASELINE config 5: %d-layer verify loop, B=128, %d successive steps" %
+                   (args.layers, args.loop_steps), "layout": args.layout, "layers": args.layers,
+                   "accepted_per_loop": accepted, "query_rows_per_loop": rows, "logits": with_logits,
+                   "cache_GB": round(2 * args.layers * loop.rows * hd * 2 / 1e9, 1)},
+        "query_tokens_per_s": round(rows / (ms_per_step * args.loop_steps * 1e-3), 1),
+        "roofline": {"bound": "hbm", "kernel": "verify_attention_kernel", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None, "algorithmic_bytes_per_launch": alg / (args.loop_steps * args.layers),
+                     "kernel_ms": round(attn_ms, 5), "launches_timed": launches},
+    }
 
 
 def padded_ablation(sets, args, with_logits, unpadded_alg_bytes, unpadded_ms):

@@ -111,8 +111,8 @@ EMS_API ems_status ems_verify_attention(
     float scale, ems_dtype dtype,
     void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Bytes of device workspace ems_greedy_accept needs (0 when logits == NULL is
- * intended, i.e. V == 0). */
+/* Bytes of device workspace ems_greedy_accept needs for up to T rows (0 when logits ==
+ * NULL is intended, i.e. V == 0); the figure for T also covers every smaller T. */
 EMS_API size_t ems_accept_workspace_bytes(int T, int V);
 
 /*

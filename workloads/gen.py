@@ -326,3 +326,91 @@ def pad_batch(b: VerifyBatch, *, seed: int = 7, interleave: bool = True, extra_p
         k_new_pad=k_new_pad, v_new_pad=v_new_pad, k_cache=k_cache, v_cache=v_cache,
         key_mask=key_mask, k_valid=torch.tensor(k, dtype=torch.int32, device=dev),
         real_rows=torch.tensor(real_rows, dtype=torch.int64, device=dev))
+
+
+@dataclasses.dataclass
+class LoopStep:
+    """Inputs of one verification step of a multi-layer loop (caches live elsewhere)."""
+    k: list                     # rows per sample
+    T: int
+    cu_seqlens: torch.Tensor    # [B+1] i32
+    q: list                     # per layer [T,H,D]
+    k_new: list
+    v_new: list
+    logits: Optional[torch.Tensor]
+    target_ids: torch.Tensor    # planted row maxima (or the given ids when logits is None)
+    input_ids: torch.Tensor
+
+
+@dataclasses.dataclass
+class VerifyLoop:
+    """BASELINE config 5: an n_layers-deep, several-steps-long verify loop over ragged caches."""
+    B: int
+    H: int
+    D: int
+    V: int
+    dtype: torch.dtype
+    scale: float
+    n_layers: int
+    rows: int
+    row_stride: int
+    head_stride: int
+    layout: str
+    kv_start: torch.Tensor      # [B] i32
+    kv_len0: torch.Tensor       # [B] i32 initial lengths
+    k_caches: list              # per layer flat arena
+    v_caches: list
+    steps: list                 # of LoopStep
+    max_k: int
+    max_kv_len: int             # upper bound over the whole loop
+
+
+def make_verify_loop(*, n_layers: int = 32, n_steps: int = 20, B: int = 128, H: int = 32, D: int = 128,
+                     V: int = 50272, seed: int = BASE_SEED + 5, device="cpu", layout: str = TOKEN_MAJOR,
+                     dtype: torch.dtype = torch.float16, mean_len: int = 1024, max_len: int = 4096,
+                     k_hi: int = 6, match_p: float = 0.7) -> VerifyLoop:
+    """Cached lengths geometric(mean_len) clipped to [16, max_len]; rows per sample U[1, k_hi]
+    redrawn every step; every sample's region has room for n_steps * k_hi more rows (rounded to
+    64) and the regions are packed back to back, which is what keeps 128 ragged caches x 32
+    layers within one GPU's memory."""
+    rng = np.random.default_rng(seed)
+    kv_len = np.clip(rng.geometric(1.0 / mean_len, B), 16, max_len).astype(np.int64)
+    caps = ((kv_len + n_steps * k_hi + 63) // 64) * 64
+    starts = np.concatenate([[0], np.cumsum(caps)[:-1]])
+    rows = int(caps.sum())
+    rs, hs = strides_for(layout, rows, H, D)
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    sent = SENTINEL_BITS[dtype]
+    k_caches, v_caches = [], []
+    for _ in range(n_layers):
+        pair = []
+        for _kv in range(2):
+            arena = torch.full((rows * H * D,), sent, dtype=torch.int16, device=dev).view(dtype)
+            view = arena_view(arena, layout, rows, H, D)
+            for i in range(B):
+                view[int(starts[i]):int(starts[i] + kv_len[i])] = _randn((int(kv_len[i]), H, D), dtype, gen, dev)
+            pair.append(arena)
+        k_caches.append(pair[0])
+        v_caches.append(pair[1])
+    steps = []
+    for s in range(n_steps):
+        k = rng.integers(1, k_hi + 1, B).tolist()
+        first = make_batch([1] * B, k, H=1, D=8, dtype=dtype, seed=seed + 100 + s, V=V,
+                           vocab_for_ids=50272, match_p=match_p, device=device)
+        T = first.T
+        steps.append(LoopStep(
+            k=k, T=T, cu_seqlens=first.cu_seqlens,
+            q=[_randn((T, H, D), dtype, gen, dev) for _ in range(n_layers)],
+            k_new=[_randn((T, H, D), dtype, gen, dev) for _ in range(n_layers)],
+            v_new=[_randn((T, H, D), dtype, gen, dev) for _ in range(n_layers)],
+            logits=first.logits, target_ids=first.target_ids, input_ids=first.input_ids))
+
+    def i32(a):
+        return torch.tensor(np.asarray(a, dtype=np.int32), dtype=torch.int32, device=dev)
+
+    return VerifyLoop(B=B, H=H, D=D, V=V, dtype=dtype, scale=float(np.float32(1.0 / np.sqrt(D))),
+                      n_layers=n_layers, rows=rows, row_stride=rs, head_stride=hs, layout=layout,
+                      kv_start=i32(starts), kv_len0=i32(kv_len), k_caches=k_caches, v_caches=v_caches,
+                      steps=steps, max_k=k_hi, max_kv_len=int(kv_len.max()) + n_steps * k_hi)

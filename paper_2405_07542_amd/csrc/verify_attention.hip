@@ -277,19 +277,23 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     Segment nxt = cur;
     if (cur_end < gend) nxt = make_segment<D, PADDED>(p, prefix, cur.i, cur_end, gend);
 
-    u32x4 qb[KS];
+    u32x4 qb[KS];                // Q^T of `cur` as the B operand of S^T = K Q^T
+    u32x4 qn[KS];                // the same for `nxt`, fetched a whole segment ahead
     SoftmaxState<ET, D> st;
     int lim_new = 0;
 
-    auto begin_segment = [&](const Segment& s) {
-        // Q^T as the B operand of S^T = K Q^T; rows beyond k_i are zero.
-        const uint32_t qoff = (uint32_t)min(n, s.k - 1) * new_row_bytes + (uint32_t)g * 16u;
+    // Q rows of pair (k rows at qaddr); rows beyond k are zero.
+    auto load_q = [&](u32x4* dst, uint64_t qaddr, int k) {
+        const uint32_t qoff = (uint32_t)min(n, k - 1) * new_row_bytes + (uint32_t)g * 16u;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const u32x4 z = {0u, 0u, 0u, 0u};
-            const u32x4 v = gload<u32x4>(s.qn, qoff + 64 * ks);
-            qb[ks] = n < s.k ? v : z;
+            const u32x4 v = gload<u32x4>(qaddr, qoff + 64 * ks);
+            dst[ks] = n < k ? v : z;
         }
+    };
+
+    auto begin_segment = [&](const Segment& s) {
 #pragma unroll
         for (int c = 0; c < VW; ++c) st.acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
         st.m = -INFINITY;
@@ -394,13 +398,22 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 cur = nxt;
                 con_t = cur.t0;
                 cur_end = c + 1 + (cur.t1 - cur.t0);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) qb[ks] = qn[ks];
                 begin_segment(cur);
-                if (cur_end < gend) nxt = make_segment<D, PADDED>(p, prefix, cur.i, cur_end, gend);
+                if (cur_end < gend) {
+                    nxt = make_segment<D, PADDED>(p, prefix, cur.i, cur_end, gend);
+                    load_q(qn, nxt.qn, nxt.k);
+                }
             }
         }
     };
 
     TileRegs<D> ta, tb;
+    load_q(qb, cur.qn, cur.k);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qn[ks] = qb[ks];
+    if (cur_end < gend) load_q(qn, nxt.qn, nxt.k);
     begin_segment(cur);
     issue(ta, cur.t0, cur.ntc, cur.L, cur.k, cur.kc, cur.vc, cur.kn, cur.vn, cur.mask_base);
     for (int c = gbeg; c < gend; c += 2) {

@@ -282,14 +282,19 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     SoftmaxState<ET, D> st;
     int lim_new = 0;
 
-    // Q rows of pair (k rows at qaddr); rows beyond k are zero.
+    // Q rows of a pair (k rows at qaddr), raw: rows beyond k repeat row k-1 and are zeroed
+    // by use_q when the pair becomes current -- touching the values here would make the wave
+    // wait for the load (and for every tile load issued before it) at once.
     auto load_q = [&](u32x4* dst, uint64_t qaddr, int k) {
         const uint32_t qoff = (uint32_t)min(n, k - 1) * new_row_bytes + (uint32_t)g * 16u;
 #pragma unroll
+        for (int ks = 0; ks < KS; ++ks) dst[ks] = gload<u32x4>(qaddr, qoff + 64 * ks);
+    };
+    auto use_q = [&](const u32x4* src, int k) {
+#pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const u32x4 z = {0u, 0u, 0u, 0u};
-            const u32x4 v = gload<u32x4>(qaddr, qoff + 64 * ks);
-            dst[ks] = n < k ? v : z;
+            qb[ks] = n < k ? src[ks] : z;
         }
     };
 
@@ -398,8 +403,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 cur = nxt;
                 con_t = cur.t0;
                 cur_end = c + 1 + (cur.t1 - cur.t0);
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) qb[ks] = qn[ks];
+                use_q(qn, cur.k);
                 begin_segment(cur);
                 if (cur_end < gend) {
                     nxt = make_segment<D, PADDED>(p, prefix, cur.i, cur_end, gend);
@@ -410,9 +414,8 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     };
 
     TileRegs<D> ta, tb;
-    load_q(qb, cur.qn, cur.k);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qn[ks] = qb[ks];
+    load_q(qn, cur.qn, cur.k);
+    use_q(qn, cur.k);
     if (cur_end < gend) load_q(qn, nxt.qn, nxt.k);
     begin_segment(cur);
     issue(ta, cur.t0, cur.ntc, cur.L, cur.k, cur.kc, cur.vc, cur.kn, cur.vn, cur.mask_base);

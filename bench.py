@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--no-logits", action="store_true", help="skip the [T,V] arg-max (ids given)")
     ap.add_argument("--breakdown", action="store_true", help="also time each call on its own")
     ap.add_argument("--no-ablation", action="store_true", help="skip the padded (vanilla) ablation")
+    ap.add_argument("--write-through", action="store_true",
+                    help="paper-order variant: attention also stores the new rows' K/V, append only advances lengths")
     ap.add_argument("--layers", type=int, default=32, help="config 5 only: layers of the verify loop")
     ap.add_argument("--loop-steps", type=int, default=20, help="config 5 only: successive verify steps")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -133,7 +135,7 @@ def main():
         b = st["b"]
         ems.ems_verify_attention(b.q, b.k_new, b.v_new, st["cache"], b.cu_seqlens, b.kv_start, b.kv_len,
                                  st["out"], max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale,
-                                 workspace=st["ws_attn"])
+                                 workspace=st["ws_attn"], write_through=args.write_through)
 
     def accept(st):
         b = st["b"]
@@ -142,6 +144,9 @@ def main():
 
     def append(st):
         b = st["b"]
+        if args.write_through:
+            ems.ems_kv_advance(b.kv_len, st["accepted"], st["new_len"])
+            return
         ems.ems_kv_append([b.k_new], [b.v_new], [st["cache"]], b.cu_seqlens, st["accepted"], b.kv_start,
                           b.kv_len, st["new_len"])
 
@@ -190,7 +195,8 @@ def main():
         "config": {"workload": "BASELINE config %d: %s" % (n, CONFIG_NAMES[n]), "layout": args.layout,
                    "B": sets[0]["b"].B, "H": sets[0]["b"].H, "D": sets[0]["b"].D,
                    "query_rows_per_step": rows_per_step, "accepted_per_step": accepted_per_step,
-                   "logits": with_logits, "buffer_sets": len(sets)},
+                   "logits": with_logits, "buffer_sets": len(sets),
+                   "variant": "write-through + advance" if args.write_through else "verify + append"},
         "query_tokens_per_s": round(rows_per_step / (ms_per_step * 1e-3), 1),
         "roofline": roofline,
     }

@@ -111,6 +111,29 @@ EMS_API ems_status ems_verify_attention(
     float scale, ems_dtype dtype,
     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Paper-order variant of the step (Sec. 3.2: "for each input token, we initially compute its
+ * KV cache and subsequently write it to memory based on the specified position for each
+ * sample"; afterwards the sample's location advances by its accepted count).
+ * ems_verify_attention_write_through computes exactly what ems_verify_attention computes and
+ * ALSO stores all k_i new rows' K/V into the cache at rows kv_start[i]+kv_len[i]+j, j < k_i
+ * (those rows must lie inside the sample's region and outside every other sample's).
+ * ems_kv_advance then replaces ems_kv_append: kv_len_out[i] = kv_len[i] + accepted[i]
+ * (kv_len_out may alias kv_len).  Rows at or beyond the new length hold the rejected
+ * drafts' K/V and are don't-care: the next step overwrites them.  The result on rows
+ * [0, kv_len+accepted) is bit-identical to verify + append.
+ */
+EMS_API ems_status ems_verify_attention_write_through(
+    const void* q, const void* k_new, const void* v_new,
+    const ems_kv_cache* cache,
+    const int32_t* cu_seqlens, const int32_t* kv_start, const int32_t* kv_len,
+    void* out, ems_dtype out_dtype,
+    int B, int T, int H, int D, int max_k, int max_kv_len,
+    float scale, ems_dtype dtype,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+EMS_API ems_status ems_kv_advance(
+    const int32_t* kv_len, const int32_t* accepted, int32_t* kv_len_out, int B, void* hip_stream);
+
 /* Bytes of device workspace ems_greedy_accept needs for up to T rows (0 when logits ==
  * NULL is intended, i.e. V == 0); the figure for T also covers every smaller T. */
 EMS_API size_t ems_accept_workspace_bytes(int T, int V);

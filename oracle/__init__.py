@@ -66,6 +66,9 @@ def _load():
         lib.oracle_padded_kv_append.argtypes = [
             u16p, u16p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, u8p, u16p, u16p, i32p,
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        lib.oracle_kv_write_through.argtypes = [
+            u16p, u16p, ctypes.c_int64, ctypes.c_int64, u16p, u16p, i32p, i32p, i32p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -227,3 +230,21 @@ def padded_kv_append(k_cache, v_cache, row_stride, head_stride, cap, key_mask, k
         int(head_stride), int(cap), _p(key_mask, ctypes.c_uint8), _p(k_new_pad, ctypes.c_uint16),
         _p(v_new_pad, ctypes.c_uint16), _p(acc, ctypes.c_int32), B, int(k_max), int(l_pad),
         int(tau_max), int(H), int(D))
+
+
+def kv_write_through(k_cache, v_cache, row_stride, head_stride, k_new, v_new, cu_seqlens, kv_start,
+                     kv_len, H, D) -> None:
+    """Paper order: all k_i new rows of every sample go to cache rows kv_len + j, in place."""
+    k_cache, v_cache = _u16(k_cache, True), _u16(v_cache, True)
+    k_new, v_new = _u16(k_new), _u16(v_new)
+    cu, ks, kl = _i32(cu_seqlens), _i32(kv_start), _i32(kv_len)
+    B = len(ks)
+    for i in range(B):
+        k = int(cu[i + 1] - cu[i])
+        if k > 0:
+            last = (int(ks[i]) + int(kl[i]) + k - 1) * row_stride + (H - 1) * head_stride + D - 1
+            assert last < k_cache.size and last < v_cache.size, "write-through beyond the arena"
+    _load().oracle_kv_write_through(
+        _p(k_cache, ctypes.c_uint16), _p(v_cache, ctypes.c_uint16), int(row_stride), int(head_stride),
+        _p(k_new, ctypes.c_uint16), _p(v_new, ctypes.c_uint16), _p(cu, ctypes.c_int32),
+        _p(ks, ctypes.c_int32), _p(kl, ctypes.c_int32), B, int(H), int(D))

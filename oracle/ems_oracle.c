@@ -353,3 +353,27 @@ int oracle_padded_kv_append(uint16_t* k_cache, uint16_t* v_cache, int64_t row_st
     }
     return 0;
 }
+
+/*
+ * Paper-order cache write (Sec. 3.2): before attention, the K/V of EVERY new row of sample i
+ * is written at the sample's own location, cache rows kv_start[i]+kv_len[i]+j for j < k_i;
+ * after verification only the location advances (kv_len += accepted).  Rows at or beyond
+ * the advanced length then hold rejected drafts and are don't-care.
+ */
+int oracle_kv_write_through(uint16_t* k_cache, uint16_t* v_cache, int64_t row_stride,
+                            int64_t head_stride, const uint16_t* k_new, const uint16_t* v_new,
+                            const int32_t* cu, const int32_t* kv_start, const int32_t* kv_len,
+                            int B, int H, int D) {
+    for (int i = 0; i < B; ++i) {
+        const int k = cu[i + 1] - cu[i];
+        for (int j = 0; j < k; ++j)
+            for (int h = 0; h < H; ++h)
+                for (int d = 0; d < D; ++d) {
+                    int64_t dst = ((int64_t)kv_start[i] + kv_len[i] + j) * row_stride + (int64_t)h * head_stride + d;
+                    int64_t src = (((int64_t)cu[i] + j) * H + h) * D + d;
+                    k_cache[dst] = k_new[src];
+                    v_cache[dst] = v_new[src];
+                }
+    }
+    return 0;
+}

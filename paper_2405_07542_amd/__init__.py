@@ -59,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.ems_verify_attention.argtypes = [vp, vp, vp, ctypes.POINTER(KvCacheStruct), vp, vp, vp,
                                            vp, i32, i32, i32, i32, i32, i32, i32,
                                            ctypes.c_float, i32, vp, sz, vp]
+        L.ems_verify_attention_write_through.restype = i32
+        L.ems_verify_attention_write_through.argtypes = L.ems_verify_attention.argtypes
+        L.ems_kv_advance.restype = i32
+        L.ems_kv_advance.argtypes = [vp, vp, vp, i32, vp]
         L.ems_greedy_accept.restype = i32
         L.ems_greedy_accept.argtypes = [vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
         L.ems_kv_append.restype = i32
@@ -113,11 +117,13 @@ def ems_accept_workspace_bytes(T: int, V: int) -> int:
 
 def ems_verify_attention(q, k_new, v_new, cache: KvCacheStruct, cu_seqlens, kv_start, kv_len,
                          out, *, max_k: int, max_kv_len: int, scale: float,
-                         workspace: torch.Tensor, stream=None) -> None:
-    """out[T,H,D] <- packed multi-token attention over the per-sample caches."""
+                         workspace: torch.Tensor, stream=None, write_through: bool = False) -> None:
+    """out[T,H,D] <- packed multi-token attention over the per-sample caches.
+    write_through=True calls ems_verify_attention_write_through (new rows' K/V also stored)."""
     T, H, D = q.shape
     B = kv_start.numel()
-    _check(lib().ems_verify_attention(
+    fn = lib().ems_verify_attention_write_through if write_through else lib().ems_verify_attention
+    _check(fn(
         _ptr(q), _ptr(k_new), _ptr(v_new), ctypes.byref(cache), _ptr(cu_seqlens), _ptr(kv_start),
         _ptr(kv_len), _ptr(out), _DT[out.dtype], B, T, H, D, int(max_k), int(max_kv_len),
         float(scale), _DT[q.dtype], _ptr(workspace), workspace.numel() * workspace.element_size(),
@@ -151,6 +157,15 @@ def ems_kv_append(k_new_layers: Sequence[torch.Tensor], v_new_layers: Sequence[t
     _check(lib().ems_kv_append(karr, varr, carr, n, _ptr(cu_seqlens), _ptr(accepted),
                                _ptr(kv_start), _ptr(kv_len), _ptr(kv_len_out), B, T, H, D,
                                _DT[k_new_layers[0].dtype], _stream(stream)))
+
+
+def ems_verify_attention_write_through(q, k_new, v_new, cache, cu_seqlens, kv_start, kv_len, out, **kw) -> None:
+    ems_verify_attention(q, k_new, v_new, cache, cu_seqlens, kv_start, kv_len, out, write_through=True, **kw)
+
+
+def ems_kv_advance(kv_len, accepted, kv_len_out, stream=None) -> None:
+    _check(lib().ems_kv_advance(_ptr(kv_len), _ptr(accepted), _ptr(kv_len_out), kv_len.numel(),
+                                _stream(stream)))
 
 
 def ems_validate_inputs(cu_seqlens, kv_start, kv_len, *, T: int, max_k: int, max_kv_len: int,
@@ -198,6 +213,6 @@ def ems_profile_read():
     return ms.value, n.value
 
 
-__all__ = ["ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
+__all__ = ["ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
            "ems_accept_workspace_bytes", "ems_verify_attention", "ems_greedy_accept",
            "ems_kv_append", "ems_validate_inputs", "EMS_F16", "EMS_BF16", "EMS_F32"]

@@ -122,7 +122,8 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
                          const int32_t* kv_start, const int32_t* kv_len, void* out,
                          ems_dtype out_dtype, int B, int T, int H, int D, int max_k,
                          int max_kv_len, float scale, ems_dtype dtype, void* workspace,
-                         size_t workspace_bytes, void* hip_stream, const PaddedArgs* pad) {
+                         size_t workspace_bytes, void* hip_stream, const PaddedArgs* pad,
+                         bool write_through = false) {
     if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
     if (T < 0) return fail(EMS_ERR_INVALID_ARG, "T = %d, need T >= 0", T);
     if (H < 1) return fail(EMS_ERR_INVALID_ARG, "H = %d, need H >= 1", H);
@@ -181,6 +182,7 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     p.H = H;
     p.num_waves = blocks * kWavesPerBlock;
     p.scale_log2 = scale * 1.4426950408889634f;
+    p.write_through = write_through ? 1 : 0;
     if (pad) {
         p.key_mask = pad->key_mask;
         p.k_valid = pad->k_valid;
@@ -213,6 +215,31 @@ ems_status ems_verify_attention(const void* q, const void* k_new, const void* v_
     return run_attention(q, k_new, v_new, cache, cu_seqlens, kv_start, kv_len, out, out_dtype, B, T,
                          H, D, max_k, max_kv_len, scale, dtype, workspace, workspace_bytes,
                          hip_stream, nullptr);
+}
+
+ems_status ems_verify_attention_write_through(const void* q, const void* k_new, const void* v_new,
+                                              const ems_kv_cache* cache, const int32_t* cu_seqlens,
+                                              const int32_t* kv_start, const int32_t* kv_len,
+                                              void* out, ems_dtype out_dtype, int B, int T, int H,
+                                              int D, int max_k, int max_kv_len, float scale,
+                                              ems_dtype dtype, void* workspace,
+                                              size_t workspace_bytes, void* hip_stream) {
+    if (cache && T > 0 && (!cache->k || !cache->v))
+        return fail(EMS_ERR_INVALID_ARG, "cache arenas must not be NULL");
+    return run_attention(q, k_new, v_new, cache, cu_seqlens, kv_start, kv_len, out, out_dtype, B, T,
+                         H, D, max_k, max_kv_len, scale, dtype, workspace, workspace_bytes,
+                         hip_stream, nullptr, true);
+}
+
+ems_status ems_kv_advance(const int32_t* kv_len, const int32_t* accepted, int32_t* kv_len_out, int B,
+                          void* hip_stream) {
+    if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
+    if (!kv_len || !accepted || !kv_len_out)
+        return fail(EMS_ERR_INVALID_ARG, "kv_len, accepted and kv_len_out must not be NULL");
+    hipError_t e = ems::launch_advance_kv_len(kv_len, accepted, kv_len_out, B,
+                                              static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail("ems_kv_advance launch", e);
+    return EMS_OK;
 }
 
 ems_status ems_padded_verify_attention(const void* q_pad, const void* k_new_pad,

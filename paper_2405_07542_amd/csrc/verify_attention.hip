@@ -332,6 +332,26 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim, g);
         } else {
             compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim_new, g);
+            if (!PADDED && p.write_through) {
+                // Paper order (Sec. 3.2): the new rows' K/V go to the sample's own location,
+                // cache rows kv_len + j, j < k_i, straight from the registers of this tile.
+                // Exactly one wave holds the new-token tile of a (sample, head) pair.
+                const uint32_t row_b = cache_row_bytes;
+                if (n < s.k) {
+                    char* kdst = reinterpret_cast<char*>(s.kc) + (uint64_t)(uint32_t)(s.L + n) * row_b + g * 16;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        *reinterpret_cast<u32x4*>(kdst + 64 * ks) = t.ka[ks];
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int key = 4 * g + e;
+                    if (key < s.k) {
+                        char* vdst = reinterpret_cast<char*>(s.vc) + (uint64_t)(uint32_t)(s.L + key) * row_b + n * (VW * 2);
+                        *reinterpret_cast<typename TileRegs<D>::vrow_t*>(vdst) = t.v[e];
+                    }
+                }
+            }
         }
     };
 

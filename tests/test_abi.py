@@ -134,3 +134,16 @@ def test_validate_inputs_rejects_bad_scalars_on_the_host():
     L = ems.lib()
     assert L.ems_validate_inputs(FAKE, FAKE, FAKE, 0, 0, 1, 1, 10, None) == ems.EMS_ERR_INVALID_ARG
     assert L.ems_validate_inputs(None, FAKE, FAKE, 1, 0, 1, 1, 10, None) == ems.EMS_ERR_INVALID_ARG
+
+
+def test_write_through_and_advance_reject_bad_arguments_on_the_host():
+    L = ems.lib()
+    assert L.ems_kv_advance(FAKE, FAKE, FAKE, 0, None) == ems.EMS_ERR_INVALID_ARG
+    assert L.ems_kv_advance(None, FAKE, FAKE, 4, None) == ems.EMS_ERR_INVALID_ARG
+    cache = ems.KvCacheStruct(FAKE, FAKE, 4096, 128, 1024)
+    args = [FAKE, FAKE, FAKE, ctypes.byref(cache), FAKE, FAKE, FAKE, FAKE, ems.EMS_F16, 4, 8, 32, 80, 4,
+            100, 0.1, ems.EMS_F16, FAKE, 1 << 30, None]
+    assert L.ems_verify_attention_write_through(*args) == ems.EMS_ERR_UNSUPPORTED     # D = 80
+    args[12] = 128
+    args[9] = 0
+    assert L.ems_verify_attention_write_through(*args) == ems.EMS_ERR_INVALID_ARG     # B = 0

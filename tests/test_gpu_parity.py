@@ -246,3 +246,34 @@ def test_verify_loop_of_several_steps():
         torch.cuda.synchronize()
         assert np.array_equal(g_len.cpu().numpy(), o_len)
         assert np.array_equal(bits(g_kc), o_kc) and np.array_equal(bits(g_vc), o_vc)
+
+
+@pytest.mark.parametrize("layout", [TOKEN_MAJOR, HEAD_MAJOR])
+@pytest.mark.parametrize("dtype,D", [(torch.float16, 128), (torch.bfloat16, 64)])
+def test_write_through_variant(layout, dtype, D):
+    """Paper order: the attention call also stores every new row's K/V at the sample's own
+    location; then only the lengths advance.  Output as for the plain call; cache bit-equal to
+    the oracle's write-through; untouched rows keep their sentinel."""
+    import paper_2405_07542_amd as ems
+    b_cpu = make_batch(RAGGED_KV, RAGGED_K, H=4, D=D, dtype=dtype, seed=48, capacity=300, layout=layout)
+    b = to_device(b_cpu)
+    kc, vc = b.k_cache.clone(), b.v_cache.clone()
+    out = torch.full((b.T, b.H, b.D), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len), dtype=torch.uint8, device="cuda")
+    ems.ems_verify_attention_write_through(b.q, b.k_new, b.v_new,
+                                           ems.kv_cache(kc, vc, b.row_stride, b.head_stride, b.rows),
+                                           b.cu_seqlens, b.kv_start, b.kv_len, out, max_k=b.max_k,
+                                           max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws)
+    _, acc, _, _ = hip_accept(b, use_logits=False)
+    lens = b.kv_len.clone()
+    ems.ems_kv_advance(lens, acc, lens)
+    torch.cuda.synchronize()
+    want = oracle_attention(b_cpu)
+    assert np.abs(out.double().cpu().numpy() - want).max() <= 2e-3
+    okc, ovc = bits(b_cpu.k_cache).copy(), bits(b_cpu.v_cache).copy()
+    oracle.kv_write_through(okc, ovc, b_cpu.row_stride, b_cpu.head_stride, bits(b_cpu.k_new),
+                            bits(b_cpu.v_new), b_cpu.cu_seqlens.numpy(), b_cpu.kv_start.numpy(),
+                            b_cpu.kv_len.numpy(), b_cpu.H, b_cpu.D)
+    assert np.array_equal(bits(kc), okc) and np.array_equal(bits(vc), ovc)
+    _, o_acc, _, _ = oracle_accept(b_cpu, use_logits=False)
+    assert np.array_equal(lens.cpu().numpy(), b_cpu.kv_len.numpy() + o_acc)

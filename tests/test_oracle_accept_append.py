@@ -256,3 +256,30 @@ def test_widening_gives_exact_values():
         out = oracle.verify_attention(zeros, zeros, fin, zeros[:0], zeros[:0], D, D,
                                       [0, 1], [0], [0], 1, D, 1.0, dtype)
         assert np.array_equal(out.reshape(-1), vals[np.isfinite(vals)])
+
+
+@pytest.mark.parametrize("layout", [TOKEN_MAJOR, HEAD_MAJOR])
+def test_write_through_then_advance_equals_append_on_the_live_rows(layout):
+    """Sec. 3.2 in the paper's own order: write every new row at the sample's location, then
+    advance the location by the accepted count.  On rows [0, kv_len+accepted) this must give
+    what appending only the accepted rows gives; rejected drafts sit beyond the new length;
+    nothing else in the arena changes."""
+    kv_len, k = [7, 0, 12, 3], [4, 3, 1, 5]
+    accepted = [2, 3, 1, 1]
+    b = make_batch(kv_len, k, H=3, D=8, dtype=torch.float16, seed=33, capacity=24, layout=layout)
+    a_k, a_v = bits(b.k_cache).copy(), bits(b.v_cache).copy()
+    new_len = oracle.kv_append(a_k, a_v, b.row_stride, b.head_stride, bits(b.k_new), bits(b.v_new),
+                               b.cu_seqlens.numpy(), accepted, b.kv_start.numpy(), b.kv_len.numpy(),
+                               b.H, b.D)
+    w_k, w_v = bits(b.k_cache).copy(), bits(b.v_cache).copy()
+    oracle.kv_write_through(w_k, w_v, b.row_stride, b.head_stride, bits(b.k_new), bits(b.v_new),
+                            b.cu_seqlens.numpy(), b.kv_start.numpy(), b.kv_len.numpy(), b.H, b.D)
+    cu = b.cu_seqlens.numpy()
+    for arena_w, arena_a, new in ((w_k, a_k, b.k_new), (w_v, a_v, b.v_new)):
+        W = arena_view(from_bits(arena_w, b.dtype), layout, b.rows, b.H, b.D)
+        A = arena_view(from_bits(arena_a, b.dtype), layout, b.rows, b.H, b.D)
+        for i in range(b.B):
+            s, L = int(b.kv_start[i]), kv_len[i]
+            assert np.array_equal(bits(W[s:s + new_len[i]]), bits(A[s:s + new_len[i]]))
+            assert np.array_equal(bits(W[s + L:s + L + k[i]]), bits(new[cu[i]:cu[i + 1]]))
+            assert (bits(W[s + L + k[i]:s + 24]) == 0x7E00).all()

@@ -199,15 +199,18 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* 
     }
 }
 
-// One (sample, head) pair's share of a wave's tile range; everything is wave-uniform.
+// One (sample, head) pair's share of a wave's tile range; everything is wave-uniform and
+// kept small, so that two of them live in scalar registers.
 struct Segment {
     int i, h;            // sample, head
     int cu_i, k, k_real; // first packed row, rows, real rows (k_real < k only in the padded ablation)
-    int L, ntc, nt;      // cached keys, cache tiles, tiles (= ntc + 1: the new-token tile is last)
+    int L;               // cached keys; ceil(L/32) cache tiles, then the new-token tile
     int t0, t1;          // this wave consumes tiles [t0, t1) of the pair
-    uint64_t kc, vc;     // cache rows of the pair: (first row of the sample, head h)
-    uint64_t kn, vn, qn; // packed new K / V / Q rows of the pair
-    uint64_t mask_base;  // padded ablation: key-mask row of the sample
+    int64_t cache_off;   // byte offset of (first cache row of the sample, head h) in the arenas
+    int64_t new_off;     // byte offset of (first packed row of the sample, head h) in q / k_new / v_new
+    int64_t mask_off;    // padded ablation: offset of the sample's key-mask row
+    __device__ __forceinline__ int ntc() const { return (L + kTileKeys - 1) / kTileKeys; }
+    __device__ __forceinline__ int nt() const { return ntc() + 1; }
 };
 
 // The segment that starts at flat tile index gpos (< gend); `i` is a sample at or before it.
@@ -223,20 +226,30 @@ __device__ __forceinline__ Segment make_segment(const AttnParams& p, const int32
     s.L = PADDED ? p.l_pad : uniform(p.kv_len[i]);
     const int64_t start = PADDED ? (int64_t)i * p.cap : (int64_t)uniform(p.kv_start[i]);
     s.k_real = PADDED ? uniform(p.k_valid[i]) : s.k;
-    s.ntc = (s.L + kTileKeys - 1) / kTileKeys;
-    s.nt = s.ntc + 1;
+    const int nt = s.nt();
     const int rem = gpos - uniform(prefix[i]);
-    s.h = uniform(rem / s.nt);
-    s.t0 = rem - s.h * s.nt;
-    s.t1 = min(s.nt, s.t0 + (gend - gpos));
-    const int64_t cache_off = start * p.row_stride_b + (int64_t)s.h * p.head_stride_b;
-    const int64_t new_off = ((int64_t)s.cu_i * p.H + s.h) * (D * 2);
-    s.kc = uniform_addr(p.k_cache + cache_off);
-    s.vc = uniform_addr(p.v_cache + cache_off);
-    s.kn = uniform_addr(p.k_new + new_off);
-    s.vn = uniform_addr(p.v_new + new_off);
-    s.qn = uniform_addr(p.q + new_off);
-    s.mask_base = PADDED ? uniform_addr(p.key_mask + (int64_t)i * p.cap) : 0;
+    s.h = uniform(rem / nt);
+    s.t0 = rem - s.h * nt;
+    s.t1 = min(nt, s.t0 + (gend - gpos));
+    s.cache_off = start * p.row_stride_b + (int64_t)s.h * p.head_stride_b;
+    s.new_off = ((int64_t)s.cu_i * p.H + s.h) * (D * 2);
+    s.mask_off = PADDED ? (int64_t)i * p.cap : 0;
+    return s;
+}
+
+// The segment after `c` in the wave's range; it starts at flat tile gpos (< gend), the first
+// tile of the next pair.  The next head of the same sample needs no memory access at all;
+// only a change of sample reads the index arrays again.
+template <int D, bool PADDED>
+__device__ __forceinline__ Segment next_segment(const AttnParams& p, const int32_t* prefix,
+                                                const Segment& c, int gpos, int gend) {
+    if (c.h + 1 >= p.H) return make_segment<D, PADDED>(p, prefix, c.i + 1, gpos, gend);
+    Segment s = c;
+    s.h = c.h + 1;
+    s.t0 = 0;
+    s.t1 = min(c.nt(), gend - gpos);
+    s.cache_off = c.cache_off + p.head_stride_b;
+    s.new_off = c.new_off + D * 2;
     return s;
 }
 
@@ -275,7 +288,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     Segment cur = make_segment<D, PADDED>(p, prefix, uniform(lo), gbeg, gend);
     int cur_end = gbeg + (cur.t1 - cur.t0);            // flat index one past cur's last tile
     Segment nxt = cur;
-    if (cur_end < gend) nxt = make_segment<D, PADDED>(p, prefix, cur.i, cur_end, gend);
+    if (cur_end < gend) nxt = next_segment<D, PADDED>(p, prefix, cur, cur_end, gend);
 
     u32x4 qb[KS];                // Q^T of `cur` as the B operand of S^T = K Q^T
     u32x4 qn[KS];                // the same for `nxt`, fetched a whole segment ahead
@@ -285,7 +298,8 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     // Q rows of a pair (k rows at qaddr), raw: rows beyond k repeat row k-1 and are zeroed
     // by use_q when the pair becomes current -- touching the values here would make the wave
     // wait for the load (and for every tile load issued before it) at once.
-    auto load_q = [&](u32x4* dst, uint64_t qaddr, int k) {
+    auto load_q = [&](u32x4* dst, int64_t new_off, int k) {
+        const uint64_t qaddr = uniform_addr(p.q + new_off);
         const uint32_t qoff = (uint32_t)min(n, k - 1) * new_row_bytes + (uint32_t)g * 16u;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) dst[ks] = gload<u32x4>(qaddr, qoff + 64 * ks);
@@ -310,21 +324,21 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
 
     // Loads of tile `tile` of a pair described by plain values (never by a pointer to a
     // Segment, so that both segments stay in scalar registers).
-    auto issue = [&](TileRegs<D>& t, int tile, int ntc, int L, int k, uint64_t kc, uint64_t vc,
-                     uint64_t kn, uint64_t vn, uint64_t mask_base) {
+    auto issue = [&](TileRegs<D>& t, int tile, int L, int k, int64_t cache_off, int64_t new_off,
+                     int64_t mask_off) {
         TileSrc src;
-        const bool is_new = tile >= ntc;                 // wave-uniform
-        src.kbase = is_new ? kn : kc;
-        src.vbase = is_new ? vn : vc;
+        const bool is_new = tile >= (L + kTileKeys - 1) / kTileKeys;   // wave-uniform
+        src.kbase = uniform_addr(is_new ? p.k_new + new_off : p.k_cache + cache_off);
+        src.vbase = uniform_addr(is_new ? p.v_new + new_off : p.v_cache + cache_off);
         src.row_bytes = is_new ? new_row_bytes : cache_row_bytes;
         src.n0 = is_new ? 0 : tile * kTileKeys;
         src.last = is_new ? k - 1 : L - 1;
-        src.mask_base = is_new ? 0 : mask_base;
+        src.mask_base = (PADDED && !is_new) ? uniform_addr(p.key_mask + mask_off) : 0;
         load_tile<D, PADDED>(t, src, n, g);
     };
 
     auto consume = [&](const TileRegs<D>& t, const Segment& s, int tile) {
-        if (tile < s.ntc) {
+        if (tile < s.ntc()) {
             const int lim = s.L - tile * kTileKeys;
             if (lim >= kTileKeys && !PADDED)
                 compute_tile<ET, D, false>(t, qb, st, p.scale_log2, lim, g);
@@ -338,7 +352,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 // Exactly one wave holds the new-token tile of a (sample, head) pair.
                 const uint32_t row_b = cache_row_bytes;
                 if (n < s.k) {
-                    char* kdst = reinterpret_cast<char*>(s.kc) + (uint64_t)(uint32_t)(s.L + n) * row_b + g * 16;
+                    char* kdst = const_cast<char*>(p.k_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + n) * row_b + g * 16;
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks)
                         *reinterpret_cast<u32x4*>(kdst + 64 * ks) = t.ka[ks];
@@ -347,7 +361,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 for (int e = 0; e < 4; ++e) {
                     const int key = 4 * g + e;
                     if (key < s.k) {
-                        char* vdst = reinterpret_cast<char*>(s.vc) + (uint64_t)(uint32_t)(s.L + key) * row_b + n * (VW * 2);
+                        char* vdst = const_cast<char*>(p.v_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + key) * row_b + n * (VW * 2);
                         *reinterpret_cast<typename TileRegs<D>::vrow_t*>(vdst) = t.v[e];
                     }
                 }
@@ -358,7 +372,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     auto finish_segment = [&](const Segment& s) {
         // the four lanes of a query row hold disjoint shares of the sum
         const float l = quad_sum(st.l);
-        if (s.t0 == 0 && s.t1 == s.nt) {
+        if (s.t0 == 0 && s.t1 == s.nt()) {
             if (n < s.k) {
                 const float inv = 1.0f / l;
                 const int64_t row = ((int64_t)(s.cu_i + n) * p.H + s.h) * D;
@@ -410,10 +424,9 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     auto step = [&](int c, const TileRegs<D>& use, TileRegs<D>& fill) {
         if (c + 1 < gend) {
             const bool same = con_t + 1 < cur.t1;        // else: first tile of the next pair
-            issue(fill, same ? con_t + 1 : nxt.t0, same ? cur.ntc : nxt.ntc, same ? cur.L : nxt.L,
-                  same ? cur.k : nxt.k, same ? cur.kc : nxt.kc, same ? cur.vc : nxt.vc,
-                  same ? cur.kn : nxt.kn, same ? cur.vn : nxt.vn,
-                  same ? cur.mask_base : nxt.mask_base);
+            issue(fill, same ? con_t + 1 : nxt.t0, same ? cur.L : nxt.L, same ? cur.k : nxt.k,
+                  same ? cur.cache_off : nxt.cache_off, same ? cur.new_off : nxt.new_off,
+                  same ? cur.mask_off : nxt.mask_off);
         }
         consume(use, cur, con_t);
         ++con_t;
@@ -426,19 +439,19 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 use_q(qn, cur.k);
                 begin_segment(cur);
                 if (cur_end < gend) {
-                    nxt = make_segment<D, PADDED>(p, prefix, cur.i, cur_end, gend);
-                    load_q(qn, nxt.qn, nxt.k);
+                    nxt = next_segment<D, PADDED>(p, prefix, cur, cur_end, gend);
+                    load_q(qn, nxt.new_off, nxt.k);
                 }
             }
         }
     };
 
     TileRegs<D> ta, tb;
-    load_q(qn, cur.qn, cur.k);
+    load_q(qn, cur.new_off, cur.k);
     use_q(qn, cur.k);
-    if (cur_end < gend) load_q(qn, nxt.qn, nxt.k);
+    if (cur_end < gend) load_q(qn, nxt.new_off, nxt.k);
     begin_segment(cur);
-    issue(ta, cur.t0, cur.ntc, cur.L, cur.k, cur.kc, cur.vc, cur.kn, cur.vn, cur.mask_base);
+    issue(ta, cur.t0, cur.L, cur.k, cur.cache_off, cur.new_off, cur.mask_off);
     for (int c = gbeg; c < gend; c += 2) {
         step(c, ta, tb);
         if (c + 1 < gend) step(c + 1, tb, ta);

@@ -43,6 +43,9 @@ def parse_args():
                     help="paper-order variant: attention also stores the new rows' K/V, append only advances lengths")
     ap.add_argument("--layers", type=int, default=32, help="config 5 only: layers of the verify loop")
     ap.add_argument("--loop-steps", type=int, default=20, help="config 5 only: successive verify steps")
+    ap.add_argument("--sweep-k", action="store_true",
+                    help="instead of the bench: attention time vs rows per sample at 512 cached tokens "
+                         "(the shape of the paper's Fig. 5), B in {4, 16}, k = 1..8")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the bench: run a plain device copy of MIB MiB five times "
                          "(the known-size kernel that scales rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -108,6 +111,9 @@ def main():
         return
     n = args.config
     with_logits = not args.no_logits
+    if args.sweep_k:
+        print(json.dumps(sweep_k()), flush=True)
+        return
     if n == 5:
         print(json.dumps(verify_loop_bench(args, with_logits)), flush=True)
         return
@@ -222,6 +228,44 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(sets[0]["b"], with_logits)
     print(json.dumps(result), flush=True)
+
+
+def sweep_k():
+    """Attention-call time as the number of rows per sample grows, 512 cached tokens per sample
+    (the paper's Fig. 5 measures the whole model this way: 16.6 ms at 1 token vs 22.6 ms at 5
+    tokens per sample, B=16, one A100).  Here only the attention path is timed."""
+    import torch
+    import paper_2405_07542_amd as ems
+    from workloads import make_batch
+    dev = "cuda:0"
+    rows = []
+    for B in (4, 16):
+        for k in range(1, 9):
+            sets = []
+            for v in range(4):
+                b = make_batch([512] * B, [k] * B, H=32, D=128, dtype=torch.float16, seed=900 + 10 * k + v,
+                               capacity=1024, device=dev)
+                ws = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len),
+                                 dtype=torch.uint8, device=dev)
+                sets.append((b, ws, torch.empty_like(b.q),
+                             ems.kv_cache(b.k_cache, b.v_cache, b.row_stride, b.head_stride, b.rows)))
+
+            def call(s):
+                b, ws, out, cache = s
+                ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, b.kv_start, b.kv_len, out,
+                                         max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws)
+            for i in range(8):
+                call(sets[i % 4])
+            torch.cuda.synchronize()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 200
+            ev0.record()
+            for i in range(reps):
+                call(sets[i % 4])
+            ev1.record()
+            torch.cuda.synchronize()
+            rows.append({"B": B, "rows_per_sample": k, "attention_call_us": round(ev0.elapsed_time(ev1) / reps * 1e3, 2)})
+    return {"sweep": "attention call time vs rows per sample, kv_len=512, H=32, D=128, fp16", "results": rows}
 
 
 def verify_loop_bench(args, with_logits):

@@ -277,3 +277,10 @@ def test_write_through_variant(layout, dtype, D):
     assert np.array_equal(bits(kc), okc) and np.array_equal(bits(vc), ovc)
     _, o_acc, _, _ = oracle_accept(b_cpu, use_logits=False)
     assert np.array_equal(lens.cpu().numpy(), b_cpu.kv_len.numpy() + o_acc)
+
+
+def test_opt_13b_head_count():
+    """OPT-13b geometry (40 heads of 128): nothing in the path depends on H being a power of two."""
+    b = make_batch([300, 1, 77], [4, 9, 1], H=40, D=128, dtype=torch.float16, seed=49)
+    check_attention(b, out_dtype=torch.float32, label="H=40")
+    run_accept_and_append(b)

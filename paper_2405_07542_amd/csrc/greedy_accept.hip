@@ -30,9 +30,10 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptPa
     const int c0 = sl * p.slice_len;
     const int c1 = min(p.V, c0 + p.slice_len);
     const uint16_t* base = reinterpret_cast<const uint16_t*>(p.logits) + (int64_t)row * p.V;
-    // every thread starts from the slice's first element, so ties resolve to it
-    float best = widen(ET{}, base[c0]);
-    int32_t arg = c0;
+    // -inf / "no index yet": a row slice that holds nothing above -inf resolves to its first
+    // column below (all its elements are then equal), without a dependent load up front
+    float best = -INFINITY;
+    int32_t arg = 0x7fffffff;
     if ((p.V & 7) == 0) {
         // 16-byte non-temporal loads (the logits are read once), two per thread in flight
         const uint64_t rowaddr = (uint64_t)base;
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptPa
     if (tid == 0) {
 #pragma unroll
         for (int w = 1; w < kArgmaxThreads / kWave; ++w) take_better(best, arg, sv[w], si[w]);
+        if (best == -INFINITY) arg = c0;       // nothing above -inf in this slice: all equal, first wins
         ArgmaxPartial out;
         out.value = best;
         out.index = arg;

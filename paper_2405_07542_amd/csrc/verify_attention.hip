@@ -30,6 +30,7 @@
 namespace ems {
 
 constexpr int kTileKeys = 32;
+constexpr int kMaxRows = 16;             // query rows per (sample, head) pair
 constexpr int kAttnThreads = 256;
 constexpr int kWavesPerBlock = kAttnThreads / kWave;
 
@@ -222,7 +223,8 @@ __device__ __forceinline__ Segment make_segment(const AttnParams& p, const int32
     s.i = i;
     // padded ablation: k_max rows and l_pad aligned cache rows for every sample
     s.cu_i = PADDED ? i * p.k_max : uniform(p.cu[i]);
-    s.k = PADDED ? p.k_max : uniform(p.cu[i + 1]) - s.cu_i;
+    // (never more than the 16 rows one MFMA tile holds, whatever cu_seqlens claims)
+    s.k = min(kMaxRows, PADDED ? p.k_max : uniform(p.cu[i + 1]) - s.cu_i);
     s.L = PADDED ? p.l_pad : uniform(p.kv_len[i]);
     const int64_t start = PADDED ? (int64_t)i * p.cap : (int64_t)uniform(p.kv_start[i]);
     s.k_real = PADDED ? uniform(p.k_valid[i]) : s.k;
@@ -466,7 +468,7 @@ template <typename ET, int D, bool PADDED>
 __global__ __launch_bounds__(kCombineThreads) void combine_partials_kernel(AttnParams p) {
     const int i = blockIdx.y, h = blockIdx.x;
     const int cu_i = PADDED ? i * p.k_max : p.cu[i];
-    const int k = PADDED ? p.k_max : p.cu[i + 1] - cu_i;
+    const int k = min(kMaxRows, PADDED ? p.k_max : p.cu[i + 1] - cu_i);
     if (k <= 0) return;
     const int total = p.ws_header[p.B];
     const int per = (total + p.num_waves - 1) / p.num_waves;

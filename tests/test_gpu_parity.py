@@ -284,3 +284,17 @@ def test_opt_13b_head_count():
     b = make_batch([300, 1, 77], [4, 9, 1], H=40, D=128, dtype=torch.float16, seed=49)
     check_attention(b, out_dtype=torch.float32, label="H=40")
     run_accept_and_append(b)
+
+
+def test_argmax_rows_of_minus_infinity():
+    """A row (or a slice of it) that holds only -inf has every element equal: index 0 wins."""
+    V = 50272
+    b_cpu = make_batch([2, 2], [3, 2], H=1, D=64, dtype=torch.float16, seed=55, V=V)
+    b_cpu.logits[1, :] = float("-inf")
+    b_cpu.logits[2, :] = float("-inf")
+    b_cpu.logits[2, 40000] = -5.0                       # one finite value in a late slice
+    b = to_device(b_cpu)
+    tgt, _, _, _ = hip_accept(b)
+    want = oracle.argmax(bits(b_cpu.logits), torch.float16)
+    assert want[1] == 0 and want[2] == 40000
+    assert np.array_equal(tgt.cpu().numpy(), want)

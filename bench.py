@@ -43,6 +43,9 @@ def parse_args():
                     help="paper-order variant: attention also stores the new rows' K/V, append only advances lengths")
     ap.add_argument("--layers", type=int, default=32, help="config 5 only: layers of the verify loop")
     ap.add_argument("--loop-steps", type=int, default=20, help="config 5 only: successive verify steps")
+    ap.add_argument("--dynamic-batching", action="store_true",
+                    help="instead of the bench: a 1-layer verify loop in which finished samples are replaced "
+                         "by new ones in fresh cache regions (the paper's proposed dynamic batching), B=64")
     ap.add_argument("--sweep-k", action="store_true",
                     help="instead of the bench: attention time vs rows per sample at 512 cached tokens "
                          "(the shape of the paper's Fig. 5), B in {4, 16}, k = 1..8")
@@ -113,6 +116,9 @@ def main():
     with_logits = not args.no_logits
     if args.sweep_k:
         print(json.dumps(sweep_k()), flush=True)
+        return
+    if args.dynamic_batching:
+        print(json.dumps(dynamic_batching_bench(args)), flush=True)
         return
     if n == 5:
         print(json.dumps(verify_loop_bench(args, with_logits)), flush=True)
@@ -228,6 +234,100 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(sets[0]["b"], with_logits)
     print(json.dumps(result), flush=True)
+
+
+def dynamic_batching_bench(args, B=64, H=32, D=128, n_steps=120, region=4096):
+    """Dynamic batching (the paper's Sec. 4.4 proposal, not implemented there): every slot of the
+    batch serves a stream of samples; when its sample finishes, the slot brings no rows for one
+    step (k_i = 0) and then starts a new sample in a FRESH region of the arena with a new cached
+    length.  Per-sample start locations make this free: nothing is moved or padded.  The
+    lengths advance on the device; retirements follow a fixed seeded schedule, so the host
+    never reads anything back.  Reports the throughput of the drifting batch next to that of
+    the same loop with no retirements."""
+    import numpy as np
+    import torch
+    import paper_2405_07542_amd as ems
+    from workloads import make_batch
+    dev = "cuda:0"
+    dtype = torch.bfloat16
+
+    def run(retire):
+        rng = np.random.default_rng(77)
+        lifetimes = rng.integers(8, 40, size=(B, 64))          # steps each successive sample of a slot lives
+        prompt = rng.integers(256, 2049, size=(B, 64))         # its cached length when it enters
+        n_regions = B * (2 + n_steps // 8) if retire else B
+        rows = n_regions * region
+        base = make_batch([1], [1], H=H, D=D, dtype=dtype, seed=78, rows=8, device=dev)
+        # the arena's content does not matter for timing; it must only be finite
+        k_arena = torch.randn(rows * H * D // 2, device=dev, dtype=torch.float32).view(torch.int16).view(dtype)
+        k_arena = torch.nan_to_num(k_arena, nan=0.0, posinf=1.0, neginf=-1.0).clamp_(-4, 4)
+        v_arena = k_arena.roll(12345)
+        cache = ems.kv_cache(k_arena, v_arena, H * D, D, rows)
+        kv_start = torch.arange(B, dtype=torch.int32, device=dev) * region
+        kv_len = torch.tensor(prompt[:, 0], dtype=torch.int32, device=dev)
+        next_region, gen_idx = B, np.zeros(B, dtype=np.int64)
+        left = lifetimes[:, 0].copy()
+        plan = []                                               # per step: device tensors + host-planned updates
+        for step in range(n_steps):
+            k = [int(rng.integers(1, 12)) if left[s] > 0 else 0 for s in range(B)]
+            T = sum(k)
+            cu = torch.tensor(np.concatenate([[0], np.cumsum(k)]), dtype=torch.int32, device=dev)
+            q = torch.randn((T, H, D), device=dev, dtype=torch.float32).to(dtype)
+            ids = torch.randint(0, 50272, (T,), device=dev, dtype=torch.int32)
+            tgt = ids.roll(-1).clone()
+            tgt[torch.rand(T, device=dev) > 0.7] += 1           # drafts agree with probability 0.7
+            refill = []
+            for s in range(B):
+                if left[s] > 0:
+                    left[s] -= 1
+                    if not retire:
+                        left[s] = 1
+                elif retire:                                     # the slot sat out this step: new sample next step
+                    gen_idx[s] += 1
+                    refill.append((s, next_region * region, int(prompt[s, gen_idx[s] % 64])))
+                    left[s] = lifetimes[s, gen_idx[s] % 64]
+                    next_region += 1
+            assert next_region <= n_regions
+            upd = None
+            if refill:
+                idx = torch.tensor([r[0] for r in refill], device=dev)
+                upd = (idx, torch.tensor([r[1] for r in refill], dtype=torch.int32, device=dev),
+                       torch.tensor([r[2] for r in refill], dtype=torch.int32, device=dev))
+            plan.append((T, cu, q, q.roll(1, 0), q.roll(2, 0), ids, tgt, upd, max(k)))
+        ws = torch.empty(ems.ems_attention_workspace_bytes(B, 16 * B, H, D, region), dtype=torch.uint8, device=dev)
+        out = torch.empty((16 * B, H, D), dtype=dtype, device=dev)
+        accepted = torch.empty(B, dtype=torch.int32, device=dev)
+        accepted_cu = torch.empty(B + 1, dtype=torch.int32, device=dev)
+        total_acc = torch.zeros((), dtype=torch.int64, device=dev)
+        start0, len0 = kv_start.clone(), kv_len.clone()
+
+        def loop(count):
+            kv_start.copy_(start0)
+            kv_len.copy_(len0)
+            for T, cu, q, kn, vn, ids, tgt, upd, max_k in plan:
+                ems.ems_verify_attention(q, kn, vn, cache, cu, kv_start, kv_len, out[:T], max_k=16,
+                                         max_kv_len=region - 16, scale=D ** -0.5, workspace=ws)
+                ems.ems_greedy_accept(None, tgt, ids, cu, accepted, accepted_cu, None)
+                ems.ems_kv_append([kn], [vn], [cache], cu, accepted, kv_start, kv_len, kv_len)
+                if count:
+                    total_acc.add_(accepted_cu[-1])
+                if upd is not None:                              # admit the new samples (device-side writes)
+                    kv_start[upd[0]] = upd[1]
+                    kv_len[upd[0]] = upd[2]
+        loop(False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        loop(True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        rows_total = sum(p[0] for p in plan)
+        return {"ms_per_step": round(dt * 1e3 / n_steps, 4), "verified_tokens_per_s": round(int(total_acc) / dt, 1),
+                "query_tokens_per_s": round(rows_total / dt, 1), "regions_used": int(next_region),
+                "mean_live_samples": round(float(np.mean([sum(1 for x in np.diff(p[1].cpu().numpy()) if x > 0)
+                                                         for p in plan])), 1)}
+
+    return {"mode": "dynamic batching, 1 layer, B=%d slots, %d steps, bf16, rows per live sample U[1,11]" % (B, n_steps),
+            "static_batch": run(False), "dynamic_batch": run(True)}
 
 
 def sweep_k():

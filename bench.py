@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--no-ablation", action="store_true", help="skip the padded (vanilla) ablation")
     ap.add_argument("--write-through", action="store_true",
                     help="paper-order variant: attention also stores the new rows' K/V, append only advances lengths")
+    ap.add_argument("--attention-variant", default="mfma", choices=["mfma", "valu"],
+                    help="arithmetic units of the attention kernel's contractions: matrix cores (default) "
+                         "or the vector ALU (a measurement aid; see ems_set_attention_variant)")
     ap.add_argument("--layers", type=int, default=32, help="config 5 only: layers of the verify loop")
     ap.add_argument("--loop-steps", type=int, default=20, help="config 5 only: successive verify steps")
     ap.add_argument("--dynamic-batching", action="store_true",
@@ -49,6 +52,9 @@ def parse_args():
     ap.add_argument("--sweep-k", action="store_true",
                     help="instead of the bench: attention time vs rows per sample at 512 cached tokens "
                          "(the shape of the paper's Fig. 5), B in {4, 16}, k = 1..8")
+    ap.add_argument("--sweep-variants", action="store_true",
+                    help="instead of the bench: attention kernel time of the matrix-core and the vector-ALU "
+                         "formulation vs rows per sample, B=64, 2048 cached tokens each, bf16")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the bench: run a plain device copy of MIB MiB five times "
                          "(the known-size kernel that scales rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -101,6 +107,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     ems.lib()     # fail loudly if the HIP library is missing
+    ems.ems_set_attention_variant(ems.EMS_ATTN_VALU if args.attention_variant == "valu" else ems.EMS_ATTN_MFMA)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if args.copy_calibration > 0:
@@ -114,6 +121,9 @@ def main():
         return
     n = args.config
     with_logits = not args.no_logits
+    if args.sweep_variants:
+        print(json.dumps(sweep_variants()), flush=True)
+        return
     if args.sweep_k:
         print(json.dumps(sweep_k()), flush=True)
         return
@@ -208,7 +218,8 @@ def main():
                    "B": sets[0]["b"].B, "H": sets[0]["b"].H, "D": sets[0]["b"].D,
                    "query_rows_per_step": rows_per_step, "accepted_per_step": accepted_per_step,
                    "logits": with_logits, "buffer_sets": len(sets),
-                   "variant": "write-through + advance" if args.write_through else "verify + append"},
+                   "variant": "write-through + advance" if args.write_through else "verify + append",
+                   "attention_variant": args.attention_variant},
         "query_tokens_per_s": round(rows_per_step / (ms_per_step * 1e-3), 1),
         "roofline": roofline,
     }
@@ -366,6 +377,55 @@ def sweep_k():
             torch.cuda.synchronize()
             rows.append({"B": B, "rows_per_sample": k, "attention_call_us": round(ev0.elapsed_time(ev1) / reps * 1e3, 2)})
     return {"sweep": "attention call time vs rows per sample, kv_len=512, H=32, D=128, fp16", "results": rows}
+
+
+def sweep_variants(B=64, L=2048, ks=(1, 2, 4, 6, 8, 12, 16)):
+    """The two formulations of the attention kernel on one HBM-bound shape (config 4's batch and
+    mean cache length, every sample with the same k): kernel time from HIP events around the main
+    kernel, and the algorithmic bandwidth it amounts to.  The matrix-core path costs the same for
+    any k <= 16; the vector-ALU path pays per row."""
+    import torch
+    import paper_2405_07542_amd as ems
+    from workloads import make_batch
+    dev = "cuda:0"
+    out_rows = []
+    for k in ks:
+        sets = []
+        for v in range(3):
+            b = make_batch([L] * B, [k] * B, H=32, D=128, dtype=torch.bfloat16, seed=700 + 10 * k + v,
+                           capacity=L + 16, device=dev)
+            ws = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len),
+                             dtype=torch.uint8, device=dev)
+            sets.append((b, ws, torch.empty_like(b.q),
+                         ems.kv_cache(b.k_cache, b.v_cache, b.row_stride, b.head_stride, b.rows)))
+        alg = attention_algorithmic_bytes(sets[0][0], 2)
+        row = {"rows_per_sample": k, "algorithmic_bytes": alg}
+        for name, variant in (("mfma", ems.EMS_ATTN_MFMA), ("valu", ems.EMS_ATTN_VALU)):
+            ems.ems_set_attention_variant(variant)
+
+            def call(s):
+                b, ws, out, cache = s
+                ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, b.kv_start, b.kv_len, out,
+                                         max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws)
+            for i in range(6):
+                call(sets[i % 3])
+            torch.cuda.synchronize()
+            reps = 60
+            ems.ems_profile_enable(reps)
+            for i in range(reps):
+                call(sets[i % 3])
+            torch.cuda.synchronize()
+            ms, n = ems.ems_profile_read()
+            ems.ems_profile_enable(0)
+            us = ms / n * 1e3
+            row[name + "_kernel_us"] = round(us, 2)
+            row[name + "_gbs"] = round(alg / (us * 1e-6) / 1e9, 1)
+        ems.ems_set_attention_variant(ems.EMS_ATTN_MFMA)
+        out_rows.append(row)
+        del sets
+        torch.cuda.empty_cache()
+    return {"sweep": "attention kernel time, matrix-core vs vector-ALU formulation, B=%d, kv_len=%d, H=32, D=128, bf16"
+                     % (B, L), "results": out_rows}
 
 
 def verify_loop_bench(args, with_logits):

@@ -233,6 +233,22 @@ EMS_API ems_status ems_validate_inputs(
 EMS_API ems_status ems_profile_enable(int max_records);
 EMS_API ems_status ems_profile_read(double* total_ms, int* launches);
 
+/*
+ * Measurement aid: which arithmetic units the attention kernel of ems_verify_attention and
+ * ems_verify_attention_write_through uses for its two contractions (scores and weighted
+ * sum of values).  EMS_ATTN_MFMA (the default) runs them on the matrix cores; EMS_ATTN_VALU
+ * runs the same tiles, loads and merge on the vector ALU (packed dot products and FMAs),
+ * so that the two can be timed against each other on one input.  Results of both meet
+ * the same tolerance.  Process-wide; takes effect with the next call; the padded ablation
+ * always uses the matrix cores.  Any other value: EMS_ERR_INVALID_ARG, setting unchanged.
+ */
+typedef enum ems_attention_variant {
+    EMS_ATTN_MFMA = 0,
+    EMS_ATTN_VALU = 1
+} ems_attention_variant;
+EMS_API ems_status ems_set_attention_variant(int variant);
+EMS_API int ems_get_attention_variant(void);
+
 /* Thread-local text for the last non-OK status returned on this thread. */
 EMS_API const char* ems_last_error_string(void);
 

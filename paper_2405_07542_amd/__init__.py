@@ -81,6 +81,10 @@ def lib() -> ctypes.CDLL:
                                            i32, i32, i32, i32, i32, i32, i32, vp]
         L.ems_profile_enable.restype = i32
         L.ems_profile_enable.argtypes = [i32]
+        L.ems_set_attention_variant.restype = i32
+        L.ems_set_attention_variant.argtypes = [i32]
+        L.ems_get_attention_variant.restype = i32
+        L.ems_get_attention_variant.argtypes = []
         L.ems_profile_read.restype = i32
         L.ems_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
         _lib = L
@@ -201,6 +205,17 @@ def ems_padded_kv_append(k_new_pad_layers, v_new_pad_layers, caches, cap: int, k
                                       _DT[k_new_pad_layers[0].dtype], _stream(stream)))
 
 
+EMS_ATTN_MFMA, EMS_ATTN_VALU = 0, 1
+
+
+def ems_set_attention_variant(variant: int) -> None:
+    _check(lib().ems_set_attention_variant(int(variant)))
+
+
+def ems_get_attention_variant() -> int:
+    return int(lib().ems_get_attention_variant())
+
+
 def ems_profile_enable(max_records: int) -> None:
     _check(lib().ems_profile_enable(int(max_records)))
 
@@ -213,6 +228,6 @@ def ems_profile_read():
     return ms.value, n.value
 
 
-__all__ = ["ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
+__all__ = ["ems_set_attention_variant", "ems_get_attention_variant", "EMS_ATTN_MFMA", "EMS_ATTN_VALU", "ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
            "ems_accept_workspace_bytes", "ems_verify_attention", "ems_greedy_accept",
            "ems_kv_append", "ems_validate_inputs", "EMS_F16", "EMS_BF16", "EMS_F32"]

@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <atomic>
 #include <vector>
 
 #include "ems_kernels.h"
@@ -89,6 +90,7 @@ struct Profile {
     int used = 0;
 };
 Profile g_prof;
+std::atomic<int> g_attn_variant{EMS_ATTN_MFMA};
 
 }  // namespace
 
@@ -197,6 +199,7 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
         ++g_prof.used;
     }
     hipError_t e = ems::launch_verify_attention(p, blocks, D, dtype == EMS_BF16, pad != nullptr,
+                                                g_attn_variant.load() == EMS_ATTN_VALU,
                                                 static_cast<hipStream_t>(hip_stream), ev0, ev1);
     if (e != hipSuccess) return hip_fail("attention launch", e);
     return EMS_OK;
@@ -437,6 +440,15 @@ ems_status ems_padded_kv_append(const void* const* k_new_pad_layers,
     }
     return EMS_OK;
 }
+
+ems_status ems_set_attention_variant(int variant) {
+    if (variant != EMS_ATTN_MFMA && variant != EMS_ATTN_VALU)
+        return fail(EMS_ERR_INVALID_ARG, "attention variant %d is neither EMS_ATTN_MFMA nor EMS_ATTN_VALU", variant);
+    g_attn_variant.store(variant);
+    return EMS_OK;
+}
+
+int ems_get_attention_variant(void) { return g_attn_variant.load(); }
 
 ems_status ems_profile_enable(int max_records) {
     for (hipEvent_t ev : g_prof.start) (void)hipEventDestroy(ev);

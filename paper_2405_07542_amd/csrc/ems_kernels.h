@@ -39,8 +39,10 @@ struct AttnParams {
 
 // ev_start / ev_stop (may be null) are recorded right before and right after the main
 // attention kernel, i.e. they exclude the partial-merge kernel.
+// valu: contractions on the vector ALU instead of the matrix cores (unpadded layout only).
 hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16, bool padded,
-                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
+                                   bool valu, hipStream_t stream, hipEvent_t ev_start,
+                                   hipEvent_t ev_stop);
 
 struct ArgmaxPartial {
     float value;

@@ -200,6 +200,163 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* 
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// The same tile on the vector ALU instead of the matrix cores (selected at run time; kept
+// to measure what the MFMA formulation buys, not as the default).  Loads and the tile
+// registers are identical.  Scores: lane (n, g) holds keys n and 16+n, head-dim slice
+// [32s + 8g, 32s + 8g + 8) of every k-step s, so a score is 16 two-way dot products per
+// key against the query row read from LDS (a broadcast read), then a sum over the four g
+// lanes.  The probabilities of a query row cross lanes through LDS (the lanes that hold a
+// V row's slice need the weights of keys 4g..4g+3 and 16+4g..16+4g+3) as 16-bit numbers,
+// exactly as the matrix-core path feeds them (bf16: hi + lo), and meet V as pairs of
+// neighbouring keys in a second run of two-way dot products.  The query rows are walked by
+// a run-time loop; the unnormalised outputs of all rows live in wave-private LDS (registers
+// cannot be indexed by a run-time row), the running max and sum of row q in lane q of one
+// register each.  Cost grows with the number of rows k: roughly 100 (fp16) to 140 (bf16)
+// vector instructions plus an LDS round trip per row per tile, where the MFMA path pays
+// the same for any k <= 16.
+struct ValuState {
+    float m, l;          // lane q: running max (log2 domain) and running sum of query row q
+};
+
+__device__ __forceinline__ float dot2(F16, uint32_t a, uint32_t b, float c) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, a), __builtin_bit_cast(h2, b), c, false);
+}
+__device__ __forceinline__ float dot2(BF16, uint32_t a, uint32_t b, float c) {
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2, a), __builtin_bit_cast(b2, b), c, false);
+}
+
+// Rotation by R lanes inside each row of 16 lanes (DPP row_ror).
+template <int R>
+__device__ __forceinline__ float row_ror(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x120 + R,
+                                                              0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_max(float x) {
+    x = fmaxf(x, row_ror<8>(x));
+    x = fmaxf(x, row_ror<4>(x));
+    x = fmaxf(x, row_ror<2>(x));
+    return fmaxf(x, row_ror<1>(x));
+}
+__device__ __forceinline__ float row16_sum(float x) {
+    x += row_ror<8>(x);
+    x += row_ror<4>(x);
+    x += row_ror<2>(x);
+    return x + row_ror<1>(x);
+}
+__device__ __forceinline__ float lane_get(float reg, int lane) {      // lane: wave-uniform
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, reg), lane));
+}
+__device__ __forceinline__ float lane_set(float reg, int lane, float value, int my_lane) {
+    return my_lane == lane ? value : reg;
+}
+
+// Wave-private LDS of the vector-ALU formulation: query rows (16-bit, row-major), P of one
+// row (hi and lo halves, 32 keys each), and the per-lane shares of the outputs of 16 rows.
+template <int D> struct ValuLds {
+    static constexpr int q_bytes = kMaxRows * D * 2;
+    static constexpr int p_bytes = 2 * kTileKeys * 2;
+    static constexpr int acc_bytes = kMaxRows * kWave * (D / 16) * 4;
+    static constexpr int bytes = q_bytes + p_bytes + acc_bytes;
+};
+
+// `lim` = visible keys of a cache tile (same for every row); the new-token tile (NEW) shows
+// row q its own key and the ones before it.
+template <typename ET, int D, bool MASKED, bool NEW>
+__device__ __forceinline__ void valu_tile(const TileRegs<D>& t, char* lds, ValuState& st,
+                                          float scale_log2, int k, int lim, int lane, int n, int g) {
+    constexpr int KS = TileRegs<D>::KS;
+    constexpr int VW = TileRegs<D>::VW;
+    constexpr bool kSplitP = PSplit<ET>::value;
+    const char* const q_lds = lds;
+    uint16_t* const p_hi = reinterpret_cast<uint16_t*>(lds + ValuLds<D>::q_bytes);
+    uint16_t* const p_lo = p_hi + kTileKeys;
+    float* const acc_lds = reinterpret_cast<float*>(lds + ValuLds<D>::q_bytes + ValuLds<D>::p_bytes);
+    // V as pairs of neighbouring keys per head-dim element (the transposition the
+    // matrix-core path does too), once per tile
+    uint32_t vt[VW][4];
+#pragma unroll
+    for (int c = 0; c < VW; ++c)
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) {
+            const uint32_t w0 = t.v[2 * pr][c >> 1];
+            const uint32_t w1 = t.v[2 * pr + 1][c >> 1];
+            vt[c][pr] = (c & 1) ? pair_hi(w0, w1) : pair_lo(w0, w1);
+        }
+#pragma unroll 1
+    for (int q = 0; q < k; ++q) {                        // wave-uniform trip count
+        float acc[VW];
+        float* const my_acc = acc_lds + (q * kWave + lane) * VW;
+#pragma unroll
+        for (int c = 0; c < VW; c += 4) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(my_acc + c);
+            acc[c] = a[0]; acc[c + 1] = a[1]; acc[c + 2] = a[2]; acc[c + 3] = a[3];
+        }
+        float pa = 0.f, pb = 0.f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const u32x4 qv = *reinterpret_cast<const u32x4*>(q_lds + q * (D * 2) + s * 64 + g * 16);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                pa = dot2(ET{}, t.ka[s][w], qv[w], pa);
+                pb = dot2(ET{}, t.kb[s][w], qv[w], pb);
+            }
+        }
+        pa = quad_sum(pa) * scale_log2;
+        pb = quad_sum(pb) * scale_log2;
+        if (MASKED) {
+            const int vis = NEW ? min(k, q + 1) : lim;
+            if (n >= vis) pa = -INFINITY;
+            if (16 + n >= vis) pb = -INFINITY;
+        }
+        // the 16 lanes of a row hold different keys, the four rows hold copies: after the
+        // row reductions every lane holds the same max and sum
+        const float m_old = lane_get(st.m, q);
+        const float m_new = fmaxf(m_old, row16_max(fmaxf(pa, pb)));
+        const float alpha = fast_exp2(m_old - m_new);
+        pa = fast_exp2(pa - m_new);
+        pb = fast_exp2(pb - m_new);
+        const float l_new = lane_get(st.l, q) * alpha + row16_sum(pa + pb);
+        st.m = lane_set(st.m, q, m_new, lane);
+        st.l = lane_set(st.l, q, l_new, lane);
+        if (g == 0) {
+            p_hi[n] = (uint16_t)pack2(ET{}, pa, 0.f);
+            p_hi[16 + n] = (uint16_t)pack2(ET{}, pb, 0.f);
+            if (kSplitP) {
+                p_lo[n] = (uint16_t)pack2(ET{}, pa - round16(ET{}, pa), 0.f);
+                p_lo[16 + n] = (uint16_t)pack2(ET{}, pb - round16(ET{}, pb), 0.f);
+            }
+        }
+        const u32x2 h0 = *reinterpret_cast<const u32x2*>(p_hi + 4 * g);
+        const u32x2 h1 = *reinterpret_cast<const u32x2*>(p_hi + 16 + 4 * g);
+        u32x2 l0 = {0u, 0u}, l1 = {0u, 0u};
+        if (kSplitP) {
+            l0 = *reinterpret_cast<const u32x2*>(p_lo + 4 * g);
+            l1 = *reinterpret_cast<const u32x2*>(p_lo + 16 + 4 * g);
+        }
+#pragma unroll
+        for (int c = 0; c < VW; ++c) {
+            float a = acc[c] * alpha;
+            a = dot2(ET{}, vt[c][0], h0[0], a);
+            a = dot2(ET{}, vt[c][1], h0[1], a);
+            a = dot2(ET{}, vt[c][2], h1[0], a);
+            a = dot2(ET{}, vt[c][3], h1[1], a);
+            if (kSplitP) {
+                a = dot2(ET{}, vt[c][0], l0[0], a);
+                a = dot2(ET{}, vt[c][1], l0[1], a);
+                a = dot2(ET{}, vt[c][2], l1[0], a);
+                a = dot2(ET{}, vt[c][3], l1[1], a);
+            }
+            acc[c] = a;
+        }
+#pragma unroll
+        for (int c = 0; c < VW; c += 4)
+            *reinterpret_cast<f32x4*>(my_acc + c) = f32x4{acc[c], acc[c + 1], acc[c + 2], acc[c + 3]};
+    }
+}
+
 // One (sample, head) pair's share of a wave's tile range; everything is wave-uniform and
 // kept small, so that two of them live in scalar registers.
 struct Segment {
@@ -255,11 +412,12 @@ __device__ __forceinline__ Segment next_segment(const AttnParams& p, const int32
     return s;
 }
 
-template <typename ET, int D, bool PADDED>
+template <typename ET, int D, bool PADDED, bool VALU = false>
 __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnParams p) {
     extern __shared__ int32_t prefix[];
     constexpr int KS = TileRegs<D>::KS;
     constexpr int VW = TileRegs<D>::VW;
+    static_assert(!(VALU && PADDED), "the vector-ALU formulation exists for the unpadded layout only");
     build_tile_prefix<PADDED>(p, prefix);
     if (blockIdx.x == 0)       // the merge kernel reads the tile prefix from the workspace header
         for (int i = threadIdx.x; i <= p.B; i += blockDim.x) p.ws_header[i] = prefix[i];
@@ -296,25 +454,42 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     u32x4 qn[KS];                // the same for `nxt`, fetched a whole segment ahead
     SoftmaxState<ET, D> st;
     int lim_new = 0;
+    // vector-ALU formulation: per-row state in registers, Q rows and P in wave-private LDS
+    ValuState vs;
+    char* const vlds = reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15) +
+                       (threadIdx.x >> 6) * ValuLds<D>::bytes;
+    float* const acc_lds = reinterpret_cast<float*>(vlds + ValuLds<D>::q_bytes + ValuLds<D>::p_bytes);
 
     // Q rows of a pair (k rows at qaddr), raw: rows beyond k repeat row k-1 and are zeroed
     // by use_q when the pair becomes current -- touching the values here would make the wave
     // wait for the load (and for every tile load issued before it) at once.
-    auto load_q = [&](u32x4* dst, int64_t new_off, int k) {
+    auto load_q = [&](u32x4* dst, int64_t new_off, int k) __attribute__((always_inline)) {
         const uint64_t qaddr = uniform_addr(p.q + new_off);
         const uint32_t qoff = (uint32_t)min(n, k - 1) * new_row_bytes + (uint32_t)g * 16u;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) dst[ks] = gload<u32x4>(qaddr, qoff + 64 * ks);
     };
-    auto use_q = [&](const u32x4* src, int k) {
+    auto use_q = [&](const u32x4* src, int k) __attribute__((always_inline)) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const u32x4 z = {0u, 0u, 0u, 0u};
-            qb[ks] = n < k ? src[ks] : z;
+            if (VALU)    // lane (n, g) holds Q[n][32ks + 8g .. +8): the LDS image is row-major Q
+                *reinterpret_cast<u32x4*>(vlds + n * (D * 2) + ks * 64 + g * 16) = src[ks];
+            else
+                qb[ks] = n < k ? src[ks] : z;
         }
     };
 
-    auto begin_segment = [&](const Segment& s) {
+    auto begin_segment = [&](const Segment& s) __attribute__((always_inline)) {
+        if (VALU) {
+            vs.m = -INFINITY;
+            vs.l = 0.f;
+            for (int q = 0; q < s.k; ++q)
+#pragma unroll
+                for (int c = 0; c < VW; c += 4)
+                    *reinterpret_cast<f32x4*>(acc_lds + (q * kWave + lane) * VW + c) = f32x4{0.f, 0.f, 0.f, 0.f};
+            return;
+        }
 #pragma unroll
         for (int c = 0; c < VW; ++c) st.acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
         st.m = -INFINITY;
@@ -327,7 +502,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     // Loads of tile `tile` of a pair described by plain values (never by a pointer to a
     // Segment, so that both segments stay in scalar registers).
     auto issue = [&](TileRegs<D>& t, int tile, int L, int k, int64_t cache_off, int64_t new_off,
-                     int64_t mask_off) {
+                     int64_t mask_off) __attribute__((always_inline)) {
         TileSrc src;
         const bool is_new = tile >= (L + kTileKeys - 1) / kTileKeys;   // wave-uniform
         src.kbase = uniform_addr(is_new ? p.k_new + new_off : p.k_cache + cache_off);
@@ -339,15 +514,23 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
         load_tile<D, PADDED>(t, src, n, g);
     };
 
-    auto consume = [&](const TileRegs<D>& t, const Segment& s, int tile) {
+    auto consume = [&](const TileRegs<D>& t, const Segment& s, int tile) __attribute__((always_inline)) {
         if (tile < s.ntc()) {
             const int lim = s.L - tile * kTileKeys;
-            if (lim >= kTileKeys && !PADDED)
+            if (VALU) {
+                if (lim >= kTileKeys)
+                    valu_tile<ET, D, false, false>(t, vlds, vs, p.scale_log2, s.k, lim, lane, n, g);
+                else
+                    valu_tile<ET, D, true, false>(t, vlds, vs, p.scale_log2, s.k, lim, lane, n, g);
+            } else if (lim >= kTileKeys && !PADDED)
                 compute_tile<ET, D, false>(t, qb, st, p.scale_log2, lim, g);
             else
                 compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim, g);
         } else {
-            compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim_new, g);
+            if (VALU)
+                valu_tile<ET, D, true, true>(t, vlds, vs, p.scale_log2, s.k, 0, lane, n, g);
+            else
+                compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim_new, g);
             if (!PADDED && p.write_through) {
                 // Paper order (Sec. 3.2): the new rows' K/V go to the sample's own location,
                 // cache rows kv_len + j, j < k_i, straight from the registers of this tile.
@@ -371,7 +554,58 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
         }
     };
 
-    auto finish_segment = [&](const Segment& s) {
+    // vector-ALU formulation: reduce the shares over lanes, then the same outputs / partials
+    auto finish_segment_valu = [&](const Segment& s) __attribute__((always_inline)) {
+        const bool whole = s.t0 == 0 && s.t1 == s.nt();
+        const int slot = 2 * wave + (s.t0 == 0 ? 1 : 0);
+#pragma unroll 1
+        for (int q = 0; q < s.k; ++q) {
+            {
+                const float l = lane_get(vs.l, q);
+                float o[VW];
+#pragma unroll
+                for (int c = 0; c < VW; c += 4) {
+                    const f32x4 a = *reinterpret_cast<const f32x4*>(acc_lds + (q * kWave + lane) * VW + c);
+                    o[c] = quad_sum(a[0]); o[c + 1] = quad_sum(a[1]);
+                    o[c + 2] = quad_sum(a[2]); o[c + 3] = quad_sum(a[3]);
+                }
+                if (g == 0) {
+                    if (whole) {
+                        const float inv = 1.0f / l;
+                        const int64_t idx = ((int64_t)(s.cu_i + q) * p.H + s.h) * D + n * VW;
+                        if (p.out_f32) {
+                            float* dst = reinterpret_cast<float*>(p.out) + idx;
+#pragma unroll
+                            for (int c = 0; c < VW; c += 4)
+                                *reinterpret_cast<f32x4*>(dst + c) =
+                                    f32x4{o[c] * inv, o[c + 1] * inv, o[c + 2] * inv, o[c + 3] * inv};
+                        } else {
+                            typename TileRegs<D>::vrow_t pk;
+#pragma unroll
+                            for (int c = 0; c < VW; c += 2) pk[c >> 1] = pack2(ET{}, o[c] * inv, o[c + 1] * inv);
+                            *reinterpret_cast<typename TileRegs<D>::vrow_t*>(
+                                reinterpret_cast<uint16_t*>(p.out) + idx) = pk;
+                        }
+                    } else {
+                        float* dst = p.ws + ((int64_t)slot * 16 + q) * (D + kPartialPad);
+#pragma unroll
+                        for (int c = 0; c < VW; c += 4)
+                            *reinterpret_cast<f32x4*>(dst + n * VW + c) = f32x4{o[c], o[c + 1], o[c + 2], o[c + 3]};
+                        if (n == 0) {
+                            dst[D] = lane_get(vs.m, q);
+                            dst[D + 1] = l;
+                        }
+                    }
+                }
+            }
+        }
+    };
+
+    auto finish_segment = [&](const Segment& s) __attribute__((always_inline)) {
+        if (VALU) {
+            finish_segment_valu(s);
+            return;
+        }
         // the four lanes of a query row hold disjoint shares of the sum
         const float l = quad_sum(st.l);
         if (s.t0 == 0 && s.t1 == s.nt()) {
@@ -423,7 +657,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     int con_t = cur.t0;              // tile of `cur` that is consumed next
 
     // One step of the walk: issue flat tile c+1 into `fill`, consume flat tile c from `use`.
-    auto step = [&](int c, const TileRegs<D>& use, TileRegs<D>& fill) {
+    auto step = [&](int c, const TileRegs<D>& use, TileRegs<D>& fill) __attribute__((always_inline)) {
         if (c + 1 < gend) {
             const bool same = con_t + 1 < cur.t1;        // else: first tile of the next pair
             issue(fill, same ? con_t + 1 : nxt.t0, same ? cur.L : nxt.L, same ? cur.k : nxt.k,
@@ -510,13 +744,33 @@ __global__ __launch_bounds__(kCombineThreads) void combine_partials_kernel(AttnP
 }
 
 template <typename ET, int D, bool PADDED>
-static hipError_t launch_typed(const AttnParams& p, int blocks, hipStream_t stream,
+static hipError_t launch_typed(const AttnParams& p, int blocks, bool valu, hipStream_t stream,
                                hipEvent_t ev_start, hipEvent_t ev_stop) {
-    const size_t lds = (size_t)(p.B + 1) * sizeof(int32_t);
+    size_t lds = (size_t)(p.B + 1) * sizeof(int32_t);
     hipError_t e;
     if (ev_start && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((verify_attention_kernel<ET, D, PADDED>), dim3(blocks), dim3(kAttnThreads),
-                       lds, stream, p);
+    if constexpr (!PADDED) {
+        if (valu) {
+            lds = ((lds + 15) & ~(size_t)15) + (size_t)kWavesPerBlock * ValuLds<D>::bytes;
+            // up to 32 KiB of prefix + 4 x 14 KiB of wave-private state: above the 64 KiB a
+            // kernel may use without asking
+            static bool raised = false;
+            if (!raised) {
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_attention_kernel<ET, D, false, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+                if (e != hipSuccess) return e;
+                raised = true;
+            }
+            hipLaunchKernelGGL((verify_attention_kernel<ET, D, false, true>), dim3(blocks),
+                               dim3(kAttnThreads), lds, stream, p);
+        } else {
+            hipLaunchKernelGGL((verify_attention_kernel<ET, D, false, false>), dim3(blocks),
+                               dim3(kAttnThreads), lds, stream, p);
+        }
+    } else {
+        hipLaunchKernelGGL((verify_attention_kernel<ET, D, true, false>), dim3(blocks),
+                           dim3(kAttnThreads), lds, stream, p);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
@@ -526,18 +780,19 @@ static hipError_t launch_typed(const AttnParams& p, int blocks, hipStream_t stre
 }
 
 template <bool PADDED>
-static hipError_t launch_layout(const AttnParams& p, int blocks, int D, bool bf16,
+static hipError_t launch_layout(const AttnParams& p, int blocks, int D, bool bf16, bool valu,
                                 hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    if (D == 128) return bf16 ? launch_typed<BF16, 128, PADDED>(p, blocks, stream, ev_start, ev_stop)
-                              : launch_typed<F16, 128, PADDED>(p, blocks, stream, ev_start, ev_stop);
-    return bf16 ? launch_typed<BF16, 64, PADDED>(p, blocks, stream, ev_start, ev_stop)
-                : launch_typed<F16, 64, PADDED>(p, blocks, stream, ev_start, ev_stop);
+    if (D == 128) return bf16 ? launch_typed<BF16, 128, PADDED>(p, blocks, valu, stream, ev_start, ev_stop)
+                              : launch_typed<F16, 128, PADDED>(p, blocks, valu, stream, ev_start, ev_stop);
+    return bf16 ? launch_typed<BF16, 64, PADDED>(p, blocks, valu, stream, ev_start, ev_stop)
+                : launch_typed<F16, 64, PADDED>(p, blocks, valu, stream, ev_start, ev_stop);
 }
 
 hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16, bool padded,
-                                   hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    return padded ? launch_layout<true>(p, blocks, D, bf16, stream, ev_start, ev_stop)
-                  : launch_layout<false>(p, blocks, D, bf16, stream, ev_start, ev_stop);
+                                   bool valu, hipStream_t stream, hipEvent_t ev_start,
+                                   hipEvent_t ev_stop) {
+    return padded ? launch_layout<true>(p, blocks, D, bf16, false, stream, ev_start, ev_stop)
+                  : launch_layout<false>(p, blocks, D, bf16, valu, stream, ev_start, ev_stop);
 }
 
 }  // namespace ems

@@ -147,3 +147,13 @@ def test_write_through_and_advance_reject_bad_arguments_on_the_host():
     args[12] = 128
     args[9] = 0
     assert L.ems_verify_attention_write_through(*args) == ems.EMS_ERR_INVALID_ARG     # B = 0
+
+
+def test_attention_variant_switch_is_host_state():
+    L = ems.lib()
+    assert L.ems_get_attention_variant() == ems.EMS_ATTN_MFMA
+    assert L.ems_set_attention_variant(ems.EMS_ATTN_VALU) == ems.EMS_OK
+    assert L.ems_get_attention_variant() == ems.EMS_ATTN_VALU
+    assert L.ems_set_attention_variant(5) == ems.EMS_ERR_INVALID_ARG
+    assert L.ems_get_attention_variant() == ems.EMS_ATTN_VALU
+    assert L.ems_set_attention_variant(ems.EMS_ATTN_MFMA) == ems.EMS_OK

@@ -234,6 +234,15 @@ EMS_API ems_status ems_profile_enable(int max_records);
 EMS_API ems_status ems_profile_read(double* total_ms, int* launches);
 
 /*
+ * Measurement aid: one launch of a plain read-only streaming kernel over `bytes` bytes of
+ * device memory at `buf` (16-byte aligned, bytes >= 1024; a tail shorter than 1 KiB is not
+ * read), asynchronous on hip_stream.  Its rate is the read ceiling of the device that the
+ * attention kernel's bandwidth is compared with.  `sink`: 4 writable device bytes (written
+ * only if the data folds to one particular pattern).  Touches nothing else.
+ */
+EMS_API ems_status ems_stream_read_probe(const void* buf, size_t bytes, void* sink, void* hip_stream);
+
+/*
  * Measurement aid: which arithmetic units the attention kernel of ems_verify_attention and
  * ems_verify_attention_write_through uses for its two contractions (scores and weighted
  * sum of values).  EMS_ATTN_MFMA (the default) runs them on the matrix cores; EMS_ATTN_VALU

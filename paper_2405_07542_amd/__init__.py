@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
                                            i32, i32, i32, i32, i32, i32, i32, vp]
         L.ems_profile_enable.restype = i32
         L.ems_profile_enable.argtypes = [i32]
+        L.ems_stream_read_probe.restype = i32
+        L.ems_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.ems_set_attention_variant.restype = i32
         L.ems_set_attention_variant.argtypes = [i32]
         L.ems_get_attention_variant.restype = i32
@@ -205,6 +207,12 @@ def ems_padded_kv_append(k_new_pad_layers, v_new_pad_layers, caches, cap: int, k
                                       _DT[k_new_pad_layers[0].dtype], _stream(stream)))
 
 
+def ems_stream_read_probe(buf, sink, stream=None) -> None:
+    """One launch of the read-only streaming kernel over the whole tensor `buf`."""
+    _check(lib().ems_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink),
+                                       _stream(stream)))
+
+
 EMS_ATTN_MFMA, EMS_ATTN_VALU = 0, 1
 
 
@@ -228,6 +236,6 @@ def ems_profile_read():
     return ms.value, n.value
 
 
-__all__ = ["ems_set_attention_variant", "ems_get_attention_variant", "EMS_ATTN_MFMA", "EMS_ATTN_VALU", "ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
+__all__ = ["ems_stream_read_probe", "ems_set_attention_variant", "ems_get_attention_variant", "EMS_ATTN_MFMA", "EMS_ATTN_VALU", "ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
            "ems_accept_workspace_bytes", "ems_verify_attention", "ems_greedy_accept",
            "ems_kv_append", "ems_validate_inputs", "EMS_F16", "EMS_BF16", "EMS_F32"]

@@ -441,6 +441,17 @@ ems_status ems_padded_kv_append(const void* const* k_new_pad_layers,
     return EMS_OK;
 }
 
+ems_status ems_stream_read_probe(const void* buf, size_t bytes, void* sink, void* hip_stream) {
+    if (!buf || !sink) return fail(EMS_ERR_INVALID_ARG, "buf and sink must not be NULL");
+    if (!aligned16(buf) || (reinterpret_cast<uintptr_t>(sink) & 3) != 0)
+        return fail(EMS_ERR_INVALID_ARG, "buf must be 16-byte aligned, sink 4-byte aligned");
+    if (bytes < 1024) return fail(EMS_ERR_INVALID_ARG, "bytes = %zu is less than one 1 KiB line", bytes);
+    hipError_t e = ems::launch_stream_read(buf, bytes, static_cast<uint32_t*>(sink), 8 * resident_attn_blocks(),
+                                           static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail("stream probe launch", e);
+    return EMS_OK;
+}
+
 ems_status ems_set_attention_variant(int variant) {
     if (variant != EMS_ATTN_MFMA && variant != EMS_ATTN_VALU)
         return fail(EMS_ERR_INVALID_ARG, "attention variant %d is neither EMS_ATTN_MFMA nor EMS_ATTN_VALU", variant);

@@ -104,4 +104,7 @@ hipError_t launch_padded_kv_append(const PaddedAppendParams& p, hipStream_t stre
 hipError_t launch_advance_kv_len(const int32_t* kv_len, const int32_t* accepted,
                                  int32_t* kv_len_out, int B, hipStream_t stream);
 
+// Read-only streaming probe over `bytes` of device memory (whole 1 KiB lines); sink: one word.
+hipError_t launch_stream_read(const void* buf, uint64_t bytes, uint32_t* sink, int blocks, hipStream_t stream);
+
 }  // namespace ems

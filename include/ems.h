@@ -99,8 +99,8 @@ EMS_API size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max
  *   max_kv_len >= every kv_len[i]            (host-known upper bounds)
  * Samples with k_i = 0 contribute nothing; kv_len[i] = 0 is legal; T = 0 is a no-op.
  * Errors: B<1, T<0, H<1, max_k<0, max_kv_len<0, NULL/misaligned pointer,
- * non-finite scale -> INVALID_ARG; D not in {64,128}, max_k > 16, B > 8192
- * -> UNSUPPORTED; workspace -> WORKSPACE; launch failure -> HIP.
+ * non-finite scale -> INVALID_ARG; D not in {64,80,128}, max_k > 16, B > 8192
+ * -> UNSUPPORTED (the padded ablation and EMS_ATTN_VALU have D in {64,128} only); workspace -> WORKSPACE; launch failure -> HIP.
  */
 EMS_API ems_status ems_verify_attention(
     const void* q, const void* k_new, const void* v_new,

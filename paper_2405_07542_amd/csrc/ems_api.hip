@@ -137,7 +137,11 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
         return fail(EMS_ERR_INVALID_ARG, "out_dtype must equal dtype or be EMS_F32");
     if (!pad && (!cu_seqlens || !kv_start || !kv_len))
         return fail(EMS_ERR_INVALID_ARG, "cu_seqlens, kv_start and kv_len must not be NULL");
-    if (D != 64 && D != 128) return fail(EMS_ERR_UNSUPPORTED, "D = %d, supported head dims are 64 and 128", D);
+    if (D != 64 && D != 80 && D != 128)
+        return fail(EMS_ERR_UNSUPPORTED, "D = %d, supported head dims are 64, 80 and 128", D);
+    if (D == 80 && pad) return fail(EMS_ERR_UNSUPPORTED, "the padded ablation has head dims 64 and 128 only");
+    if (D == 80 && g_attn_variant.load() == EMS_ATTN_VALU)
+        return fail(EMS_ERR_UNSUPPORTED, "EMS_ATTN_VALU has head dims 64 and 128 only");
     if (max_k > EMS_MAX_QUERY_ROWS)
         return fail(EMS_ERR_UNSUPPORTED, "max_k = %d, at most %d rows per sample", max_k, EMS_MAX_QUERY_ROWS);
     if (B > kMaxB) return fail(EMS_ERR_UNSUPPORTED, "B = %d, at most %d samples", B, kMaxB);

@@ -64,10 +64,25 @@ __device__ __forceinline__ void build_tile_prefix(const AttnParams& p, int32_t* 
     __syncthreads();
 }
 
+// Head dims: 64 and 128 fill every lane; 80 (a row of 160 bytes) is run as a 96-wide
+// score product whose last k-step is half empty (the lane quarters g >= 2 re-read the
+// pieces of g - 2 and meet zeros in Q) and a V / output layout of 8 elements per lane in
+// which only 10 of the 16 lanes of a row hold data (the others re-read lane 9's piece and
+// their results are never stored).
 template <int D>
 struct TileRegs {
-    static constexpr int KS = D / 32;        // MFMA k-steps over the head dim
-    static constexpr int VW = D / 16;        // head-dim elements per lane per V row
+    static_assert(D == 64 || D == 80 || D == 128, "head dims 64, 80 and 128");
+    static constexpr int KS = (D + 31) / 32;          // MFMA k-steps over the head dim
+    static constexpr int VW = D == 64 ? 4 : 8;        // head-dim elements per lane per V row
+    static constexpr int kVLanes = D / VW;            // lanes of a 16-lane row that hold V / output data
+    static constexpr int kTailQ = (D % 32) / 8;       // valid lane quarters of the last k-step; 0 = all four
+    // byte offset of lane quarter g's 16-byte piece of k-step s inside a K or Q row
+    static __device__ __forceinline__ uint32_t piece(int s, int g) {
+        return (uint32_t)(64 * s + 16 * ((kTailQ != 0 && s == KS - 1) ? g % (kTailQ != 0 ? kTailQ : 1) : g));
+    }
+    static __device__ __forceinline__ bool piece_valid(int s, int g) {
+        return !(kTailQ != 0 && s == KS - 1 && g >= kTailQ);
+    }
     typedef uint32_t vrow_t __attribute__((ext_vector_type(VW / 2)));
     u32x4 ka[KS], kb[KS];                    // keys 0..15 / 16..31 of the tile, A-operand layout
     vrow_t v[8];                             // this lane's 8 keys x VW head-dim elements
@@ -88,17 +103,18 @@ template <int D, bool PADDED>
 __device__ __forceinline__ void load_tile(TileRegs<D>& t, const TileSrc& src, int n, int g) {
     constexpr int KS = TileRegs<D>::KS;
     constexpr int VW = TileRegs<D>::VW;
-    const uint32_t ra = (uint32_t)min(src.n0 + n, src.last) * src.row_bytes + (uint32_t)g * 16u;
-    const uint32_t rb = (uint32_t)min(src.n0 + 16 + n, src.last) * src.row_bytes + (uint32_t)g * 16u;
+    const uint32_t ra = (uint32_t)min(src.n0 + n, src.last) * src.row_bytes;
+    const uint32_t rb = (uint32_t)min(src.n0 + 16 + n, src.last) * src.row_bytes;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-        t.ka[s] = gload_stream<u32x4>(src.kbase, ra + 64 * s);
-        t.kb[s] = gload_stream<u32x4>(src.kbase, rb + 64 * s);
+        t.ka[s] = gload_stream<u32x4>(src.kbase, ra + TileRegs<D>::piece(s, g));
+        t.kb[s] = gload_stream<u32x4>(src.kbase, rb + TileRegs<D>::piece(s, g));
     }
+    const uint32_t vcol = (uint32_t)min(n, TileRegs<D>::kVLanes - 1) * (VW * 2);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int key = src.n0 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
-        const uint32_t off = (uint32_t)min(key, src.last) * src.row_bytes + (uint32_t)n * (VW * 2);
+        const uint32_t off = (uint32_t)min(key, src.last) * src.row_bytes + vcol;
         t.v[e] = gload_stream<typename TileRegs<D>::vrow_t>(src.vbase, off);
     }
     if (PADDED) {
@@ -115,8 +131,8 @@ template <> struct PSplit<BF16> { static constexpr bool value = true; };
 
 template <typename ET, int D>
 struct SoftmaxState {
-    static constexpr int VW = D / 16;
-    f32x4 acc[VW];     // acc[c][i] = O[query n][d = (4g+i)*VW + c], unnormalised
+    static constexpr int VW = TileRegs<D>::VW;
+    f32x4 acc[VW];     // acc[c][i] = O[query n][d = (4g+i)*VW + c], unnormalised (rows 4g+i < kVLanes)
     float m;           // running max (log2 domain), same in the 4 lanes of a query
     float l;           // this lane's share of the running sum
 };
@@ -418,6 +434,8 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     constexpr int KS = TileRegs<D>::KS;
     constexpr int VW = TileRegs<D>::VW;
     static_assert(!(VALU && PADDED), "the vector-ALU formulation exists for the unpadded layout only");
+    static_assert(!(VALU && D == 80), "the vector-ALU formulation exists for head dims 64 and 128 only");
+    typedef TileRegs<D> TR;
     build_tile_prefix<PADDED>(p, prefix);
     if (blockIdx.x == 0)       // the merge kernel reads the tile prefix from the workspace header
         for (int i = threadIdx.x; i <= p.B; i += blockDim.x) p.ws_header[i] = prefix[i];
@@ -465,9 +483,9 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     // wait for the load (and for every tile load issued before it) at once.
     auto load_q = [&](u32x4* dst, int64_t new_off, int k) __attribute__((always_inline)) {
         const uint64_t qaddr = uniform_addr(p.q + new_off);
-        const uint32_t qoff = (uint32_t)min(n, k - 1) * new_row_bytes + (uint32_t)g * 16u;
+        const uint32_t qoff = (uint32_t)min(n, k - 1) * new_row_bytes;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) dst[ks] = gload<u32x4>(qaddr, qoff + 64 * ks);
+        for (int ks = 0; ks < KS; ++ks) dst[ks] = gload<u32x4>(qaddr, qoff + TR::piece(ks, g));
     };
     auto use_q = [&](const u32x4* src, int k) __attribute__((always_inline)) {
 #pragma unroll
@@ -476,7 +494,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
             if (VALU)    // lane (n, g) holds Q[n][32ks + 8g .. +8): the LDS image is row-major Q
                 *reinterpret_cast<u32x4*>(vlds + n * (D * 2) + ks * 64 + g * 16) = src[ks];
             else
-                qb[ks] = n < k ? src[ks] : z;
+                qb[ks] = (n < k && TR::piece_valid(ks, g)) ? src[ks] : z;
         }
     };
 
@@ -537,15 +555,16 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 // Exactly one wave holds the new-token tile of a (sample, head) pair.
                 const uint32_t row_b = cache_row_bytes;
                 if (n < s.k) {
-                    char* kdst = const_cast<char*>(p.k_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + n) * row_b + g * 16;
+                    char* kdst = const_cast<char*>(p.k_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + n) * row_b;
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks)
-                        *reinterpret_cast<u32x4*>(kdst + 64 * ks) = t.ka[ks];
+                        if (TR::piece_valid(ks, g))
+                            *reinterpret_cast<u32x4*>(kdst + TR::piece(ks, g)) = t.ka[ks];
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int key = 4 * g + e;
-                    if (key < s.k) {
+                    if (key < s.k && n < TR::kVLanes) {
                         char* vdst = const_cast<char*>(p.v_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + key) * row_b + n * (VW * 2);
                         *reinterpret_cast<typename TileRegs<D>::vrow_t*>(vdst) = t.v[e];
                     }
@@ -614,6 +633,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 const int64_t row = ((int64_t)(s.cu_i + n) * p.H + s.h) * D;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
+                    if (4 * g + r >= TR::kVLanes) continue;      // head dim 80: output rows 10..15 hold nothing
                     const int d0 = (4 * g + r) * VW;
                     float o[VW];
 #pragma unroll
@@ -640,6 +660,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 float* dst = p.ws + ((int64_t)slot * 16 + n) * (D + kPartialPad);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
+                    if (4 * g + r >= TR::kVLanes) continue;
                     const int d0 = (4 * g + r) * VW;
 #pragma unroll
                     for (int c = 0; c < VW; c += 4)
@@ -715,6 +736,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_partials_kernel(AttnP
     constexpr int lanes_per_row = D / 4;
     constexpr int rows_per_pass = kCombineThreads / lanes_per_row;
     const int c4 = (threadIdx.x % lanes_per_row) * 4;
+    if ((int)threadIdx.x >= rows_per_pass * lanes_per_row) return;    // head dim 80: 240 of 256 threads
     for (int j = threadIdx.x / lanes_per_row; j < k; j += rows_per_pass) {
         float M = -INFINITY;
         for (int w = w0; w <= w1; ++w) {
@@ -749,7 +771,8 @@ static hipError_t launch_typed(const AttnParams& p, int blocks, bool valu, hipSt
     size_t lds = (size_t)(p.B + 1) * sizeof(int32_t);
     hipError_t e;
     if (ev_start && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
-    if constexpr (!PADDED) {
+    bool launched = false;
+    if constexpr (!PADDED && D != 80) {
         if (valu) {
             lds = ((lds + 15) & ~(size_t)15) + (size_t)kWavesPerBlock * ValuLds<D>::bytes;
             // up to 32 KiB of prefix + 4 x 14 KiB of wave-private state: above the 64 KiB a
@@ -763,14 +786,12 @@ static hipError_t launch_typed(const AttnParams& p, int blocks, bool valu, hipSt
             }
             hipLaunchKernelGGL((verify_attention_kernel<ET, D, false, true>), dim3(blocks),
                                dim3(kAttnThreads), lds, stream, p);
-        } else {
-            hipLaunchKernelGGL((verify_attention_kernel<ET, D, false, false>), dim3(blocks),
-                               dim3(kAttnThreads), lds, stream, p);
+            launched = true;
         }
-    } else {
-        hipLaunchKernelGGL((verify_attention_kernel<ET, D, true, false>), dim3(blocks),
-                           dim3(kAttnThreads), lds, stream, p);
     }
+    if (!launched)
+        hipLaunchKernelGGL((verify_attention_kernel<ET, D, PADDED, false>), dim3(blocks),
+                           dim3(kAttnThreads), lds, stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
@@ -784,6 +805,10 @@ static hipError_t launch_layout(const AttnParams& p, int blocks, int D, bool bf1
                                 hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
     if (D == 128) return bf16 ? launch_typed<BF16, 128, PADDED>(p, blocks, valu, stream, ev_start, ev_stop)
                               : launch_typed<F16, 128, PADDED>(p, blocks, valu, stream, ev_start, ev_stop);
+    if constexpr (!PADDED) {
+        if (D == 80) return bf16 ? launch_typed<BF16, 80, false>(p, blocks, false, stream, ev_start, ev_stop)
+                                 : launch_typed<F16, 80, false>(p, blocks, false, stream, ev_start, ev_stop);
+    }
     return bf16 ? launch_typed<BF16, 64, PADDED>(p, blocks, valu, stream, ev_start, ev_stop)
                 : launch_typed<F16, 64, PADDED>(p, blocks, valu, stream, ev_start, ev_stop);
 }

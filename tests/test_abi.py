@@ -63,7 +63,7 @@ def attention(**over):
     (dict(out=FAKE + 2), ems.EMS_ERR_INVALID_ARG, "aligned"),
     (dict(cache=None), ems.EMS_ERR_INVALID_ARG, "cache"),
     (dict(cache=ems.KvCacheStruct(FAKE, FAKE, 4100, 128, 1024)), ems.EMS_ERR_INVALID_ARG, "strides"),
-    (dict(D=80), ems.EMS_ERR_UNSUPPORTED, "head dim"),
+    (dict(D=96), ems.EMS_ERR_UNSUPPORTED, "head dim"),
     (dict(max_k=17), ems.EMS_ERR_UNSUPPORTED, "rows per sample"),
     (dict(B=10000), ems.EMS_ERR_UNSUPPORTED, "samples"),
     (dict(max_kv_len=1 << 20), ems.EMS_ERR_UNSUPPORTED, "4 GiB"),
@@ -141,9 +141,9 @@ def test_write_through_and_advance_reject_bad_arguments_on_the_host():
     assert L.ems_kv_advance(FAKE, FAKE, FAKE, 0, None) == ems.EMS_ERR_INVALID_ARG
     assert L.ems_kv_advance(None, FAKE, FAKE, 4, None) == ems.EMS_ERR_INVALID_ARG
     cache = ems.KvCacheStruct(FAKE, FAKE, 4096, 128, 1024)
-    args = [FAKE, FAKE, FAKE, ctypes.byref(cache), FAKE, FAKE, FAKE, FAKE, ems.EMS_F16, 4, 8, 32, 80, 4,
+    args = [FAKE, FAKE, FAKE, ctypes.byref(cache), FAKE, FAKE, FAKE, FAKE, ems.EMS_F16, 4, 8, 32, 96, 4,
             100, 0.1, ems.EMS_F16, FAKE, 1 << 30, None]
-    assert L.ems_verify_attention_write_through(*args) == ems.EMS_ERR_UNSUPPORTED     # D = 80
+    assert L.ems_verify_attention_write_through(*args) == ems.EMS_ERR_UNSUPPORTED     # D = 96
     args[12] = 128
     args[9] = 0
     assert L.ems_verify_attention_write_through(*args) == ems.EMS_ERR_INVALID_ARG     # B = 0

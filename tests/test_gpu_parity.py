@@ -249,7 +249,7 @@ def test_verify_loop_of_several_steps():
 
 
 @pytest.mark.parametrize("layout", [TOKEN_MAJOR, HEAD_MAJOR])
-@pytest.mark.parametrize("dtype,D", [(torch.float16, 128), (torch.bfloat16, 64)])
+@pytest.mark.parametrize("dtype,D", [(torch.float16, 128), (torch.bfloat16, 64), (torch.bfloat16, 80)])
 def test_write_through_variant(layout, dtype, D):
     """Paper order: the attention call also stores every new row's K/V at the sample's own
     location; then only the lengths advance.  Output as for the plain call; cache bit-equal to
@@ -284,6 +284,21 @@ def test_opt_13b_head_count():
     b = make_batch([300, 1, 77], [4, 9, 1], H=40, D=128, dtype=torch.float16, seed=49)
     check_attention(b, out_dtype=torch.float32, label="H=40")
     run_accept_and_append(b)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("layout", [TOKEN_MAJOR, HEAD_MAJOR])
+def test_head_dim_80(dtype, layout):
+    """OPT-2.7b geometry (32 heads of 80): a head dim that is not a power of two.  Ragged
+    lengths over several tiles with tails, pairs merged from partials, the last row of the
+    last head at the very end of the arena, then accept and append on the same batch."""
+    b = make_batch(RAGGED_KV, RAGGED_K, H=4, D=80, dtype=dtype, seed=56, capacity=300, layout=layout)
+    check_attention(b, out_dtype=torch.float32, label="D=80 ragged f32 out")
+    check_attention(b, label="D=80 ragged 16-bit out")
+    big = make_batch([1500, 40, 2047], [7, 16, 1], H=32, D=80, dtype=dtype, seed=57, capacity=2048,
+                     kv_start=[0, 2048, 4096 + 0], rows=4096 + 2048, layout=layout)
+    check_attention(big, label="D=80 OPT-2.7b shape, arena filled to its last row")
+    run_accept_and_append(make_batch([300, 1, 77], [4, 9, 1], H=32, D=80, dtype=dtype, seed=58, layout=layout))
 
 
 def test_argmax_rows_of_minus_infinity():

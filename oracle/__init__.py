@@ -54,6 +54,14 @@ def _load():
             i32p, i32p, i32p, f64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_float, ctypes.c_int]
         lib.oracle_argmax.argtypes = [u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p]
+        lib.oracle_tree_verify_attention.argtypes = [
+            u16p, u16p, u16p, u16p, u16p, ctypes.c_int64, ctypes.c_int64,
+            i32p, i32p, i32p, i32p, f64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_float, ctypes.c_int]
+        lib.oracle_tree_accept.argtypes = [i32p, i32p, i32p, i32p, ctypes.c_int, i32p, i32p, i32p, i32p]
+        lib.oracle_kv_append_rows.argtypes = [
+            u16p, u16p, ctypes.c_int64, ctypes.c_int64, u16p, u16p,
+            i32p, i32p, i32p, i32p, i32p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         lib.oracle_greedy_accept.argtypes = [i32p, i32p, i32p, ctypes.c_int, i32p, i32p, i32p]
         lib.oracle_kv_append.argtypes = [
             u16p, u16p, ctypes.c_int64, ctypes.c_int64, u16p, u16p,
@@ -248,3 +256,75 @@ def kv_write_through(k_cache, v_cache, row_stride, head_stride, k_new, v_new, cu
         _p(k_cache, ctypes.c_uint16), _p(v_cache, ctypes.c_uint16), int(row_stride), int(head_stride),
         _p(k_new, ctypes.c_uint16), _p(v_new, ctypes.c_uint16), _p(cu, ctypes.c_int32),
         _p(ks, ctypes.c_int32), _p(kl, ctypes.c_int32), B, int(H), int(D))
+
+
+def tree_verify_attention(q, k_new, v_new, k_cache, v_cache, row_stride, head_stride,
+                          cu_seqlens, parent, kv_start, kv_len, H, D, scale, dtype) -> np.ndarray:
+    """fp64 [T, H, D] attention output under a per-sample token tree (parent[T]: index of the
+    parent row inside the sample, -1 for a sample's row 0)."""
+    q, k_new, v_new = _u16(q), _u16(k_new), _u16(v_new)
+    k_cache, v_cache = _u16(k_cache), _u16(v_cache)
+    cu, par, ks, kl = _i32(cu_seqlens), _i32(parent), _i32(kv_start), _i32(kv_len)
+    B = len(ks)
+    T = int(cu[B])
+    assert len(cu) == B + 1 and len(kl) == B and cu[0] == 0 and len(par) == T
+    assert q.size == T * H * D and k_new.size == T * H * D and v_new.size == T * H * D
+    for i in range(B):
+        if kl[i] > 0 and cu[i + 1] > cu[i]:
+            last = (int(ks[i]) + int(kl[i]) - 1) * row_stride + (H - 1) * head_stride + D - 1
+            assert 0 <= last < k_cache.size and last < v_cache.size, "cache region out of bounds"
+    out = np.zeros((T, H, D), dtype=np.float64)
+    rc = _load().oracle_tree_verify_attention(
+        _p(q, ctypes.c_uint16), _p(k_new, ctypes.c_uint16), _p(v_new, ctypes.c_uint16),
+        _p(k_cache, ctypes.c_uint16), _p(v_cache, ctypes.c_uint16),
+        int(row_stride), int(head_stride),
+        _p(cu, ctypes.c_int32), _p(par, ctypes.c_int32), _p(ks, ctypes.c_int32), _p(kl, ctypes.c_int32),
+        _p(out, ctypes.c_double), B, int(H), int(D), float(scale), _dt(dtype))
+    if rc == 2:
+        raise ValueError("parent[] is not a tree in topological order")
+    if rc:
+        raise MemoryError("oracle_tree_verify_attention ran out of memory")
+    return out
+
+
+def tree_accept(target_ids, input_ids, parent, cu_seqlens):
+    """Returns (accepted[B], accepted_cu[B+1], out_tokens[sum], accepted_rows[sum])."""
+    x, ids, par, cu = _i32(target_ids), _i32(input_ids), _i32(parent), _i32(cu_seqlens)
+    B = len(cu) - 1
+    T = int(cu[B])
+    assert len(x) == T and len(ids) == T and len(par) == T
+    acc = np.zeros(B, dtype=np.int32)
+    acc_cu = np.zeros(B + 1, dtype=np.int32)
+    out = np.full(max(T, 1), -1, dtype=np.int32)
+    rows = np.full(max(T, 1), -1, dtype=np.int32)
+    _load().oracle_tree_accept(_p(x, ctypes.c_int32), _p(ids, ctypes.c_int32), _p(par, ctypes.c_int32),
+                               _p(cu, ctypes.c_int32), B, _p(acc, ctypes.c_int32),
+                               _p(acc_cu, ctypes.c_int32), _p(out, ctypes.c_int32),
+                               _p(rows, ctypes.c_int32))
+    n = int(acc_cu[B])
+    return acc, acc_cu, out[:n].copy(), rows[:n].copy()
+
+
+def kv_append_rows(k_cache, v_cache, row_stride, head_stride, k_new, v_new,
+                   accepted_rows, accepted_cu, kv_start, kv_len, H, D) -> np.ndarray:
+    """Gathers the packed rows accepted_rows into the caches in place; returns kv_len_out."""
+    k_cache, v_cache = _u16(k_cache, True), _u16(v_cache, True)
+    k_new, v_new = _u16(k_new), _u16(v_new)
+    rows, acu, ks, kl = _i32(accepted_rows), _i32(accepted_cu), _i32(kv_start), _i32(kv_len)
+    B = len(ks)
+    assert len(acu) == B + 1 and len(rows) >= int(acu[B])
+    T = k_new.size // (H * D)
+    for i in range(B):
+        a = int(acu[i + 1] - acu[i])
+        assert a >= 0
+        if a > 0:
+            assert all(0 <= int(r) < T for r in rows[acu[i]:acu[i + 1]])
+            last = (int(ks[i]) + int(kl[i]) + a - 1) * row_stride + (H - 1) * head_stride + D - 1
+            assert last < k_cache.size and last < v_cache.size, "append beyond the arena"
+    out = np.zeros(B, dtype=np.int32)
+    _load().oracle_kv_append_rows(
+        _p(k_cache, ctypes.c_uint16), _p(v_cache, ctypes.c_uint16), int(row_stride),
+        int(head_stride), _p(k_new, ctypes.c_uint16), _p(v_new, ctypes.c_uint16),
+        _p(rows, ctypes.c_int32), _p(acu, ctypes.c_int32), _p(ks, ctypes.c_int32),
+        _p(kl, ctypes.c_int32), _p(out, ctypes.c_int32), B, int(H), int(D))
+    return out

@@ -23,7 +23,10 @@
  * Parity pins (tests/test_oracle_*.py): dense padded per-sample brute force,
  * torch's CPU attention in the k_i = 1 and kv_len = 0 special cases,
  * autoregressive equivalence, closed forms, the paper's Table 1, Alg. 2 run
- * literally, sentinel-filled arenas.  No function here is "parity unpinned".
+ * literally, sentinel-filled arenas; for the tree functions: reduction to the
+ * causal ones on a chain, causal attention along every root-to-row path, a dense
+ * brute force with a matrix-closure mask, a per-node validity rule for acceptance,
+ * a numpy gather for the append.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -374,6 +377,161 @@ int oracle_kv_write_through(uint16_t* k_cache, uint16_t* v_cache, int64_t row_st
                     k_cache[dst] = k_new[src];
                     v_cache[dst] = v_new[src];
                 }
+    }
+    return 0;
+}
+
+/*
+ * Tree-structured verification.  The paper names it as the next thing to combine with
+ * the multi-sample method (Limitations, item 4; Sec. 2 "Dynamic Tree decoding": several
+ * candidate tokens at the same position) and gives no algorithm of its own, so what
+ * follows is the usual statement of tree verification, sample by sample.
+ *
+ * The k_i new rows of sample i form a token tree: row 0 (the last emitted token) is the
+ * root and row j > 0 continues the row parent[cu[i]+j], a row of the same sample with a
+ * smaller index (parent[cu[i]] = -1).  A root-to-node path is one candidate continuation.
+ *
+ * Attention: row j sees every cached key of its sample and, among the new rows, itself
+ * and its ancestors only:   mask[L + jj] = (jj is j or an ancestor of j).
+ * With parent[j] = j-1 (a chain) this is the causal mask of oracle_verify_attention.
+ * Returns 0, 1 on memory exhaustion, 2 when parent[] is not a tree in topological order.
+ */
+int oracle_tree_verify_attention(const uint16_t* q, const uint16_t* k_new, const uint16_t* v_new,
+                                 const uint16_t* k_cache, const uint16_t* v_cache,
+                                 int64_t row_stride, int64_t head_stride,
+                                 const int32_t* cu, const int32_t* parent,
+                                 const int32_t* kv_start, const int32_t* kv_len,
+                                 double* out, int B, int H, int D, float scale, int dtype) {
+    for (int i = 0; i < B; ++i) {
+        const int k = cu[i + 1] - cu[i];
+        for (int j = 0; j < k; ++j) {
+            const int pj = parent[cu[i] + j];
+            if (j == 0 ? pj != -1 : (pj < 0 || pj >= j)) return 2;
+        }
+    }
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int i = 0; i < B; ++i) {
+        for (int h = 0; h < H; ++h) {
+            const int k = cu[i + 1] - cu[i];
+            const int L = kv_len[i];
+            const int64_t s = kv_start[i];
+            const int N = L + k;
+            if (k <= 0) continue;
+            double* key = (double*)malloc(sizeof(double) * (size_t)N * D);
+            double* val = (double*)malloc(sizeof(double) * (size_t)N * D);
+            double* S = (double*)malloc(sizeof(double) * (size_t)N);
+            double* p = (double*)malloc(sizeof(double) * (size_t)N);
+            unsigned char* mask = (unsigned char*)malloc((size_t)N);
+            if (!key || !val || !S || !p || !mask) {
+#pragma omp atomic write
+                failed = 1;
+                free(key); free(val); free(S); free(p); free(mask);
+                continue;
+            }
+            for (int n = 0; n < N; ++n) {
+                for (int d = 0; d < D; ++d) {
+                    int64_t off = n < L ? (s + n) * row_stride + (int64_t)h * head_stride + d
+                                        : ((int64_t)(cu[i] + n - L) * H + h) * D + d;
+                    key[(size_t)n * D + d] = widen(n < L ? k_cache[off] : k_new[off], dtype);
+                    val[(size_t)n * D + d] = widen(n < L ? v_cache[off] : v_new[off], dtype);
+                }
+            }
+            for (int j = 0; j < k; ++j) {
+                const int64_t qoff = ((int64_t)(cu[i] + j) * H + h) * D;
+                for (int n = 0; n < N; ++n) mask[n] = (unsigned char)(n < L);
+                for (int u = j; u >= 0; u = parent[cu[i] + u]) mask[L + u] = 1;   /* j, then its ancestors */
+                double m = -INFINITY;
+                for (int n = 0; n < N; ++n) {
+                    if (mask[n]) {
+                        double dot = 0.0;
+                        for (int d = 0; d < D; ++d)
+                            dot += widen(q[qoff + d], dtype) * key[(size_t)n * D + d];
+                        S[n] = (double)scale * dot;
+                    } else {
+                        S[n] = -INFINITY;
+                    }
+                    if (S[n] > m) m = S[n];
+                }
+                double Z = 0.0;
+                for (int n = 0; n < N; ++n) {
+                    p[n] = mask[n] ? exp(S[n] - m) : 0.0;
+                    Z += p[n];
+                }
+                for (int d = 0; d < D; ++d) {
+                    double acc = 0.0;
+                    for (int n = 0; n < N; ++n) acc += p[n] * val[(size_t)n * D + d];
+                    out[qoff + d] = acc / Z;
+                }
+            }
+            free(key); free(val); free(S); free(p); free(mask);
+        }
+    }
+    return failed;
+}
+
+/*
+ * Greedy acceptance along the tree: starting at the root, the target's greedy token after
+ * the current row, x[row], is looked for among the tokens of that row's children; the
+ * matching child (the lowest-indexed one if several carry the same token) is accepted and
+ * becomes the current row; the walk ends at a row none of whose children matches.
+ *   accepted[i]      = number of rows on the accepted path (root included), 0 when k_i = 0
+ *   out_tokens       = x at the rows of the path, packed sample after sample
+ *   accepted_rows    = the packed row index cu[i] + j of every row of the path, same packing
+ * With a chain this is oracle_greedy_accept, and accepted_rows = cu[i], cu[i]+1, ...
+ */
+int oracle_tree_accept(const int32_t* x, const int32_t* input_ids, const int32_t* parent,
+                       const int32_t* cu, int B, int32_t* accepted, int32_t* accepted_cu,
+                       int32_t* out_tokens, int32_t* accepted_rows) {
+    accepted_cu[0] = 0;
+    for (int i = 0; i < B; ++i) {
+        const int k = cu[i + 1] - cu[i];
+        int tau = 0;
+        if (k > 0) {
+            int u = 0;
+            for (;;) {
+                if (out_tokens) out_tokens[accepted_cu[i] + tau] = x[cu[i] + u];
+                if (accepted_rows) accepted_rows[accepted_cu[i] + tau] = cu[i] + u;
+                tau += 1;
+                int next = -1;
+                for (int c = u + 1; c < k && next < 0; ++c)
+                    if (parent[cu[i] + c] == u && input_ids[cu[i] + c] == x[cu[i] + u]) next = c;
+                if (next < 0) break;
+                u = next;
+            }
+        }
+        accepted[i] = tau;
+        accepted_cu[i + 1] = accepted_cu[i] + tau;
+    }
+    return 0;
+}
+
+/*
+ * Append of an accepted path: the rows of a path are not contiguous in the packed tensors,
+ * so the copy gathers them: cache row kv_start[i]+kv_len[i]+j receives, bit for bit, packed
+ * row accepted_rows[accepted_cu[i]+j], j < accepted[i] = accepted_cu[i+1]-accepted_cu[i];
+ * kv_len_out[i] = kv_len[i] + accepted[i].  Nothing else in the arena is written
+ * (Sec. 3.2 "Unpad KV cache": each sample advances by its own count).
+ */
+int oracle_kv_append_rows(uint16_t* k_cache, uint16_t* v_cache, int64_t row_stride, int64_t head_stride,
+                          const uint16_t* k_new, const uint16_t* v_new,
+                          const int32_t* accepted_rows, const int32_t* accepted_cu,
+                          const int32_t* kv_start, const int32_t* kv_len, int32_t* kv_len_out,
+                          int B, int H, int D) {
+    for (int i = 0; i < B; ++i) {
+        const int a = accepted_cu[i + 1] - accepted_cu[i];
+        for (int j = 0; j < a; ++j) {
+            const int64_t dst_row = (int64_t)kv_start[i] + kv_len[i] + j;
+            const int64_t src_row = accepted_rows[accepted_cu[i] + j];
+            for (int h = 0; h < H; ++h)
+                for (int d = 0; d < D; ++d) {
+                    int64_t dst = dst_row * row_stride + (int64_t)h * head_stride + d;
+                    int64_t src = (src_row * H + h) * D + d;
+                    k_cache[dst] = k_new[src];
+                    v_cache[dst] = v_new[src];
+                }
+        }
+        if (kv_len_out) kv_len_out[i] = kv_len[i] + a;
     }
     return 0;
 }

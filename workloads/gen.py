@@ -65,6 +65,7 @@ class VerifyBatch:
     max_k: int
     max_kv_len: int
     name: str = ""
+    parent: Optional[torch.Tensor] = None     # [T] i32, token trees only: parent row inside the sample, -1 for row 0
 
     def clone_caches(self):
         return self.k_cache.clone(), self.v_cache.clone()
@@ -181,6 +182,54 @@ def make_batch(kv_len: Sequence[int], k: Sequence[int], *, H: int, D: int,
         q=q, k_new=k_new, v_new=v_new, k_cache=k_cache, v_cache=v_cache, logits=logits,
         target_ids=target_ids.to(torch.int32).to(dev), input_ids=input_ids.to(torch.int32).to(dev),
         max_k=max(k) if k else 0, max_kv_len=max(kv_len) if kv_len else 0, name=name)
+
+
+def grow_trees(b: VerifyBatch, seed: int, match_p: float = 0.7, shape: str = "random",
+               duplicate_p: float = 0.15) -> VerifyBatch:
+    """The same batch with its new rows arranged as one token tree per sample (inputs of
+    tree-structured verification).  Row 0 of a sample is the root; parent[j] < j.
+      shape "random": parent drawn uniformly among the earlier rows (bushy, Medusa-like mixes);
+            "chain" : parent[j] = j - 1 (ordinary drafts);
+            "star"  : every row hangs off the root (many candidates for one position);
+            "wide"  : parent drawn among the last three rows (several long branches).
+    input_ids are redrawn to fit the tree: with probability match_p one child of a row (picked
+    at random) carries that row's target token, the other children carry other tokens that
+    differ from it; with probability duplicate_p a later sibling repeats an earlier sibling's
+    token (so that "the lowest-indexed matching child" is exercised).  target_ids, logits and
+    everything else are shared with `b`."""
+    import dataclasses
+    rng = np.random.default_rng(seed)
+    cu = b.cu_seqlens.cpu().numpy()
+    x = b.target_ids.cpu().numpy()
+    ids = b.input_ids.cpu().numpy().copy()
+    vocab = int(max(2, b.V if b.V else max(int(x.max(initial=0)), int(ids.max(initial=0))) + 1))
+    parent = np.full(len(x), -1, dtype=np.int32)
+    for i in range(b.B):
+        c0, k = int(cu[i]), int(cu[i + 1] - cu[i])
+        for j in range(1, k):
+            if shape == "chain":
+                parent[c0 + j] = j - 1
+            elif shape == "star":
+                parent[c0 + j] = 0
+            elif shape == "wide":
+                parent[c0 + j] = int(rng.integers(max(0, j - 3), j))
+            else:
+                parent[c0 + j] = int(rng.integers(0, j))
+        for u in range(k):
+            kids = [c for c in range(u + 1, k) if parent[c0 + c] == u]
+            if not kids:
+                continue
+            lucky = kids[int(rng.integers(0, len(kids)))] if rng.random() < match_p else -1
+            for n_c, c in enumerate(kids):
+                if c == lucky:
+                    ids[c0 + c] = x[c0 + u]
+                elif n_c > 0 and rng.random() < duplicate_p:
+                    ids[c0 + c] = ids[c0 + kids[int(rng.integers(0, n_c))]]
+                else:
+                    ids[c0 + c] = (int(x[c0 + u]) + 1 + int(rng.integers(0, vocab - 1))) % vocab
+    dev = b.input_ids.device
+    return dataclasses.replace(b, input_ids=torch.from_numpy(ids).to(torch.int32).to(dev),
+                               parent=torch.from_numpy(parent).to(dev), name=b.name + "+tree:" + shape)
 
 
 def draw_lengths(n: int, seed: int):

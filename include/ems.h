@@ -112,9 +112,9 @@ EMS_API ems_status ems_verify_attention(
     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * Paper-order variant of the step (Sec. 3.2: "for each input token, we initially compute its
- * KV cache and subsequently write it to memory based on the specified position for each
- * sample"; afterwards the sample's location advances by its accepted count).
+ * Paper-order variant of the step (Sec. 3.2, "Unpad KV cache": the K/V of every input token
+ * is written at its sample's own position before attention runs; after verification the
+ * sample's location advances by its accepted count).
  * ems_verify_attention_write_through computes exactly what ems_verify_attention computes and
  * ALSO stores all k_i new rows' K/V into the cache at rows kv_start[i]+kv_len[i]+j, j < k_i
  * (those rows must lie inside the sample's region and outside every other sample's).
@@ -232,6 +232,55 @@ EMS_API ems_status ems_validate_inputs(
  */
 EMS_API ems_status ems_profile_enable(int max_records);
 EMS_API ems_status ems_profile_read(double* total_ms, int* launches);
+
+/*
+ * Tree-structured verification.  The paper names tree decoding as the next thing to combine
+ * with the multi-sample method (Limitations, item 4; Sec. 2 "Dynamic Tree decoding") and
+ * gives no algorithm; these three calls are the usual definition, per sample, on the same
+ * packed / per-sample-cache layout.
+ *
+ *   parent   device int32 [T]: the k_i new rows of sample i form a token tree; row 0 (the
+ *            last emitted token) is the root, parent[cu_seqlens[i]] = -1, and row j > 0
+ *            continues row parent[cu_seqlens[i]+j] of the same sample, 0 <= parent < j.
+ *            A chain (parent = j-1) is ordinary speculative decoding.  An entry outside
+ *            [0, j) is treated as "no parent" by the attention call and matches no row in
+ *            the accept call; k_i <= EMS_MAX_QUERY_ROWS as everywhere.
+ *
+ * ems_tree_verify_attention: as ems_verify_attention (same arguments, workspace and errors),
+ *   except that among the new rows row j sees itself and its ancestors only (every cached row
+ *   is still visible).  Not available with EMS_ATTN_VALU (UNSUPPORTED).
+ * ems_tree_accept: as ems_greedy_accept (same arguments, workspace and errors), except that
+ *   acceptance walks the tree: from row 0, step to the lowest-indexed child of the current row
+ *   whose input token equals the target's token after the current row; stop when no child
+ *   matches.  accepted[i] = rows on that path (>= 1; 0 if k_i = 0); out_tokens = the target's
+ *   tokens after the rows of the path; accepted_rows (device int32 [T] or NULL) = the packed
+ *   row index of every row of the path, both packed sample after sample at accepted_cu.
+ * ems_kv_append_rows: as ems_kv_append, for rows that are not a prefix: cache row
+ *   kv_start[i]+kv_len[i]+j receives packed row accepted_rows[accepted_cu[i]+j] of every layer,
+ *   j < accepted_cu[i+1]-accepted_cu[i]; kv_len_out[i] = kv_len[i] + that count (may alias
+ *   kv_len, may be NULL).  An index outside [0, T) copies nothing.
+ */
+EMS_API ems_status ems_tree_verify_attention(
+    const void* q, const void* k_new, const void* v_new,
+    const ems_kv_cache* cache,
+    const int32_t* cu_seqlens, const int32_t* parent,
+    const int32_t* kv_start, const int32_t* kv_len,
+    void* out, ems_dtype out_dtype,
+    int B, int T, int H, int D, int max_k, int max_kv_len,
+    float scale, ems_dtype dtype,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+EMS_API ems_status ems_tree_accept(
+    const void* logits, ems_dtype dtype, int V,
+    int32_t* target_ids, const int32_t* input_ids, const int32_t* parent,
+    const int32_t* cu_seqlens, int B, int T,
+    int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens, int32_t* accepted_rows,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+EMS_API ems_status ems_kv_append_rows(
+    const void* const* k_new_layers, const void* const* v_new_layers,
+    const ems_kv_cache* caches, int n_layers,
+    const int32_t* accepted_rows, const int32_t* accepted_cu,
+    const int32_t* kv_start, const int32_t* kv_len, int32_t* kv_len_out,
+    int B, int T, int H, int D, ems_dtype dtype, void* hip_stream);
 
 /*
  * Measurement aid: one launch of a plain read-only streaming kernel over `bytes` bytes of

@@ -63,6 +63,16 @@ def lib() -> ctypes.CDLL:
         L.ems_verify_attention_write_through.argtypes = L.ems_verify_attention.argtypes
         L.ems_kv_advance.restype = i32
         L.ems_kv_advance.argtypes = [vp, vp, vp, i32, vp]
+        L.ems_tree_verify_attention.restype = i32
+        L.ems_tree_verify_attention.argtypes = [vp, vp, vp, ctypes.POINTER(KvCacheStruct), vp, vp, vp, vp,
+                                                vp, i32, i32, i32, i32, i32, i32, i32,
+                                                ctypes.c_float, i32, vp, sz, vp]
+        L.ems_tree_accept.restype = i32
+        L.ems_tree_accept.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.ems_kv_append_rows.restype = i32
+        L.ems_kv_append_rows.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                         ctypes.POINTER(KvCacheStruct), i32, vp, vp, vp, vp, vp,
+                                         i32, i32, i32, i32, i32, vp]
         L.ems_greedy_accept.restype = i32
         L.ems_greedy_accept.argtypes = [vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
         L.ems_kv_append.restype = i32
@@ -165,6 +175,49 @@ def ems_kv_append(k_new_layers: Sequence[torch.Tensor], v_new_layers: Sequence[t
                                _DT[k_new_layers[0].dtype], _stream(stream)))
 
 
+def ems_tree_verify_attention(q, k_new, v_new, cache: KvCacheStruct, cu_seqlens, parent, kv_start,
+                              kv_len, out, *, max_k: int, max_kv_len: int, scale: float,
+                              workspace: torch.Tensor, stream=None) -> None:
+    """As ems_verify_attention, with a per-sample token tree: parent[T] int32."""
+    T, H, D = q.shape
+    B = kv_start.numel()
+    _check(lib().ems_tree_verify_attention(
+        _ptr(q), _ptr(k_new), _ptr(v_new), ctypes.byref(cache), _ptr(cu_seqlens), _ptr(parent),
+        _ptr(kv_start), _ptr(kv_len), _ptr(out), _DT[out.dtype], B, T, H, D, int(max_k),
+        int(max_kv_len), float(scale), _DT[q.dtype], _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ems_tree_accept(logits: Optional[torch.Tensor], target_ids, input_ids, parent, cu_seqlens,
+                    accepted, accepted_cu, out_tokens: Optional[torch.Tensor],
+                    accepted_rows: Optional[torch.Tensor], *,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    B = accepted.numel()
+    T = input_ids.numel()
+    V = logits.shape[1] if logits is not None else 0
+    dt = _DT[logits.dtype] if logits is not None else EMS_F16
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().ems_tree_accept(
+        _ptr(logits), dt, V, _ptr(target_ids), _ptr(input_ids), _ptr(parent), _ptr(cu_seqlens), B, T,
+        _ptr(accepted), _ptr(accepted_cu), _ptr(out_tokens), _ptr(accepted_rows), _ptr(workspace),
+        ws_bytes, _stream(stream)))
+
+
+def ems_kv_append_rows(k_new_layers: Sequence[torch.Tensor], v_new_layers: Sequence[torch.Tensor],
+                       caches: Sequence[KvCacheStruct], accepted_rows, accepted_cu, kv_start, kv_len,
+                       kv_len_out: Optional[torch.Tensor], stream=None) -> None:
+    n = len(caches)
+    assert len(k_new_layers) == n and len(v_new_layers) == n
+    T, H, D = k_new_layers[0].shape
+    B = kv_start.numel()
+    karr = (ctypes.c_void_p * n)(*[t.data_ptr() for t in k_new_layers])
+    varr = (ctypes.c_void_p * n)(*[t.data_ptr() for t in v_new_layers])
+    carr = (KvCacheStruct * n)(*caches)
+    _check(lib().ems_kv_append_rows(karr, varr, carr, n, _ptr(accepted_rows), _ptr(accepted_cu),
+                                    _ptr(kv_start), _ptr(kv_len), _ptr(kv_len_out), B, T, H, D,
+                                    _DT[k_new_layers[0].dtype], _stream(stream)))
+
+
 def ems_verify_attention_write_through(q, k_new, v_new, cache, cu_seqlens, kv_start, kv_len, out, **kw) -> None:
     ems_verify_attention(q, k_new, v_new, cache, cu_seqlens, kv_start, kv_len, out, write_through=True, **kw)
 
@@ -236,6 +289,6 @@ def ems_profile_read():
     return ms.value, n.value
 
 
-__all__ = ["ems_stream_read_probe", "ems_set_attention_variant", "ems_get_attention_variant", "EMS_ATTN_MFMA", "EMS_ATTN_VALU", "ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
+__all__ = ["ems_tree_verify_attention", "ems_tree_accept", "ems_kv_append_rows", "ems_stream_read_probe", "ems_set_attention_variant", "ems_get_attention_variant", "EMS_ATTN_MFMA", "EMS_ATTN_VALU", "ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
            "ems_accept_workspace_bytes", "ems_verify_attention", "ems_greedy_accept",
            "ems_kv_append", "ems_validate_inputs", "EMS_F16", "EMS_BF16", "EMS_F32"]

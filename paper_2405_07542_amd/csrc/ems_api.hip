@@ -125,7 +125,7 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
                          ems_dtype out_dtype, int B, int T, int H, int D, int max_k,
                          int max_kv_len, float scale, ems_dtype dtype, void* workspace,
                          size_t workspace_bytes, void* hip_stream, const PaddedArgs* pad,
-                         bool write_through = false) {
+                         bool write_through = false, const int32_t* parent = nullptr) {
     if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
     if (T < 0) return fail(EMS_ERR_INVALID_ARG, "T = %d, need T >= 0", T);
     if (H < 1) return fail(EMS_ERR_INVALID_ARG, "H = %d, need H >= 1", H);
@@ -180,6 +180,7 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     p.cu = cu_seqlens;
     p.kv_start = kv_start;
     p.kv_len = kv_len;
+    p.parent = parent;
     p.out = out;
     p.ws_header = static_cast<int32_t*>(workspace);
     p.ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + attn_ws_header_bytes(B));
@@ -238,12 +239,27 @@ ems_status ems_verify_attention_write_through(const void* q, const void* k_new, 
                          hip_stream, nullptr, true);
 }
 
+ems_status ems_tree_verify_attention(const void* q, const void* k_new, const void* v_new,
+                                     const ems_kv_cache* cache, const int32_t* cu_seqlens,
+                                     const int32_t* parent, const int32_t* kv_start,
+                                     const int32_t* kv_len, void* out, ems_dtype out_dtype, int B,
+                                     int T, int H, int D, int max_k, int max_kv_len, float scale,
+                                     ems_dtype dtype, void* workspace, size_t workspace_bytes,
+                                     void* hip_stream) {
+    if (!parent && T > 0) return fail(EMS_ERR_INVALID_ARG, "parent must not be NULL");
+    if (g_attn_variant.load() == EMS_ATTN_VALU)
+        return fail(EMS_ERR_UNSUPPORTED, "EMS_ATTN_VALU has no token-tree mask");
+    return run_attention(q, k_new, v_new, cache, cu_seqlens, kv_start, kv_len, out, out_dtype, B, T,
+                         H, D, max_k, max_kv_len, scale, dtype, workspace, workspace_bytes,
+                         hip_stream, nullptr, false, parent);
+}
+
 ems_status ems_kv_advance(const int32_t* kv_len, const int32_t* accepted, int32_t* kv_len_out, int B,
                           void* hip_stream) {
     if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
     if (!kv_len || !accepted || !kv_len_out)
         return fail(EMS_ERR_INVALID_ARG, "kv_len, accepted and kv_len_out must not be NULL");
-    hipError_t e = ems::launch_advance_kv_len(kv_len, accepted, kv_len_out, B,
+    hipError_t e = ems::launch_advance_kv_len(kv_len, accepted, nullptr, kv_len_out, B,
                                               static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return hip_fail("ems_kv_advance launch", e);
     return EMS_OK;
@@ -280,10 +296,16 @@ size_t ems_accept_workspace_bytes(int T, int V) {
     return (size_t)T * 16 * sizeof(ems::ArgmaxPartial);
 }
 
-ems_status ems_greedy_accept(const void* logits, ems_dtype dtype, int V, int32_t* target_ids,
-                             const int32_t* input_ids, const int32_t* cu_seqlens, int B, int T,
-                             int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens,
-                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Shared by ems_greedy_accept (parent == nullptr) and ems_tree_accept.
+ems_status run_accept(const void* logits, ems_dtype dtype, int V, int32_t* target_ids,
+                      const int32_t* input_ids, const int32_t* parent, const int32_t* cu_seqlens,
+                      int B, int T, int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens,
+                      int32_t* accepted_rows, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
     if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
     if (T < 0) return fail(EMS_ERR_INVALID_ARG, "T = %d, need T >= 0", T);
     if (V < 0) return fail(EMS_ERR_INVALID_ARG, "V = %d, need V >= 0", V);
@@ -319,9 +341,40 @@ ems_status ems_greedy_accept(const void* logits, ems_dtype dtype, int V, int32_t
     p.accepted = accepted;
     p.accepted_cu = accepted_cu;
     p.out_tokens = out_tokens;
+    p.parent = parent;
+    p.accepted_rows = accepted_rows;
     hipError_t e = ems::launch_greedy_accept(p, static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) return hip_fail("ems_greedy_accept launch", e);
+    if (e != hipSuccess) return hip_fail("accept launch", e);
     return EMS_OK;
+}
+
+// Shared by ems_kv_append (rows == nullptr) and ems_kv_append_rows (cu_seqlens, accepted unused).
+ems_status run_append(const void* const* k_new_layers, const void* const* v_new_layers,
+                      const ems_kv_cache* caches, int n_layers, const int32_t* cu_seqlens,
+                      const int32_t* accepted, const int32_t* rows, const int32_t* rows_cu,
+                      const int32_t* kv_start, const int32_t* kv_len, int32_t* kv_len_out, int B,
+                      int T, int H, int D, ems_dtype dtype, void* hip_stream);
+
+}  // namespace
+
+extern "C" {
+
+ems_status ems_greedy_accept(const void* logits, ems_dtype dtype, int V, int32_t* target_ids,
+                             const int32_t* input_ids, const int32_t* cu_seqlens, int B, int T,
+                             int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run_accept(logits, dtype, V, target_ids, input_ids, nullptr, cu_seqlens, B, T, accepted,
+                      accepted_cu, out_tokens, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+ems_status ems_tree_accept(const void* logits, ems_dtype dtype, int V, int32_t* target_ids,
+                           const int32_t* input_ids, const int32_t* parent,
+                           const int32_t* cu_seqlens, int B, int T, int32_t* accepted,
+                           int32_t* accepted_cu, int32_t* out_tokens, int32_t* accepted_rows,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (T > 0 && !parent) return fail(EMS_ERR_INVALID_ARG, "parent must not be NULL");
+    return run_accept(logits, dtype, V, target_ids, input_ids, parent, cu_seqlens, B, T, accepted,
+                      accepted_cu, out_tokens, accepted_rows, workspace, workspace_bytes, hip_stream);
 }
 
 ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_new_layers,
@@ -329,6 +382,32 @@ ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_n
                          const int32_t* accepted, const int32_t* kv_start, const int32_t* kv_len,
                          int32_t* kv_len_out, int B, int T, int H, int D, ems_dtype dtype,
                          void* hip_stream) {
+    if (!cu_seqlens || !accepted)
+        return fail(EMS_ERR_INVALID_ARG, "cu_seqlens, accepted, kv_start and kv_len must not be NULL");
+    return run_append(k_new_layers, v_new_layers, caches, n_layers, cu_seqlens, accepted, nullptr,
+                      nullptr, kv_start, kv_len, kv_len_out, B, T, H, D, dtype, hip_stream);
+}
+
+ems_status ems_kv_append_rows(const void* const* k_new_layers, const void* const* v_new_layers,
+                              const ems_kv_cache* caches, int n_layers, const int32_t* accepted_rows,
+                              const int32_t* accepted_cu, const int32_t* kv_start,
+                              const int32_t* kv_len, int32_t* kv_len_out, int B, int T, int H, int D,
+                              ems_dtype dtype, void* hip_stream) {
+    if (!accepted_rows || !accepted_cu)
+        return fail(EMS_ERR_INVALID_ARG, "accepted_rows and accepted_cu must not be NULL");
+    return run_append(k_new_layers, v_new_layers, caches, n_layers, nullptr, nullptr, accepted_rows,
+                      accepted_cu, kv_start, kv_len, kv_len_out, B, T, H, D, dtype, hip_stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+ems_status run_append(const void* const* k_new_layers, const void* const* v_new_layers,
+                      const ems_kv_cache* caches, int n_layers, const int32_t* cu_seqlens,
+                      const int32_t* accepted, const int32_t* rows, const int32_t* rows_cu,
+                      const int32_t* kv_start, const int32_t* kv_len, int32_t* kv_len_out, int B,
+                      int T, int H, int D, ems_dtype dtype, void* hip_stream) {
     if (n_layers < 1) return fail(EMS_ERR_INVALID_ARG, "n_layers = %d, need n_layers >= 1", n_layers);
     if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
     if (B > 65535 * 32) return fail(EMS_ERR_UNSUPPORTED, "B = %d is too large", B);
@@ -338,7 +417,7 @@ ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_n
     if (!dtype16(dtype)) return fail(EMS_ERR_INVALID_ARG, "dtype must be EMS_F16 or EMS_BF16");
     if (!k_new_layers || !v_new_layers || !caches)
         return fail(EMS_ERR_INVALID_ARG, "layer arrays must not be NULL");
-    if (!cu_seqlens || !accepted || !kv_start || !kv_len)
+    if (!kv_start || !kv_len)
         return fail(EMS_ERR_INVALID_ARG, "cu_seqlens, accepted, kv_start and kv_len must not be NULL");
     for (int l = 0; l < n_layers; ++l) {
         const ems_kv_cache& c = caches[l];
@@ -369,6 +448,9 @@ ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_n
             }
             p.cu = cu_seqlens;
             p.accepted = accepted;
+            p.rows = rows;
+            p.rows_cu = rows_cu;
+            p.T = T;
             p.kv_start = kv_start;
             p.kv_len = kv_len;
             p.kv_len_out = (lengths_pending && !in_place) ? kv_len_out : nullptr;
@@ -381,11 +463,15 @@ ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_n
         }
     }
     if (lengths_pending) {
-        hipError_t e = ems::launch_advance_kv_len(kv_len, accepted, kv_len_out, B, stream);
+        hipError_t e = ems::launch_advance_kv_len(kv_len, accepted, rows_cu, kv_len_out, B, stream);
         if (e != hipSuccess) return hip_fail("ems_kv_append length update launch", e);
     }
     return EMS_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 ems_status ems_padded_kv_append(const void* const* k_new_pad_layers,
                                 const void* const* v_new_pad_layers, const ems_kv_cache* caches,

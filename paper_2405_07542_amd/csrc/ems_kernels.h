@@ -21,6 +21,8 @@ struct AttnParams {
     const int32_t* cu;
     const int32_t* kv_start;
     const int32_t* kv_len;
+    const int32_t* parent;     // [T] or nullptr: token trees -- row j of a sample continues row parent[j] < j of
+                               // the same sample (-1 for row 0) and sees, among the new rows, itself and its ancestors
     void* out;
     int32_t* ws_header;        // workspace header: the B+1 tile prefix sums, for the merge kernel
     float* ws;                 // 2 * num_waves partial slots of 16 x (D + kPartialPad) floats
@@ -63,6 +65,10 @@ struct AcceptParams {
     int32_t* accepted;
     int32_t* accepted_cu;
     int32_t* out_tokens;       // may be nullptr
+    // token trees (parent != nullptr): acceptance walks from row 0 to the child that carries the
+    // target's token; accepted_rows receives the packed row index of every row of the accepted path
+    const int32_t* parent;
+    int32_t* accepted_rows;    // may be nullptr
 };
 
 hipError_t launch_greedy_accept(const AcceptParams& p, hipStream_t stream);
@@ -81,6 +87,11 @@ struct AppendParams {
     int n_layers;
     const int32_t* cu;
     const int32_t* accepted;
+    // gathered append (rows != nullptr): sample i appends packed rows rows[rows_cu[i] .. rows_cu[i+1])
+    // instead of its first accepted[i] rows; cu and accepted are then unused
+    const int32_t* rows;
+    const int32_t* rows_cu;
+    int T;                     // packed rows in k_new / v_new (gathered row indices are checked against it)
     const int32_t* kv_start;
     const int32_t* kv_len;
     int32_t* kv_len_out;       // written by this launch when non-null (must not alias kv_len)
@@ -101,7 +112,8 @@ struct PaddedAppendParams {
 
 hipError_t launch_kv_append(const AppendParams& p, hipStream_t stream);
 hipError_t launch_padded_kv_append(const PaddedAppendParams& p, hipStream_t stream);
-hipError_t launch_advance_kv_len(const int32_t* kv_len, const int32_t* accepted,
+// kv_len_out[i] = kv_len[i] + accepted[i], or + (rows_cu[i+1] - rows_cu[i]) when accepted is null
+hipError_t launch_advance_kv_len(const int32_t* kv_len, const int32_t* accepted, const int32_t* rows_cu,
                                  int32_t* kv_len_out, int B, hipStream_t stream);
 
 // Read-only streaming probe over `bytes` of device memory (whole 1 KiB lines); sink: one word.

@@ -11,6 +11,9 @@
 //      block-wide exclusive scan of the lengths, packed copy of accepted tokens.
 // Comparisons are on exactly widened values, so results are bit-exact; ties go
 // to the lowest index at every merge level.
+// With a parent array (token trees) step 2 walks from each sample's row 0 to the child
+// that carries the target's token instead of counting leading matches, and also
+// reports which packed rows form the accepted path.
 #include "ems_device.h"
 #include "ems_kernels.h"
 
@@ -89,6 +92,30 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptPa
 
 constexpr int kMaxAcceptB = 8192;
 
+// Acceptance along a token tree, one wave per sample (k <= 64 rows, lane j = row j): from row
+// 0, step to the lowest-indexed child of the current row whose token equals the target's
+// token after that row; stop when no child matches.  `emit(step, row)` is called once per
+// accepted row, in path order.  Children have larger indices than their parents, so the
+// walk moves strictly upward and ends after at most k steps whatever parent[] holds.
+template <typename Emit>
+__device__ __forceinline__ int tree_walk(const AcceptParams& p, int base, int k, int lane, Emit emit) {
+    if (k <= 0) return 0;
+    const bool in = lane < k;
+    const int pj = in ? p.parent[base + lane] : -2;
+    const int idj = in ? p.input_ids[base + lane] : 0;
+    const int xj = in ? p.target_ids[base + lane] : 0;
+    int u = 0, a = 0;
+    for (;;) {
+        emit(a, u);
+        ++a;
+        const int xu = __shfl(xj, u);
+        const uint64_t m = __builtin_amdgcn_ballot_w64(in && lane > u && pj == u && idj == xu);
+        if (m == 0 || a >= k) break;
+        u = __builtin_ctzll(m);
+    }
+    return a;
+}
+
 __global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParams p) {
     __shared__ int32_t acc_s[kMaxAcceptB];
     __shared__ int32_t wave_tot[kAcceptThreads / kWave];
@@ -107,10 +134,19 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParam
         __syncthreads();
     }
 
+    const bool tree = p.parent != nullptr;
     // one wave per sample: count the leading drafts that match the target's tokens
     for (int i = wid; i < p.B; i += kAcceptThreads / kWave) {
         const int base = p.cu[i];
         const int k = p.cu[i + 1] - base;
+        if (tree) {
+            const int a = tree_walk(p, base, min(k, kWave), lane, [](int, int) {});
+            if (lane == 0) {
+                acc_s[i] = a;
+                p.accepted[i] = a;
+            }
+            continue;
+        }
         int m = 0;
         for (int c0 = 0; c0 < k - 1; c0 += kWave) {
             const int j = c0 + lane;
@@ -152,12 +188,29 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParam
         if (i >= p.B) break;
         const int a = acc_s[i];
         p.accepted_cu[i] = run;
-        if (p.out_tokens != nullptr) {
+        if (tree) {
+            acc_s[i] = run;                     // the walk below needs the sample's offset
+        } else if (p.out_tokens != nullptr) {
             const int base = p.cu[i];
             for (int j = 0; j < a; ++j) p.out_tokens[run + j] = p.target_ids[base + j];
         }
         run += a;
         if (i == p.B - 1) p.accepted_cu[p.B] = run;
+    }
+    if (!tree || (p.out_tokens == nullptr && p.accepted_rows == nullptr)) return;
+    __syncthreads();
+    // token trees: the accepted rows are not a prefix of the sample's rows; walk again, now
+    // that every sample knows where its share of the packed outputs begins
+    for (int i = wid; i < p.B; i += kAcceptThreads / kWave) {
+        const int base = p.cu[i];
+        const int k = p.cu[i + 1] - base;
+        const int off = acc_s[i];
+        tree_walk(p, base, min(k, kWave), lane, [&](int step, int row) {
+            if (lane == 0) {
+                if (p.out_tokens != nullptr) p.out_tokens[off + step] = p.target_ids[base + row];
+                if (p.accepted_rows != nullptr) p.accepted_rows[off + step] = base + row;
+            }
+        });
     }
 }
 

@@ -7,6 +7,9 @@
 // one layer's K or V with 16-byte loads and stores.  The per-sample lengths are
 // written by the same launch, except when kv_len_out aliases kv_len: then a
 // second, tiny launch advances them after every block has read the old ones.
+// The same kernel serves the gathered append of tree-structured verification: the rows
+// of an accepted root-to-leaf path are not contiguous, so each destination row names
+// its packed source row.
 #include "ems_device.h"
 #include "ems_kernels.h"
 
@@ -16,14 +19,16 @@ constexpr int kAppendThreads = 256;
 
 __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(AppendParams p) {
     const int i = blockIdx.x;
-    const int acc = p.accepted[i];
+    const bool gather = p.rows != nullptr;
+    const int rows0 = gather ? p.rows_cu[i] : 0;
+    const int acc = gather ? p.rows_cu[i + 1] - rows0 : p.accepted[i];
     const int len = p.kv_len[i];
     // the lengths ride along unless they are updated in place (then a later launch does it,
     // because other blocks still read kv_len[i])
     if (p.kv_len_out != nullptr && blockIdx.y == 0 && threadIdx.x == 0) p.kv_len_out[i] = len + acc;
     // never more than the sample brought (accepted[i] <= k_i is the caller's contract)
-    const int cu_i = p.cu[i];
-    const int a = min(acc, p.cu[i + 1] - cu_i);
+    const int cu_i = gather ? 0 : p.cu[i];
+    const int a = gather ? acc : min(acc, p.cu[i + 1] - cu_i);
     if (a <= 0) return;
     const AppendLayer& ly = p.layer[blockIdx.y >> 1];
     const bool is_v = blockIdx.y & 1;
@@ -36,7 +41,10 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(AppendParams 
         const int c = v - h * vph;
         const int64_t doff = (int64_t)h * ly.head_stride_b + c * 16;
         for (int j = 0; j < a; ++j) {
-            const u32x4 w = *reinterpret_cast<const u32x4*>(src + ((int64_t)j * row_vecs + v) * 16);
+            // gathered append (an accepted tree path): the j-th row of the path, wherever it sits
+            const int r = gather ? p.rows[rows0 + j] : j;
+            if (gather && (unsigned)r >= (unsigned)p.T) continue;      // not a packed row: nothing to copy
+            const u32x4 w = *reinterpret_cast<const u32x4*>(src + ((int64_t)r * row_vecs + v) * 16);
             *reinterpret_cast<u32x4*>(dst + j * ly.row_stride_b + doff) = w;
         }
     }
@@ -69,9 +77,9 @@ __global__ __launch_bounds__(kAppendThreads) void padded_kv_append_kernel(Padded
 }
 
 __global__ void advance_kv_len_kernel(const int32_t* kv_len, const int32_t* accepted,
-                                      int32_t* kv_len_out, int B) {
+                                      const int32_t* rows_cu, int32_t* kv_len_out, int B) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < B) kv_len_out[i] = kv_len[i] + accepted[i];
+    if (i < B) kv_len_out[i] = kv_len[i] + (accepted != nullptr ? accepted[i] : rows_cu[i + 1] - rows_cu[i]);
 }
 
 hipError_t launch_kv_append(const AppendParams& p, hipStream_t stream) {
@@ -85,10 +93,10 @@ hipError_t launch_padded_kv_append(const PaddedAppendParams& p, hipStream_t stre
     return hipGetLastError();
 }
 
-hipError_t launch_advance_kv_len(const int32_t* kv_len, const int32_t* accepted,
+hipError_t launch_advance_kv_len(const int32_t* kv_len, const int32_t* accepted, const int32_t* rows_cu,
                                  int32_t* kv_len_out, int B, hipStream_t stream) {
     hipLaunchKernelGGL(advance_kv_len_kernel, dim3((B + 255) / 256), dim3(256), 0, stream, kv_len,
-                       accepted, kv_len_out, B);
+                       accepted, rows_cu, kv_len_out, B);
     return hipGetLastError();
 }
 

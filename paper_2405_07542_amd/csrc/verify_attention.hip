@@ -138,8 +138,11 @@ struct SoftmaxState {
 };
 
 // One tile: scores, masked online softmax, PV.  `lim` = number of visible keys
-// of this tile for this lane's query row (>= 32 means no masking).
-template <typename ET, int D, bool MASKED, bool PADDED = false>
+// of this tile for this lane's query row (>= 32 means no masking); with BITS it is
+// instead a bit set over the tile's first 16 keys (bit n = key n visible; keys 16..31
+// hidden), the form the new-token tile uses: a causal prefix, or a row's ancestors in
+// a token tree.
+template <typename ET, int D, bool MASKED, bool PADDED = false, bool BITS = false>
 __device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* qb,
                                              SoftmaxState<ET, D>& st, float scale_log2, int lim,
                                              int g) {
@@ -156,7 +159,10 @@ __device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* 
     for (int i = 0; i < 4; ++i) {
         x[i] = sa[i] * scale_log2;
         x[4 + i] = sb[i] * scale_log2;
-        if (MASKED) {
+        if (MASKED && BITS) {
+            if (((lim >> (4 * g + i)) & 1) == 0) x[i] = -INFINITY;
+            x[4 + i] = -INFINITY;
+        } else if (MASKED) {
             if (4 * g + i >= lim) x[i] = -INFINITY;
             if (16 + 4 * g + i >= lim) x[4 + i] = -INFINITY;
         }
@@ -373,6 +379,27 @@ __device__ __forceinline__ void valu_tile(const TileRegs<D>& t, char* lds, ValuS
     }
 }
 
+// Token trees: the new rows a row sees are itself and its ancestors.  Lane n of every
+// 16-lane row holds parent[n] of the pair's sample; four rounds of pointer doubling
+// (each row adopts the set of the row it currently points to, then points where that
+// row pointed) cover any depth up to 16.  Anything that is not a valid parent (not in
+// [0, n), or n >= k) counts as "no parent", so the exchanges stay inside the sample.
+__device__ __forceinline__ int tree_visibility(int parent_n, int n, int k) {
+    int jump = (n < k && parent_n >= 0 && parent_n < n) ? parent_n : -1;
+    int seen = 1 << n;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int src = jump >= 0 ? jump : n;
+        const int seen_src = __shfl(seen, src, 16);
+        const int jump_src = __shfl(jump, src, 16);
+        if (jump >= 0) {
+            seen |= seen_src;
+            jump = jump_src;
+        }
+    }
+    return seen;
+}
+
 // One (sample, head) pair's share of a wave's tile range; everything is wave-uniform and
 // kept small, so that two of them live in scalar registers.
 struct Segment {
@@ -471,7 +498,8 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     u32x4 qb[KS];                // Q^T of `cur` as the B operand of S^T = K Q^T
     u32x4 qn[KS];                // the same for `nxt`, fetched a whole segment ahead
     SoftmaxState<ET, D> st;
-    int lim_new = 0;
+    int vis_new = 0;             // this lane's row: visible keys of the new-token tile, one bit per key
+    int par_n = -1;              // token trees: parent of row n of `nxt`, fetched with its Q
     // vector-ALU formulation: per-row state in registers, Q rows and P in wave-private LDS
     ValuState vs;
     char* const vlds = reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15) +
@@ -486,6 +514,10 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
         const uint32_t qoff = (uint32_t)min(n, k - 1) * new_row_bytes;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) dst[ks] = gload<u32x4>(qaddr, qoff + TR::piece(ks, g));
+    };
+    auto load_parent = [&](int cu_i, int k) __attribute__((always_inline)) {
+        if (!PADDED && p.parent != nullptr)
+            par_n = gload<int32_t>(uniform_addr(p.parent + cu_i), (uint32_t)min(n, k - 1) * 4u);
     };
     auto use_q = [&](const u32x4* src, int k) __attribute__((always_inline)) {
 #pragma unroll
@@ -513,8 +545,10 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
         st.m = -INFINITY;
         st.l = 0.f;
         // visible keys of the new-token tile for this lane's row: itself and the rows before
-        // it (padded: rows and keys at or beyond k_real are padding; padding rows see the real keys)
-        lim_new = min(s.k_real, n + 1);
+        // it (padded: rows and keys at or beyond k_real are padding; padding rows see the real keys);
+        // in a token tree: itself and its ancestors
+        vis_new = (1 << min(s.k_real, n + 1)) - 1;
+        if (!PADDED && p.parent != nullptr) vis_new = tree_visibility(par_n, n, s.k);
     };
 
     // Loads of tile `tile` of a pair described by plain values (never by a pointer to a
@@ -548,7 +582,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
             if (VALU)
                 valu_tile<ET, D, true, true>(t, vlds, vs, p.scale_log2, s.k, 0, lane, n, g);
             else
-                compute_tile<ET, D, true, PADDED>(t, qb, st, p.scale_log2, lim_new, g);
+                compute_tile<ET, D, true, PADDED, true>(t, qb, st, p.scale_log2, vis_new, g);
             if (!PADDED && p.write_through) {
                 // Paper order (Sec. 3.2): the new rows' K/V go to the sample's own location,
                 // cache rows kv_len + j, j < k_i, straight from the registers of this tile.
@@ -698,6 +732,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 if (cur_end < gend) {
                     nxt = next_segment<D, PADDED>(p, prefix, cur, cur_end, gend);
                     load_q(qn, nxt.new_off, nxt.k);
+                    load_parent(nxt.cu_i, nxt.k);
                 }
             }
         }
@@ -705,9 +740,13 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
 
     TileRegs<D> ta, tb;
     load_q(qn, cur.new_off, cur.k);
+    load_parent(cur.cu_i, cur.k);
     use_q(qn, cur.k);
-    if (cur_end < gend) load_q(qn, nxt.new_off, nxt.k);
     begin_segment(cur);
+    if (cur_end < gend) {
+        load_q(qn, nxt.new_off, nxt.k);
+        load_parent(nxt.cu_i, nxt.k);
+    }
     issue(ta, cur.t0, cur.L, cur.k, cur.cache_off, cur.new_off, cur.mask_off);
     for (int c = gbeg; c < gend; c += 2) {
         step(c, ta, tb);

@@ -44,6 +44,10 @@ def parse_args():
     ap.add_argument("--attention-variant", default="mfma", choices=["mfma", "valu"],
                     help="arithmetic units of the attention kernel's contractions: matrix cores (default) "
                          "or the vector ALU (a measurement aid; see ems_set_attention_variant)")
+    ap.add_argument("--tree", default=None, choices=["random", "wide", "star", "chain"],
+                    help="tree-structured verification: the same config with every sample's new rows arranged "
+                         "as a token tree of this shape (ems_tree_verify_attention / ems_tree_accept / "
+                         "ems_kv_append_rows instead of the three causal calls)")
     ap.add_argument("--layers", type=int, default=32, help="config 5 only: layers of the verify loop")
     ap.add_argument("--loop-steps", type=int, default=20, help="config 5 only: successive verify steps")
     ap.add_argument("--dynamic-batching", action="store_true",
@@ -140,6 +144,8 @@ def main():
         return
     n = args.config
     with_logits = not args.no_logits
+    if args.tree and (args.write_through or args.attention_variant == "valu" or n == 5):
+        sys.exit("--tree runs the matrix-core kernel with the gathered append on configs 2-4 only")
     if args.sweep_variants:
         print(json.dumps(sweep_variants()), flush=True)
         return
@@ -156,6 +162,9 @@ def main():
     sets = []
     for v in range(args.sets):
         b = make_config(n, device=dev, layout=args.layout, with_logits=with_logits, variant=v)
+        if args.tree:
+            from workloads import grow_trees
+            b = grow_trees(b, 4242 + v, match_p=0.7, shape=args.tree)
         ws_attn = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len),
                               dtype=torch.uint8, device=dev)
         ws_acc = torch.empty(max(8, ems.ems_accept_workspace_bytes(b.T, b.V)), dtype=torch.uint8, device=dev)
@@ -167,6 +176,7 @@ def main():
             accepted=torch.empty(b.B, dtype=torch.int32, device=dev),
             accepted_cu=torch.empty(b.B + 1, dtype=torch.int32, device=dev),
             out_tokens=torch.empty(b.T, dtype=torch.int32, device=dev),
+            accepted_rows=torch.empty(b.T, dtype=torch.int32, device=dev),
             # the lengths are NOT advanced between timed steps, so every step does the same work
             new_len=torch.empty(b.B, dtype=torch.int32, device=dev))
         sets.append(st)
@@ -174,17 +184,31 @@ def main():
 
     def attention(st):
         b = st["b"]
+        if args.tree:
+            ems.ems_tree_verify_attention(b.q, b.k_new, b.v_new, st["cache"], b.cu_seqlens, b.parent, b.kv_start,
+                                          b.kv_len, st["out"], max_k=b.max_k, max_kv_len=b.max_kv_len,
+                                          scale=b.scale, workspace=st["ws_attn"])
+            return
         ems.ems_verify_attention(b.q, b.k_new, b.v_new, st["cache"], b.cu_seqlens, b.kv_start, b.kv_len,
                                  st["out"], max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale,
                                  workspace=st["ws_attn"], write_through=args.write_through)
 
     def accept(st):
         b = st["b"]
+        if args.tree:
+            ems.ems_tree_accept(b.logits if with_logits else None, st["target"], b.input_ids, b.parent,
+                                b.cu_seqlens, st["accepted"], st["accepted_cu"], st["out_tokens"],
+                                st["accepted_rows"], workspace=st["ws_acc"])
+            return
         ems.ems_greedy_accept(b.logits if with_logits else None, st["target"], b.input_ids, b.cu_seqlens,
                               st["accepted"], st["accepted_cu"], st["out_tokens"], workspace=st["ws_acc"])
 
     def append(st):
         b = st["b"]
+        if args.tree:
+            ems.ems_kv_append_rows([b.k_new], [b.v_new], [st["cache"]], st["accepted_rows"], st["accepted_cu"],
+                                   b.kv_start, b.kv_len, st["new_len"])
+            return
         if args.write_through:
             ems.ems_kv_advance(b.kv_len, st["accepted"], st["new_len"])
             return
@@ -241,7 +265,7 @@ def main():
                    "query_rows_per_step": rows_per_step, "accepted_per_step": accepted_per_step,
                    "logits": with_logits, "buffer_sets": len(sets),
                    "variant": "write-through + advance" if args.write_through else "verify + append",
-                   "attention_variant": args.attention_variant},
+                   "attention_variant": args.attention_variant, "tree": args.tree},
         "query_tokens_per_s": round(rows_per_step / (ms_per_step * 1e-3), 1),
         "roofline": roofline,
     }
@@ -262,7 +286,7 @@ def main():
                                   "accept_call": round(time_call(accept), 5),
                                   "append_call": round(time_call(append), 5)}
 
-    if not args.no_ablation:
+    if not args.no_ablation and not args.tree:      # the padded ablation is the causal method's
         result["padded_ablation"] = padded_ablation(sets, args, with_logits, alg_bytes, ms_per_step)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(sets[0]["b"], with_logits)

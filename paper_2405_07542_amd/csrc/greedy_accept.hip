@@ -6,8 +6,8 @@
 // Two launches on the caller's stream:
 //   1. argmax_partial_kernel  grid (slices, T): each block scans one slice of one
 //      logits row with 16-byte loads and keeps (value, lowest index);
-//   2. accept_scan_kernel     one block: finishes the arg-max per row, one wave per
-//      sample compares drafts with targets (ballot + count of leading matches),
+//   2. accept_scan_kernel     one block: finishes the arg-max per row, 16 lanes per
+//      sample compare drafts with targets (ballot + count of leading matches),
 //      block-wide exclusive scan of the lengths, packed copy of accepted tokens.
 // Comparisons are on exactly widened values, so results are bit-exact; ties go
 // to the lowest index at every merge level.
@@ -135,33 +135,50 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParam
     }
 
     const bool tree = p.parent != nullptr;
-    // one wave per sample: count the leading drafts that match the target's tokens
-    for (int i = wid; i < p.B; i += kAcceptThreads / kWave) {
-        const int base = p.cu[i];
-        const int k = p.cu[i + 1] - base;
-        if (tree) {
+    if (tree) {
+        // token trees: one wave per sample walks from the root
+        for (int i = wid; i < p.B; i += kAcceptThreads / kWave) {
+            const int base = p.cu[i];
+            const int k = p.cu[i + 1] - base;
             const int a = tree_walk(p, base, min(k, kWave), lane, [](int, int) {});
             if (lane == 0) {
                 acc_s[i] = a;
                 p.accepted[i] = a;
             }
-            continue;
         }
-        int m = 0;
-        for (int c0 = 0; c0 < k - 1; c0 += kWave) {
-            const int j = c0 + lane;
-            const bool match = (j < k - 1) && (p.target_ids[base + j] == p.input_ids[base + j + 1]);
-            const uint64_t miss = ~__builtin_amdgcn_ballot_w64(match);
-            if (miss != 0) {
-                m += __builtin_ctzll(miss);
-                break;
+    } else {
+        // 16 lanes per sample (64 samples per pass of the block): count the leading drafts that
+        // match the target's tokens, 16 rows at a time.  The loop is wave-uniform; a group that
+        // has found its first mismatch idles until the other three groups of its wave have too.
+        const int sub = lane >> 4, l16 = lane & 15;
+        for (int i0 = 0; i0 < p.B; i0 += kAcceptThreads / 16) {
+            const int i = i0 + (tid >> 4);
+            const bool live = i < p.B;
+            const int base = live ? p.cu[i] : 0;
+            const int k = live ? p.cu[i + 1] - base : 0;
+            int m = 0;
+            bool done = k <= 1;
+            for (int c0 = 0;; c0 += 16) {
+                const int j = c0 + l16;
+                const bool match = !done && j < k - 1 &&
+                                   p.target_ids[base + j] == p.input_ids[base + j + 1];
+                const uint32_t mine = (uint32_t)(__builtin_amdgcn_ballot_w64(match) >> (16 * sub)) & 0xffffu;
+                if (!done) {
+                    const uint32_t miss = ~mine & 0xffffu;      // a row past the last draft counts as a miss
+                    if (miss != 0) {
+                        m += __builtin_ctz(miss);
+                        done = true;
+                    } else {
+                        m += 16;
+                    }
+                }
+                if (__builtin_amdgcn_ballot_w64(!done) == 0) break;
             }
-            m += kWave;
-        }
-        if (lane == 0) {
-            const int a = k > 0 ? m + 1 : 0;
-            acc_s[i] = a;
-            p.accepted[i] = a;
+            if (live && l16 == 0) {
+                const int a = k > 0 ? m + 1 : 0;
+                acc_s[i] = a;
+                p.accepted[i] = a;
+            }
         }
     }
     __syncthreads();

@@ -3,8 +3,8 @@
 // copied from the packed new K/V to the sample's own write location, so no
 // padding row is ever written and every cache stays contiguous.
 //
-// Grid (B, 2 * n_layers): one block copies the accepted rows of one sample for
-// one layer's K or V with 16-byte loads and stores.  The per-sample lengths are
+// Grid (B, 2 * n_layers, 4): four blocks share the accepted rows of one sample for
+// one layer's K or V, 16-byte loads and stores, four loads in flight per thread.  The per-sample lengths are
 // written by the same launch, except when kv_len_out aliases kv_len: then a
 // second, tiny launch advances them after every block has read the old ones.
 // The same kernel serves the gathered append of tree-structured verification: the rows
@@ -16,6 +16,7 @@
 namespace ems {
 
 constexpr int kAppendThreads = 256;
+constexpr int kAppendSplit = 4;        // blocks per (sample, layer, K|V)
 
 __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(AppendParams p) {
     const int i = blockIdx.x;
@@ -25,7 +26,8 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(AppendParams 
     const int len = p.kv_len[i];
     // the lengths ride along unless they are updated in place (then a later launch does it,
     // because other blocks still read kv_len[i])
-    if (p.kv_len_out != nullptr && blockIdx.y == 0 && threadIdx.x == 0) p.kv_len_out[i] = len + acc;
+    if (p.kv_len_out != nullptr && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0)
+        p.kv_len_out[i] = len + acc;
     // never more than the sample brought (accepted[i] <= k_i is the caller's contract)
     const int cu_i = gather ? 0 : p.cu[i];
     const int a = gather ? acc : min(acc, p.cu[i + 1] - cu_i);
@@ -36,17 +38,37 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(AppendParams 
     const int row_vecs = p.H * vph;
     const char* src = (is_v ? ly.v_new : ly.k_new) + (int64_t)cu_i * row_vecs * 16;
     char* dst = (is_v ? ly.v_cache : ly.k_cache) + ((int64_t)p.kv_start[i] + len) * ly.row_stride_b;
-    for (int v = threadIdx.x; v < row_vecs; v += kAppendThreads) {
+    // The a x row_vecs 16-byte pieces of this (sample, layer, K|V) are dealt round-robin to the
+    // threads of its kAppendSplit blocks; a thread loads four pieces before it stores them, so
+    // that four reads are in flight instead of one.
+    const int total = a * row_vecs;
+    const int stride = kAppendThreads * kAppendSplit;
+    auto locate = [&](int idx, const char*& s_ptr, char*& d_ptr) -> bool {
+        const int j = idx / row_vecs;
+        const int v = idx - j * row_vecs;
         const int h = v / vph;
         const int c = v - h * vph;
-        const int64_t doff = (int64_t)h * ly.head_stride_b + c * 16;
-        for (int j = 0; j < a; ++j) {
-            // gathered append (an accepted tree path): the j-th row of the path, wherever it sits
-            const int r = gather ? p.rows[rows0 + j] : j;
-            if (gather && (unsigned)r >= (unsigned)p.T) continue;      // not a packed row: nothing to copy
-            const u32x4 w = *reinterpret_cast<const u32x4*>(src + ((int64_t)r * row_vecs + v) * 16);
-            *reinterpret_cast<u32x4*>(dst + j * ly.row_stride_b + doff) = w;
+        // gathered append (an accepted tree path): the j-th row of the path, wherever it sits
+        const int r = gather ? p.rows[rows0 + j] : j;
+        s_ptr = src + ((int64_t)r * row_vecs + v) * 16;
+        d_ptr = dst + (int64_t)j * ly.row_stride_b + (int64_t)h * ly.head_stride_b + c * 16;
+        return !gather || (unsigned)r < (unsigned)p.T;     // not a packed row: nothing to copy
+    };
+    for (int idx0 = blockIdx.z * kAppendThreads + threadIdx.x; idx0 < total; idx0 += 4 * stride) {
+        u32x4 w[4];
+        char* d[4];
+        bool ok[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = idx0 + u * stride;
+            const char* sp = nullptr;
+            d[u] = nullptr;
+            ok[u] = idx < total && locate(idx, sp, d[u]);
+            if (ok[u]) w[u] = *reinterpret_cast<const u32x4*>(sp);
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (ok[u]) *reinterpret_cast<u32x4*>(d[u]) = w[u];
     }
 }
 
@@ -83,7 +105,8 @@ __global__ void advance_kv_len_kernel(const int32_t* kv_len, const int32_t* acce
 }
 
 hipError_t launch_kv_append(const AppendParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL(kv_append_kernel, dim3(p.B, 2 * p.n_layers), dim3(kAppendThreads), 0, stream, p);
+    hipLaunchKernelGGL(kv_append_kernel, dim3(p.B, 2 * p.n_layers, kAppendSplit), dim3(kAppendThreads), 0,
+                       stream, p);
     return hipGetLastError();
 }
 

@@ -157,3 +157,32 @@ def test_attention_variant_switch_is_host_state():
     assert L.ems_set_attention_variant(5) == ems.EMS_ERR_INVALID_ARG
     assert L.ems_get_attention_variant() == ems.EMS_ATTN_VALU
     assert L.ems_set_attention_variant(ems.EMS_ATTN_MFMA) == ems.EMS_OK
+
+
+def test_tree_entry_points_reject_bad_arguments_on_the_host():
+    L = ems.lib()
+    cache = ems.KvCacheStruct(FAKE, FAKE, 4096, 128, 1024)
+    args = [FAKE, FAKE, FAKE, ctypes.byref(cache), FAKE, None, FAKE, FAKE, FAKE, ems.EMS_F16, 4, 8, 32, 128,
+            4, 100, 0.1, ems.EMS_F16, FAKE, 1 << 30, None]
+    assert L.ems_tree_verify_attention(*args) == ems.EMS_ERR_INVALID_ARG          # parent = NULL
+    assert b"parent" in L.ems_last_error_string()
+    args[5] = FAKE
+    args[13] = 96
+    assert L.ems_tree_verify_attention(*args) == ems.EMS_ERR_UNSUPPORTED          # D = 96
+    args[13] = 128
+    args[10] = 0
+    assert L.ems_tree_verify_attention(*args) == ems.EMS_ERR_INVALID_ARG          # B = 0
+    # accept: parent required with rows; sizes checked as in the plain call
+    assert L.ems_tree_accept(None, ems.EMS_F16, 0, FAKE, FAKE, None, FAKE, 4, 8, FAKE, FAKE, None, None,
+                             None, 0, None) == ems.EMS_ERR_INVALID_ARG
+    assert L.ems_tree_accept(None, ems.EMS_F16, 0, FAKE, FAKE, FAKE, FAKE, 0, 8, FAKE, FAKE, None, None,
+                             None, 0, None) == ems.EMS_ERR_INVALID_ARG
+    # gathered append
+    karr = (ctypes.c_void_p * 1)(FAKE)
+    carr = (ems.KvCacheStruct * 1)(cache)
+    assert L.ems_kv_append_rows(karr, karr, carr, 1, None, FAKE, FAKE, FAKE, None, 4, 8, 32, 128,
+                                ems.EMS_F16, None) == ems.EMS_ERR_INVALID_ARG
+    assert L.ems_kv_append_rows(karr, karr, carr, 0, FAKE, FAKE, FAKE, FAKE, None, 4, 8, 32, 128,
+                                ems.EMS_F16, None) == ems.EMS_ERR_INVALID_ARG
+    assert L.ems_stream_read_probe(None, 4096, FAKE, None) == ems.EMS_ERR_INVALID_ARG
+    assert L.ems_stream_read_probe(FAKE, 100, FAKE, None) == ems.EMS_ERR_INVALID_ARG

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptPa
     float best = -INFINITY;
     int32_t arg = 0x7fffffff;
     if ((p.V & 7) == 0) {
-        // 16-byte non-temporal loads (the logits are read once), two per thread in flight
+        // 16-byte non-temporal loads (the logits are read once)
         const uint64_t rowaddr = (uint64_t)base;
         auto scan8 = [&](const u32x4 w, int v) {
 #pragma unroll
@@ -52,14 +52,19 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptPa
             }
         };
         const int v1 = c1 >> 3;
-        int v = (c0 >> 3) + tid;
-        for (; v + kArgmaxThreads < v1; v += 2 * kArgmaxThreads) {
-            const u32x4 wa = gload_stream<u32x4>(rowaddr, (uint32_t)v * 16u);
-            const u32x4 wb = gload_stream<u32x4>(rowaddr, (uint32_t)(v + kArgmaxThreads) * 16u);
-            scan8(wa, v);
-            scan8(wb, v + kArgmaxThreads);
+        // four loads in flight per thread; a thread whose last group is short re-reads the
+        // slice's last vector instead (scanning an element twice changes nothing)
+        for (int v = (c0 >> 3) + tid; v < v1; v += 4 * kArgmaxThreads) {
+            int vv[4];
+            u32x4 w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                vv[u] = min(v + u * kArgmaxThreads, v1 - 1);
+                w[u] = gload_stream<u32x4>(rowaddr, (uint32_t)vv[u] * 16u);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) scan8(w[u], vv[u]);
         }
-        if (v < v1) scan8(gload_stream<u32x4>(rowaddr, (uint32_t)v * 16u), v);
     } else {
         for (int c = c0 + tid; c < c1; c += kArgmaxThreads) {
             const float y = widen(ET{}, base[c]);

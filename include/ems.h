@@ -299,6 +299,9 @@ EMS_API ems_status ems_stream_read_probe(const void* buf, size_t bytes, void* si
  * so that the two can be timed against each other on one input.  Results of both meet
  * the same tolerance.  Process-wide; takes effect with the next call; the padded ablation
  * always uses the matrix cores.  Any other value: EMS_ERR_INVALID_ARG, setting unchanged.
+ * While EMS_ATTN_VALU is selected, calls with D = 80, with a token tree, or with so many
+ * samples that the per-row state no longer fits the 160 KiB of LDS next to the B+1 prefix
+ * sums (D = 128: B > 3967) return EMS_ERR_UNSUPPORTED.
  */
 typedef enum ems_attention_variant {
     EMS_ATTN_MFMA = 0,

@@ -145,6 +145,9 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     if (D == 80 && pad) return fail(EMS_ERR_UNSUPPORTED, "the padded ablation has head dims 64 and 128 only");
     if (D == 80 && g_attn_variant.load() == EMS_ATTN_VALU)
         return fail(EMS_ERR_UNSUPPORTED, "EMS_ATTN_VALU has head dims 64 and 128 only");
+    if (!pad && g_attn_variant.load() == EMS_ATTN_VALU && ems::valu_attention_lds_bytes(B, D) > (size_t)ems::kMaxLdsBytes)
+        return fail(EMS_ERR_UNSUPPORTED, "EMS_ATTN_VALU keeps its per-row state in LDS: B = %d at D = %d needs %zu of %d bytes",
+                    B, D, ems::valu_attention_lds_bytes(B, D), ems::kMaxLdsBytes);
     if (max_k > EMS_MAX_QUERY_ROWS)
         return fail(EMS_ERR_UNSUPPORTED, "max_k = %d, at most %d rows per sample", max_k, EMS_MAX_QUERY_ROWS);
     if (B > kMaxB) return fail(EMS_ERR_UNSUPPORTED, "B = %d, at most %d samples", B, kMaxB);

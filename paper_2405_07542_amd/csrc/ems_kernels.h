@@ -39,6 +39,10 @@ struct AttnParams {
     int64_t cap;
 };
 
+constexpr int kMaxLdsBytes = 160 * 1024;   // LDS a workgroup may use on gfx950
+// LDS bytes per workgroup of the vector-ALU formulation (prefix sums + wave-private state), D in {64, 128}
+size_t valu_attention_lds_bytes(int B, int D);
+
 // ev_start / ev_stop (may be null) are recorded right before and right after the main
 // attention kernel, i.e. they exclude the partial-merge kernel.
 // valu: contractions on the vector ALU instead of the matrix cores (unpadded layout only).

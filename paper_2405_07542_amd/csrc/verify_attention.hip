@@ -24,6 +24,8 @@
 //   * a range that covers only part of a pair writes an fp32 partial
 //     (accumulator, running max, running sum); a second small kernel merges
 //     the partials of such pairs by log-sum-exp.
+#include <atomic>
+
 #include "ems_device.h"
 #include "ems_kernels.h"
 
@@ -835,14 +837,15 @@ static hipError_t launch_typed(const AttnParams& p, int blocks, bool valu, hipSt
     if constexpr (!PADDED && D != 80) {
         if (valu) {
             lds = ((lds + 15) & ~(size_t)15) + (size_t)kWavesPerBlock * ValuLds<D>::bytes;
-            // up to 32 KiB of prefix + 4 x 14 KiB of wave-private state: above the 64 KiB a
-            // kernel may use without asking
-            static bool raised = false;
-            if (!raised) {
+            // prefix sums + 4 x 36 KiB (D = 128) of wave-private state: well above the 64 KiB a
+            // kernel may use by default on some HIP platforms, so ask for the device's 160 KiB
+            if (lds > kMaxLdsBytes) return hipErrorInvalidValue;   // (the API layer rejects such B first)
+            static std::atomic<bool> raised{false};
+            if (!raised.load()) {
                 e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_attention_kernel<ET, D, false, true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
                 if (e != hipSuccess) return e;
-                raised = true;
+                raised.store(true);
             }
             hipLaunchKernelGGL((verify_attention_kernel<ET, D, false, true>), dim3(blocks),
                                dim3(kAttnThreads), lds, stream, p);
@@ -871,6 +874,11 @@ static hipError_t launch_layout(const AttnParams& p, int blocks, int D, bool bf1
     }
     return bf16 ? launch_typed<BF16, 64, PADDED>(p, blocks, valu, stream, ev_start, ev_stop)
                 : launch_typed<F16, 64, PADDED>(p, blocks, valu, stream, ev_start, ev_stop);
+}
+
+size_t valu_attention_lds_bytes(int B, int D) {
+    const size_t prefix = (((size_t)(B + 1) * sizeof(int32_t)) + 15) & ~(size_t)15;
+    return prefix + (size_t)kWavesPerBlock * (D == 128 ? ValuLds<128>::bytes : ValuLds<64>::bytes);
 }
 
 hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16, bool padded,

@@ -313,3 +313,16 @@ def test_argmax_rows_of_minus_infinity():
     want = oracle.argmax(bits(b_cpu.logits), torch.float16)
     assert want[1] == 0 and want[2] == 40000
     assert np.array_equal(tgt.cpu().numpy(), want)
+
+
+def test_maximum_batch_size():
+    """B = 8192, the most samples a call accepts: 32 KiB of tile prefix sums in LDS, one merge
+    block per (sample, head); many samples bring no rows at all."""
+    rng = np.random.default_rng(59)
+    B = 8192
+    kv = rng.integers(0, 41, B).tolist()
+    k = rng.integers(0, 4, B).tolist()
+    k[0], k[-1] = 3, 2
+    b = make_batch(kv, k, H=1, D=64, dtype=torch.float16, seed=60, capacity=48)
+    check_attention(b, out_dtype=torch.float32, label="B=8192")
+    run_accept_and_append(b)

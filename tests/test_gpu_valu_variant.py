@@ -60,3 +60,22 @@ def test_setter_rejects_unknown_values():
     with pytest.raises(ems.EmsError):
         ems.ems_set_attention_variant(7)
     assert ems.ems_get_attention_variant() == ems.EMS_ATTN_VALU
+
+
+def test_large_batches_and_the_lds_limit():
+    """The per-row state lives in LDS (4 x 36 KiB at D = 128) next to the tile prefix sums: B = 3900
+    fits the 160 KiB of a workgroup, B = 8192 does not and is refused on the host; D = 64 (4 x 18
+    KiB) takes the maximum batch."""
+    rng = np.random.default_rng(73)
+    B = 3900
+    b = make_batch(rng.integers(0, 41, B).tolist(), rng.integers(0, 4, B).tolist(), H=1, D=128,
+                   dtype=torch.bfloat16, seed=74, capacity=48)
+    check_attention(b, out_dtype=torch.float32, label="valu B=3900 D=128")
+    B = 8192
+    kv, k = rng.integers(0, 41, B).tolist(), rng.integers(0, 4, B).tolist()
+    check_attention(make_batch(kv, k, H=1, D=64, dtype=torch.float16, seed=75, capacity=48),
+                    out_dtype=torch.float32, label="valu B=8192 D=64")
+    big = to_device(make_batch(kv, k, H=1, D=128, dtype=torch.float16, seed=76, capacity=48))
+    with pytest.raises(ems.EmsError) as e:
+        hip_attention(big)
+    assert e.value.status == ems.EMS_ERR_UNSUPPORTED and "LDS" in str(e.value)

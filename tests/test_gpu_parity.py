@@ -56,6 +56,13 @@ def test_one_pair_shared_by_many_waves():
     check_attention(b, out_dtype=torch.float32)
 
 
+def test_one_very_long_cache_merged_from_a_thousand_partials():
+    """One (sample, head) pair of 300 000 cached rows: every wave of the launch holds a slice of
+    it, so its rows are merged from ~1000 partials; byte offsets inside the sample reach 150 MB."""
+    b = make_batch([300000], [5], H=1, D=128, dtype=torch.bfloat16, seed=77)
+    check_attention(b, out_dtype=torch.float32, label="L=300000")
+
+
 def test_degenerate_batches():
     # empty caches everywhere; finished samples (k_i = 0) in between; maximum rows per sample
     check_attention(make_batch([0, 0, 0], [4, 1, 16], H=2, D=128, seed=43, capacity=32))

@@ -33,8 +33,10 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=4, help="BASELINE config number (2..5)")
     ap.add_argument("--layout", default="token_major", choices=["token_major", "head_major"])
-    ap.add_argument("--sets", type=int, default=3,
-                    help="independent buffer sets rotated between steps (cold last-level cache)")
+    ap.add_argument("--sets", type=int, default=0,
+                    help="independent buffer sets rotated between steps so that no step finds its K/V in the "
+                         "last-level cache; 0 (default) = as many as make the rotated K/V at least 2 GiB, "
+                         "between 3 and 16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-logits", action="store_true", help="skip the [T,V] arg-max (ids given)")
     ap.add_argument("--breakdown", action="store_true", help="also time each call on its own")
@@ -160,8 +162,12 @@ def main():
         return
 
     sets = []
-    for v in range(args.sets):
+    n_sets = args.sets
+    v = 0
+    while n_sets == 0 or v < n_sets:
         b = make_config(n, device=dev, layout=args.layout, with_logits=with_logits, variant=v)
+        if n_sets == 0:      # sized from the first draw: 256 MB of Infinity Cache must not hold a whole rotation
+            n_sets = int(min(16, max(3, -(-(2 << 30) // max(1, attention_algorithmic_bytes(b, 2))))))
         if args.tree:
             from workloads import grow_trees
             b = grow_trees(b, 4242 + v, match_p=0.7, shape=args.tree)
@@ -180,6 +186,7 @@ def main():
             # the lengths are NOT advanced between timed steps, so every step does the same work
             new_len=torch.empty(b.B, dtype=torch.int32, device=dev))
         sets.append(st)
+        v += 1
     torch.cuda.synchronize()
 
     def attention(st):

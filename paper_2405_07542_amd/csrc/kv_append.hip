@@ -3,8 +3,9 @@
 // copied from the packed new K/V to the sample's own write location, so no
 // padding row is ever written and every cache stays contiguous.
 //
-// Grid (B, 2 * n_layers, 4): four blocks share the accepted rows of one sample for
-// one layer's K or V, 16-byte loads and stores, four loads in flight per thread.  The per-sample lengths are
+// Grid (B, 2 * n_layers, s): s blocks (4 for small launches, else 1) share the accepted
+// rows of one sample for one layer's K or V; 16-byte loads and stores, four loads in
+// flight per thread.  The per-sample lengths are
 // written by the same launch, except when kv_len_out aliases kv_len: then a
 // second, tiny launch advances them after every block has read the old ones.
 // The same kernel serves the gathered append of tree-structured verification: the rows
@@ -16,7 +17,7 @@
 namespace ems {
 
 constexpr int kAppendThreads = 256;
-constexpr int kAppendSplit = 4;        // blocks per (sample, layer, K|V)
+constexpr int kAppendSplit = 4;        // blocks per (sample, layer, K|V) when the launch would otherwise be small
 
 __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(AppendParams p) {
     const int i = blockIdx.x;
@@ -38,21 +39,37 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(AppendParams 
     const int row_vecs = p.H * vph;
     const char* src = (is_v ? ly.v_new : ly.k_new) + (int64_t)cu_i * row_vecs * 16;
     char* dst = (is_v ? ly.v_cache : ly.k_cache) + ((int64_t)p.kv_start[i] + len) * ly.row_stride_b;
-    // The a x row_vecs 16-byte pieces of this (sample, layer, K|V) are dealt round-robin to the
-    // threads of its kAppendSplit blocks; a thread loads four pieces before it stores them, so
-    // that four reads are in flight instead of one.
+    if (gridDim.z == 1) {
+        // many layers in one launch: plenty of blocks; each thread owns a column of 16-byte
+        // pieces and walks down the rows
+        for (int v = threadIdx.x; v < row_vecs; v += kAppendThreads) {
+            const int h = v / vph;
+            const int c = v - h * vph;
+            const int64_t doff = (int64_t)h * ly.head_stride_b + c * 16;
+            for (int j = 0; j < a; ++j) {
+                // gathered append (an accepted tree path): the j-th row of the path, wherever it sits
+                const int r = gather ? p.rows[rows0 + j] : j;
+                if (gather && (unsigned)r >= (unsigned)p.T) continue;      // not a packed row: nothing to copy
+                const u32x4 w = *reinterpret_cast<const u32x4*>(src + ((int64_t)r * row_vecs + v) * 16);
+                *reinterpret_cast<u32x4*>(dst + j * ly.row_stride_b + doff) = w;
+            }
+        }
+        return;
+    }
+    // A small launch (one layer, modest B): the a x row_vecs 16-byte pieces of this (sample,
+    // layer, K|V) are dealt round-robin to the threads of its gridDim.z blocks; a thread loads
+    // four pieces before it stores them, so that four reads are in flight instead of one.
     const int total = a * row_vecs;
-    const int stride = kAppendThreads * kAppendSplit;
+    const int stride = kAppendThreads * (int)gridDim.z;
     auto locate = [&](int idx, const char*& s_ptr, char*& d_ptr) -> bool {
         const int j = idx / row_vecs;
         const int v = idx - j * row_vecs;
         const int h = v / vph;
         const int c = v - h * vph;
-        // gathered append (an accepted tree path): the j-th row of the path, wherever it sits
         const int r = gather ? p.rows[rows0 + j] : j;
         s_ptr = src + ((int64_t)r * row_vecs + v) * 16;
         d_ptr = dst + (int64_t)j * ly.row_stride_b + (int64_t)h * ly.head_stride_b + c * 16;
-        return !gather || (unsigned)r < (unsigned)p.T;     // not a packed row: nothing to copy
+        return !gather || (unsigned)r < (unsigned)p.T;
     };
     for (int idx0 = blockIdx.z * kAppendThreads + threadIdx.x; idx0 < total; idx0 += 4 * stride) {
         u32x4 w[4];
@@ -105,7 +122,10 @@ __global__ void advance_kv_len_kernel(const int32_t* kv_len, const int32_t* acce
 }
 
 hipError_t launch_kv_append(const AppendParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL(kv_append_kernel, dim3(p.B, 2 * p.n_layers, kAppendSplit), dim3(kAppendThreads), 0,
+    // a one-layer append of a small batch has too few (sample, layer, K|V) units to fill the chip:
+    // split each over several blocks; many layers bring enough blocks by themselves
+    const int split = (int64_t)p.B * 2 * p.n_layers < 2048 ? kAppendSplit : 1;
+    hipLaunchKernelGGL(kv_append_kernel, dim3(p.B, 2 * p.n_layers, split), dim3(kAppendThreads), 0,
                        stream, p);
     return hipGetLastError();
 }

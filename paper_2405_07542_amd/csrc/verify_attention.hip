@@ -757,13 +757,15 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
 }
 
 // Merge the partials of every (sample, head) pair whose tiles were shared by several
-// waves.  Grid (H, B); 16 x D/4 threads: D/4 lanes per output row, 4 columns per lane, all
-// 16 possible rows at once.  The slots of a pair are folded in wave order into a running
+// waves.  Grid (H, B); 8 x D/4 threads: D/4 lanes per output row, 4 columns per lane, 8 rows
+// per pass (most blocks find nothing to merge and leave at once, so they are kept small).
+// The slots of a pair are folded in wave order into a running
 // (max, sum, accumulator), so the result does not depend on timing; a slot's loads do not
 // depend on the running state, so two slots are fetched before either is folded.
 template <int D> struct Combine {
     static constexpr int lanes_per_row = D / 4;
-    static constexpr int threads = kMaxRows * lanes_per_row;
+    static constexpr int rows_per_pass = 8;
+    static constexpr int threads = rows_per_pass * lanes_per_row;
 };
 
 template <typename ET, int D, bool PADDED>
@@ -783,47 +785,47 @@ __global__ __launch_bounds__(Combine<D>::threads) void combine_partials_kernel(A
     constexpr int pitch = D + kPartialPad;
     constexpr int lanes_per_row = Combine<D>::lanes_per_row;
     const int c4 = (threadIdx.x % lanes_per_row) * 4;
-    const int j = threadIdx.x / lanes_per_row;
-    if (j >= k) return;
-    // slot of wave w for this pair: 2w+1 if the pair starts in w's range, 2w if it continues
-    auto slot_row = [&](int w) -> const float* {
-        const int slot = 2 * w + (w == w0 ? 1 : 0);
-        return p.ws + ((int64_t)slot * 16 + j) * pitch;
-    };
-    float M = -INFINITY, den = 0.f;
-    f32x4 num = {0.f, 0.f, 0.f, 0.f};
-    auto fold = [&](float m, float l, f32x4 v) {
-        const float Mn = fmaxf(M, m);
-        // (padded ablation: a range of nothing but padding keys has max -inf and sum 0)
-        const float Ms = Mn == -INFINITY ? 0.f : Mn;
-        const float a = fast_exp2(M - Ms), b = fast_exp2(m - Ms);
-        num = num * a + v * b;
-        den = den * a + l * b;
-        M = Mn;
-    };
-    int w = w0;
-    for (; w + 1 <= w1; w += 2) {
-        const float* s0 = slot_row(w);
-        const float* s1 = slot_row(w + 1);
-        const float m0 = s0[D], l0 = s0[D + 1], m1 = s1[D], l1 = s1[D + 1];
-        const f32x4 v0 = *reinterpret_cast<const f32x4*>(s0 + c4);
-        const f32x4 v1 = *reinterpret_cast<const f32x4*>(s1 + c4);
-        fold(m0, l0, v0);
-        fold(m1, l1, v1);
-    }
-    if (w <= w1) {
-        const float* s0 = slot_row(w);
-        fold(s0[D], s0[D + 1], *reinterpret_cast<const f32x4*>(s0 + c4));
-    }
-    const float inv = 1.0f / den;
-    const int64_t idx = ((int64_t)(cu_i + j) * p.H + h) * D + c4;
-    if (p.out_f32) {
-        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + idx) = num * inv;
-    } else {
-        u32x2 pk;
-        pk[0] = pack2(ET{}, num[0] * inv, num[1] * inv);
-        pk[1] = pack2(ET{}, num[2] * inv, num[3] * inv);
-        *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(p.out) + idx) = pk;
+    for (int j = threadIdx.x / lanes_per_row; j < k; j += Combine<D>::rows_per_pass) {
+        // slot of wave w for this pair: 2w+1 if the pair starts in w's range, 2w if it continues
+        auto slot_row = [&](int w) -> const float* {
+            const int slot = 2 * w + (w == w0 ? 1 : 0);
+            return p.ws + ((int64_t)slot * 16 + j) * pitch;
+        };
+        float M = -INFINITY, den = 0.f;
+        f32x4 num = {0.f, 0.f, 0.f, 0.f};
+        auto fold = [&](float m, float l, f32x4 v) {
+            const float Mn = fmaxf(M, m);
+            // (padded ablation: a range of nothing but padding keys has max -inf and sum 0)
+            const float Ms = Mn == -INFINITY ? 0.f : Mn;
+            const float a = fast_exp2(M - Ms), b = fast_exp2(m - Ms);
+            num = num * a + v * b;
+            den = den * a + l * b;
+            M = Mn;
+        };
+        int w = w0;
+        for (; w + 1 <= w1; w += 2) {
+            const float* s0 = slot_row(w);
+            const float* s1 = slot_row(w + 1);
+            const float m0 = s0[D], l0 = s0[D + 1], m1 = s1[D], l1 = s1[D + 1];
+            const f32x4 v0 = *reinterpret_cast<const f32x4*>(s0 + c4);
+            const f32x4 v1 = *reinterpret_cast<const f32x4*>(s1 + c4);
+            fold(m0, l0, v0);
+            fold(m1, l1, v1);
+        }
+        if (w <= w1) {
+            const float* s0 = slot_row(w);
+            fold(s0[D], s0[D + 1], *reinterpret_cast<const f32x4*>(s0 + c4));
+        }
+        const float inv = 1.0f / den;
+        const int64_t idx = ((int64_t)(cu_i + j) * p.H + h) * D + c4;
+        if (p.out_f32) {
+            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + idx) = num * inv;
+        } else {
+            u32x2 pk;
+            pk[0] = pack2(ET{}, num[0] * inv, num[1] * inv);
+            pk[1] = pack2(ET{}, num[2] * inv, num[3] * inv);
+            *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(p.out) + idx) = pk;
+        }
     }
 }
 

@@ -1,0 +1,55 @@
+"""GPU parity on a seeded sweep of random valid shapes: batch size, head count, head dim, dtype,
+cache layout, ragged cached lengths (empty caches, exact tile multiples, tails), rows per
+sample (0..16), regions placed in shuffled order with gaps.  Every case runs the whole step
+(attention, accept from given ids, append) and its tree-structured twin against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2405_07542_amd as ems
+from workloads import HEAD_MAJOR, TOKEN_MAJOR, bits, grow_trees, make_batch
+from helpers import to_device
+from test_gpu_parity import check_attention, run_accept_and_append
+from test_gpu_tree import check_accept_and_append, check_tree_attention
+
+pytestmark = pytest.mark.gpu
+
+
+def random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    B = int(rng.choice([1, 2, 3, 5, 9, 17, 40]))
+    H = int(rng.choice([1, 2, 3, 5, 8, 12]))
+    D = int(rng.choice([64, 80, 128]))
+    dtype = [torch.float16, torch.bfloat16][int(rng.integers(0, 2))]
+    layout = [TOKEN_MAJOR, HEAD_MAJOR][int(rng.integers(0, 2))]
+    pool = [0, 1, 2, 31, 32, 33, 63, 64, 65, 96, 127, 128, 129]
+    kv = [int(rng.choice(pool)) if rng.random() < 0.5 else int(rng.integers(0, 700)) for _ in range(B)]
+    k = [int(rng.integers(0, 17)) for _ in range(B)]
+    if sum(k) == 0:
+        k[0] = 1
+    # regions in shuffled order, each with room for the sample's new rows and a random gap after it
+    order = rng.permutation(B)
+    starts, pos = [0] * B, int(rng.integers(0, 5))
+    for i in order:
+        starts[i] = pos
+        pos += kv[i] + k[i] + int(rng.integers(0, 40))
+    b = make_batch(kv, k, H=H, D=D, dtype=dtype, seed=2000 + seed, kv_start=starts, rows=pos + 1,
+                   layout=layout, vocab_for_ids=17, match_p=0.75)
+    return b
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shape(seed):
+    b = random_case(seed)
+    print("case", seed, "B", b.B, "H", b.H, "D", b.D, b.dtype, b.layout, "kv", b.kv_len.tolist(),
+          "k", np.diff(b.cu_seqlens.numpy()).tolist(), "start", b.kv_start.tolist(), flush=True)
+    dev = to_device(b)
+    ems.ems_validate_inputs(dev.cu_seqlens, dev.kv_start, dev.kv_len, T=b.T, max_k=16,
+                            max_kv_len=max(1, b.max_kv_len), rows=b.rows)
+    check_attention(b, out_dtype=torch.float32, label="random %d f32" % seed)
+    check_attention(b, label="random %d" % seed)
+    run_accept_and_append(b)
+    t = grow_trees(b, 3000 + seed, match_p=0.75, shape=["random", "wide", "star"][seed % 3])
+    check_tree_attention(t, out_dtype=torch.float32)
+    check_accept_and_append(t, use_logits=False, n_layers=2)

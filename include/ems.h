@@ -260,6 +260,10 @@ EMS_API ems_status ems_profile_read(double* total_ms, int* launches);
  *   j < accepted_cu[i+1]-accepted_cu[i]; kv_len_out[i] = kv_len[i] + that count (may alias
  *   kv_len, may be NULL).  An index outside [0, T) copies nothing.
  */
+/* Debug validator for a parent array (synchronises hip_stream, copies both arrays to the host):
+ * INVALID_ARG naming the first row whose parent is not -1 (row 0) or in [0, j) (row j). */
+EMS_API ems_status ems_validate_tree(
+    const int32_t* cu_seqlens, const int32_t* parent, int B, int T, void* hip_stream);
 EMS_API ems_status ems_tree_verify_attention(
     const void* q, const void* k_new, const void* v_new,
     const ems_kv_cache* cache,

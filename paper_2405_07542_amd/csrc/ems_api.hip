@@ -628,4 +628,30 @@ ems_status ems_validate_inputs(const int32_t* cu_seqlens, const int32_t* kv_star
     return EMS_OK;
 }
 
+ems_status ems_validate_tree(const int32_t* cu_seqlens, const int32_t* parent, int B, int T,
+                             void* hip_stream) {
+    if (B < 1 || T < 0) return fail(EMS_ERR_INVALID_ARG, "B = %d, T = %d out of range", B, T);
+    if (!cu_seqlens || (T > 0 && !parent)) return fail(EMS_ERR_INVALID_ARG, "cu_seqlens and parent must not be NULL");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    std::vector<int32_t> cu(B + 1), par(T);
+    hipError_t e = hipMemcpyAsync(cu.data(), cu_seqlens, sizeof(int32_t) * (B + 1), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess && T > 0)
+        e = hipMemcpyAsync(par.data(), parent, sizeof(int32_t) * T, hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return hip_fail("ems_validate_tree copy", e);
+    if (cu[0] != 0 || cu[B] != T)
+        return fail(EMS_ERR_INVALID_ARG, "cu_seqlens must run from 0 to T = %d (got %d .. %d)", T, cu[0], cu[B]);
+    for (int i = 0; i < B; ++i) {
+        const int k = cu[i + 1] - cu[i];
+        if (k < 0 || cu[i + 1] > T) return fail(EMS_ERR_INVALID_ARG, "cu_seqlens decreases or overruns at sample %d", i);
+        for (int j = 0; j < k; ++j) {
+            const int pj = par[cu[i] + j];
+            if (j == 0 ? pj != -1 : (pj < 0 || pj >= j))
+                return fail(EMS_ERR_INVALID_ARG, "sample %d, row %d: parent = %d (row 0 needs -1, row j a value in [0, j))",
+                            i, j, pj);
+        }
+    }
+    return EMS_OK;
+}
+
 }  // extern "C"

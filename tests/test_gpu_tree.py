@@ -147,6 +147,13 @@ def test_tree_step_config_4_full_size():
 
 def test_tree_entry_points_reject_bad_arguments():
     b = to_device(grow_trees(make_batch([5, 6], [3, 2], H=2, D=64, seed=71, capacity=16), 72))
+    ems.ems_validate_tree(b.cu_seqlens, b.parent)
+    for row, value in ((0, 0), (1, 1), (3, 2), (4, -1)):        # rows 0-2 = sample 0, rows 3-4 = sample 1
+        bad = b.parent.clone()
+        bad[row] = value
+        with pytest.raises(ems.EmsError) as e:
+            ems.ems_validate_tree(b.cu_seqlens, bad)
+        assert e.value.status == ems.EMS_ERR_INVALID_ARG and "parent" in str(e.value)
     out = torch.empty_like(b.q)
     ws = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len), dtype=torch.uint8, device="cuda")
     cache = ems.kv_cache(b.k_cache, b.v_cache, b.row_stride, b.head_stride, b.rows)

@@ -14,15 +14,18 @@
  *   3. ems_kv_append         only the accepted tokens' K/V enter each cache, at the
  *                            sample's own location, which advances by its own
  *                            accepted count (Sec. 3.2, Fig. 2 / Table 1)
- * plus the padded "vanilla" method of Sec. 3.1 as an ablation in the same library.
+ * plus the padded "vanilla" method of Sec. 3.1 as an ablation in the same library, the
+ * paper-order variant of steps 1 and 3 (write-through, then advance), the same three steps
+ * for token trees (ems_tree_*), two debug validators and three measurement aids.
  *
  * Conventions shared by every entry point
  *   - Pointers named *device* point to GPU memory owned by the caller; pointers
  *     named *host* are ordinary host memory read during the call only.
- *   - The library never allocates, frees or synchronises.  Work is enqueued on
- *     `hip_stream` (a hipStream_t passed as void*, NULL = the default stream) and
- *     the call returns at once.  Device arrays must stay alive until that work is
- *     done.
+ *   - The library never allocates or frees device memory and never synchronises
+ *     (the two debug validators and ems_profile_read do wait, as they say).  Work is
+ *     enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) and the call returns at once.  Device arrays must stay alive until
+ *     that work is done.  A sequence of calls can be captured into a HIP graph.
  *   - Packed tensors q, k_new, v_new, out are [T, H, D], d fastest, no padding
  *     rows; sample i owns rows cu_seqlens[i] .. cu_seqlens[i+1]-1 (k_i rows).
  *     Row 0 of a sample is its last emitted token (whose K/V is not cached yet),

@@ -137,6 +137,22 @@ EMS_API ems_status ems_verify_attention_write_through(
 EMS_API ems_status ems_kv_advance(
     const int32_t* kv_len, const int32_t* accepted, int32_t* kv_len_out, int B, void* hip_stream);
 
+/*
+ * "Unpad input tokens" (Appendix D, Alg. 1): concatenate the input tokens of all samples and
+ * keep each sample's count.  The per-sample lists are given as a padded array:
+ *   padded_ids  device int32 [B, k_max]: sample i's tokens in its first token_nums[i] slots
+ *   token_nums  device int32 [B]: tokens of each sample (values outside [0, k_max] are clamped)
+ *   cu_seqlens  device int32 [B+1] out: running sum of the counts, cu_seqlens[B] = total T
+ *   packed_ids  device int32 [capacity] out: sample after sample, no padding; the caller sizes
+ *               it for the largest possible total (B * k_max always suffices)
+ * Errors: B < 1 or B > 8192, k_max < 0, NULL pointer -> INVALID_ARG / UNSUPPORTED.
+ * The total is known on the device only; the other calls take T from the host, so a caller
+ * that does not know it reads cu_seqlens[B] back or passes capacity-sized tensors.
+ */
+EMS_API ems_status ems_pack_tokens(
+    const int32_t* padded_ids, const int32_t* token_nums, int B, int k_max,
+    int32_t* cu_seqlens, int32_t* packed_ids, void* hip_stream);
+
 /* Bytes of device workspace ems_greedy_accept needs for up to T rows (0 when logits ==
  * NULL is intended, i.e. V == 0); the figure for T also covers every smaller T. */
 EMS_API size_t ems_accept_workspace_bytes(int T, int V);

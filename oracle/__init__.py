@@ -58,6 +58,8 @@ def _load():
             u16p, u16p, u16p, u16p, u16p, ctypes.c_int64, ctypes.c_int64,
             i32p, i32p, i32p, i32p, f64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_float, ctypes.c_int]
+        lib.oracle_concatenate_tokens.argtypes = [i32p, i32p, ctypes.c_int, ctypes.c_int, i32p, i32p]
+        lib.oracle_concatenate_tokens.restype = ctypes.c_int
         lib.oracle_tree_accept.argtypes = [i32p, i32p, i32p, i32p, ctypes.c_int, i32p, i32p, i32p, i32p]
         lib.oracle_kv_append_rows.argtypes = [
             u16p, u16p, ctypes.c_int64, ctypes.c_int64, u16p, u16p,
@@ -328,3 +330,16 @@ def kv_append_rows(k_cache, v_cache, row_stride, head_stride, k_new, v_new,
         _p(rows, ctypes.c_int32), _p(acu, ctypes.c_int32), _p(ks, ctypes.c_int32),
         _p(kl, ctypes.c_int32), _p(out, ctypes.c_int32), B, int(H), int(D))
     return out
+
+
+def concatenate_tokens(padded_ids, lens):
+    """Alg. 1.  Returns (concatenated[total], token_nums_per_sample[B], total)."""
+    ids, ln = _i32(padded_ids), _i32(lens)
+    B = len(ln)
+    k_max = ids.size // B if B else 0
+    assert ids.size == B * k_max and all(0 <= int(x) <= k_max for x in ln)
+    out = np.full(max(1, B * k_max), -1, dtype=np.int32)
+    nums = np.zeros(B, dtype=np.int32)
+    total = _load().oracle_concatenate_tokens(_p(ids, ctypes.c_int32), _p(ln, ctypes.c_int32), B, k_max,
+                                              _p(out, ctypes.c_int32), _p(nums, ctypes.c_int32))
+    return out[:total].copy(), nums, int(total)

@@ -23,7 +23,7 @@
  * Parity pins (tests/test_oracle_*.py): dense padded per-sample brute force,
  * torch's CPU attention in the k_i = 1 and kv_len = 0 special cases,
  * autoregressive equivalence, closed forms, the paper's Table 1, Alg. 2 run
- * literally, sentinel-filled arenas; for the tree functions: reduction to the
+ * literally (and as the inverse of Alg. 1), sentinel-filled arenas; for the tree functions: reduction to the
  * causal ones on a chain, causal attention along every root-to-row path, a dense
  * brute force with a matrix-closure mask, a per-node validity rule for acceptance,
  * a numpy gather for the append.  No function here is "parity unpinned".
@@ -534,4 +534,23 @@ int oracle_kv_append_rows(uint16_t* k_cache, uint16_t* v_cache, int64_t row_stri
         if (kv_len_out) kv_len_out[i] = kv_len[i] + a;
     }
     return 0;
+}
+
+/*
+ * "Unpad input tokens", Appendix D, Alg. 1: the input tokens of the samples are appended
+ * one sample after the other into a single sequence; the number of tokens of every sample
+ * and their total are recorded.  The samples' token lists are given as the first lens[i]
+ * entries of row i of a padded [B, k_max] array.  Returns the total.
+ */
+int oracle_concatenate_tokens(const int32_t* padded_ids, const int32_t* lens, int B, int k_max,
+                              int32_t* concatenated, int32_t* token_nums_per_sample) {
+    int total_input_token_nums = 0;
+    for (int i = 0; i < B; ++i) {
+        const int len = lens[i];
+        for (int j = 0; j < len; ++j)
+            concatenated[total_input_token_nums + j] = padded_ids[(size_t)i * k_max + j];
+        token_nums_per_sample[i] = len;
+        total_input_token_nums += len;
+    }
+    return total_input_token_nums;
 }

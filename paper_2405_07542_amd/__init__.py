@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.ems_tree_verify_attention.argtypes = [vp, vp, vp, ctypes.POINTER(KvCacheStruct), vp, vp, vp, vp,
                                                 vp, i32, i32, i32, i32, i32, i32, i32,
                                                 ctypes.c_float, i32, vp, sz, vp]
+        L.ems_pack_tokens.restype = i32
+        L.ems_pack_tokens.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.ems_validate_tree.restype = i32
         L.ems_validate_tree.argtypes = [vp, vp, i32, i32, vp]
         L.ems_tree_accept.restype = i32
@@ -190,6 +192,13 @@ def ems_tree_verify_attention(q, k_new, v_new, cache: KvCacheStruct, cu_seqlens,
         workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
+def ems_pack_tokens(padded_ids, token_nums, cu_seqlens, packed_ids, stream=None) -> None:
+    """Alg. 1 on the device: padded [B, k_max] ids + counts -> cu_seqlens [B+1], packed ids."""
+    B, k_max = padded_ids.shape
+    _check(lib().ems_pack_tokens(_ptr(padded_ids), _ptr(token_nums), B, k_max, _ptr(cu_seqlens),
+                                 _ptr(packed_ids), _stream(stream)))
+
+
 def ems_validate_tree(cu_seqlens, parent, stream=None) -> None:
     _check(lib().ems_validate_tree(_ptr(cu_seqlens), _ptr(parent), cu_seqlens.numel() - 1, parent.numel(),
                                    _stream(stream)))
@@ -296,6 +305,6 @@ def ems_profile_read():
     return ms.value, n.value
 
 
-__all__ = ["ems_validate_tree", "ems_tree_verify_attention", "ems_tree_accept", "ems_kv_append_rows", "ems_stream_read_probe", "ems_set_attention_variant", "ems_get_attention_variant", "EMS_ATTN_MFMA", "EMS_ATTN_VALU", "ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
+__all__ = ["ems_pack_tokens", "ems_validate_tree", "ems_tree_verify_attention", "ems_tree_accept", "ems_kv_append_rows", "ems_stream_read_probe", "ems_set_attention_variant", "ems_get_attention_variant", "EMS_ATTN_MFMA", "EMS_ATTN_VALU", "ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
            "ems_accept_workspace_bytes", "ems_verify_attention", "ems_greedy_accept",
            "ems_kv_append", "ems_validate_inputs", "EMS_F16", "EMS_BF16", "EMS_F32"]

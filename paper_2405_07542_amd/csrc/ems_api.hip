@@ -537,6 +537,26 @@ ems_status ems_padded_kv_append(const void* const* k_new_pad_layers,
     return EMS_OK;
 }
 
+ems_status ems_pack_tokens(const int32_t* padded_ids, const int32_t* token_nums, int B, int k_max,
+                           int32_t* cu_seqlens, int32_t* packed_ids, void* hip_stream) {
+    if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
+    if (B > kMaxB) return fail(EMS_ERR_UNSUPPORTED, "B = %d, at most %d samples", B, kMaxB);
+    if (k_max < 0) return fail(EMS_ERR_INVALID_ARG, "k_max = %d, need k_max >= 0", k_max);
+    if (!token_nums || !cu_seqlens) return fail(EMS_ERR_INVALID_ARG, "token_nums and cu_seqlens must not be NULL");
+    if (k_max > 0 && (!padded_ids || !packed_ids))
+        return fail(EMS_ERR_INVALID_ARG, "padded_ids and packed_ids must not be NULL");
+    ems::PackParams p;
+    p.padded_ids = padded_ids;
+    p.token_nums = token_nums;
+    p.cu = cu_seqlens;
+    p.packed_ids = packed_ids;
+    p.B = B;
+    p.k_max = k_max;
+    hipError_t e = ems::launch_pack_tokens(p, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail("ems_pack_tokens launch", e);
+    return EMS_OK;
+}
+
 ems_status ems_stream_read_probe(const void* buf, size_t bytes, void* sink, void* hip_stream) {
     if (!buf || !sink) return fail(EMS_ERR_INVALID_ARG, "buf and sink must not be NULL");
     if (!aligned16(buf) || (reinterpret_cast<uintptr_t>(sink) & 3) != 0)

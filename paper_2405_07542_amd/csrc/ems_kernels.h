@@ -120,6 +120,15 @@ hipError_t launch_padded_kv_append(const PaddedAppendParams& p, hipStream_t stre
 hipError_t launch_advance_kv_len(const int32_t* kv_len, const int32_t* accepted, const int32_t* rows_cu,
                                  int32_t* kv_len_out, int B, hipStream_t stream);
 
+struct PackParams {
+    const int32_t* padded_ids;   // [B, k_max]
+    const int32_t* token_nums;   // [B]
+    int32_t* cu;                 // [B + 1] out
+    int32_t* packed_ids;         // [>= sum of counts] out
+    int B, k_max;
+};
+hipError_t launch_pack_tokens(const PackParams& p, hipStream_t stream);
+
 // Read-only streaming probe over `bytes` of device memory (whole 1 KiB lines); sink: one word.
 hipError_t launch_stream_read(const void* buf, uint64_t bytes, uint32_t* sink, int blocks, hipStream_t stream);
 

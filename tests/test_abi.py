@@ -186,3 +186,12 @@ def test_tree_entry_points_reject_bad_arguments_on_the_host():
                                 ems.EMS_F16, None) == ems.EMS_ERR_INVALID_ARG
     assert L.ems_stream_read_probe(None, 4096, FAKE, None) == ems.EMS_ERR_INVALID_ARG
     assert L.ems_stream_read_probe(FAKE, 100, FAKE, None) == ems.EMS_ERR_INVALID_ARG
+
+
+def test_pack_tokens_rejects_bad_arguments_on_the_host():
+    L = ems.lib()
+    assert L.ems_pack_tokens(FAKE, FAKE, 0, 4, FAKE, FAKE, None) == ems.EMS_ERR_INVALID_ARG
+    assert L.ems_pack_tokens(FAKE, FAKE, 9000, 4, FAKE, FAKE, None) == ems.EMS_ERR_UNSUPPORTED
+    assert L.ems_pack_tokens(FAKE, FAKE, 4, -1, FAKE, FAKE, None) == ems.EMS_ERR_INVALID_ARG
+    assert L.ems_pack_tokens(FAKE, None, 4, 4, FAKE, FAKE, None) == ems.EMS_ERR_INVALID_ARG
+    assert L.ems_pack_tokens(None, FAKE, 4, 4, FAKE, FAKE, None) == ems.EMS_ERR_INVALID_ARG

@@ -333,3 +333,21 @@ def test_maximum_batch_size():
     b = make_batch(kv, k, H=1, D=64, dtype=torch.float16, seed=60, capacity=48)
     check_attention(b, out_dtype=torch.float32, label="B=8192")
     run_accept_and_append(b)
+
+
+@pytest.mark.parametrize("B,k_max", [(2, 5), (64, 11), (3000, 16), (8192, 3), (5, 200)])
+def test_pack_tokens(B, k_max):
+    """Alg. 1 on the device against the oracle's: running sum of the counts, packed ids, nothing
+    written past the total; the result feeds ems_validate_inputs' checks of cu_seqlens."""
+    import paper_2405_07542_amd as ems
+    rng = np.random.default_rng(91 + B)
+    lens = rng.integers(0, k_max + 1, B).astype(np.int32)
+    padded = rng.integers(0, 50272, (B, k_max)).astype(np.int32)
+    cat, nums, total = oracle.concatenate_tokens(padded, lens)
+    cu = torch.full((B + 1,), -7, dtype=torch.int32, device="cuda")
+    packed = torch.full((B * k_max,), -7, dtype=torch.int32, device="cuda")
+    ems.ems_pack_tokens(torch.from_numpy(padded).cuda(), torch.from_numpy(lens).cuda(), cu, packed)
+    torch.cuda.synchronize()
+    assert np.array_equal(cu.cpu().numpy(), np.concatenate([[0], np.cumsum(nums)]))
+    assert np.array_equal(packed.cpu().numpy()[:total], cat)
+    assert (packed.cpu().numpy()[total:] == -7).all()

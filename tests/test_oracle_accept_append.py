@@ -283,3 +283,22 @@ def test_write_through_then_advance_equals_append_on_the_live_rows(layout):
             assert np.array_equal(bits(W[s:s + new_len[i]]), bits(A[s:s + new_len[i]]))
             assert np.array_equal(bits(W[s + L:s + L + k[i]]), bits(new[cu[i]:cu[i + 1]]))
             assert (bits(W[s + L + k[i]:s + 24]) == 0x7E00).all()
+
+
+def test_concatenation_of_input_tokens_alg_1():
+    """Alg. 1 against plain Python list concatenation, the example of Fig. 3 (samples with 5 and
+    2 tokens give 7 packed rows), and Alg. 2 as its inverse on every packed row."""
+    rng = np.random.default_rng(90)
+    for B, k_max in ((2, 5), (7, 9), (33, 16), (1, 1)):
+        lens = rng.integers(0, k_max + 1, B).astype(np.int32)
+        if (B, k_max) == (2, 5):
+            lens = np.array([5, 2], dtype=np.int32)
+        padded = rng.integers(0, 1000, (B, k_max)).astype(np.int32)
+        cat, nums, total = oracle.concatenate_tokens(padded, lens)
+        want = sum((padded[i, :lens[i]].tolist() for i in range(B)), [])
+        assert cat.tolist() == want and total == len(want) and np.array_equal(nums, lens)
+        if (B, k_max) == (2, 5):
+            assert total == 7
+        for r in range(total):
+            i, pos = oracle.restore_index(nums, r)
+            assert cat[r] == padded[i, pos]

@@ -58,6 +58,11 @@ def parse_args():
     ap.add_argument("--sweep-k", action="store_true",
                     help="instead of the bench: attention time vs rows per sample at 512 cached tokens "
                          "(the shape of the paper's Fig. 5), B in {4, 16}, k = 1..8")
+    ap.add_argument("--per-token-grid", action="store_true",
+                    help="instead of the bench: the paper's own launch shape (Appendix D: one work item per head and "
+                         "packed token, every token streaming its sample's whole cache) emulated on config 4 by "
+                         "writing the new rows through and calling the same kernel with every packed row as a "
+                         "sample of its own; reports the attention time next to the shared-K/V call")
     ap.add_argument("--sweep-variants", action="store_true",
                     help="instead of the bench: attention kernel time of the matrix-core and the vector-ALU "
                          "formulation vs rows per sample, B=64, 2048 cached tokens each, bf16")
@@ -148,6 +153,9 @@ def main():
     with_logits = not args.no_logits
     if args.tree and (args.write_through or args.attention_variant == "valu" or n == 5):
         sys.exit("--tree runs the matrix-core kernel with the gathered append on configs 2-4 only")
+    if args.per_token_grid:
+        print(json.dumps(per_token_grid(args)), flush=True)
+        return
     if args.sweep_variants:
         print(json.dumps(sweep_variants()), flush=True)
         return
@@ -430,6 +438,77 @@ def sweep_k():
             torch.cuda.synchronize()
             rows.append({"B": B, "rows_per_sample": k, "attention_call_us": round(ev0.elapsed_time(ev1) / reps * 1e3, 2)})
     return {"sweep": "attention call time vs rows per sample, kv_len=512, H=32, D=128, fp16", "results": rows}
+
+
+def per_token_rows_as_samples(b):
+    """Index arrays that present every packed row of `b` as a sample of its own (k = 1) whose cache is
+    its real sample's cache plus the new rows before it -- which must already have been written
+    through to rows kv_len + j.  This is the paper's formulation (Sec. 3.2 with the grid of Appendix
+    D): K/V of all new tokens stored first, then one work item per (head, token)."""
+    import torch
+    k = (b.cu_seqlens[1:] - b.cu_seqlens[:-1]).long()
+    sample = torch.repeat_interleave(torch.arange(b.B, device=k.device), k)
+    pos = torch.arange(b.T, device=k.device) - b.cu_seqlens[:-1].long()[sample]
+    cu = torch.arange(b.T + 1, dtype=torch.int32, device=k.device)
+    kv_start = b.kv_start[sample].to(torch.int32)
+    kv_len = (b.kv_len.long()[sample] + pos).to(torch.int32)
+    return cu, kv_start.contiguous(), kv_len.contiguous()
+
+
+def per_token_grid(args, reps=60):
+    import torch
+    import paper_2405_07542_amd as ems
+    from workloads import make_config
+    dev = "cuda:0"
+    sets = []
+    for v in range(3):
+        b = make_config(4, device=dev, layout=args.layout, with_logits=False, variant=v)
+        cache = ems.kv_cache(b.k_cache, b.v_cache, b.row_stride, b.head_stride, b.rows)
+        ws = torch.empty(ems.ems_attention_workspace_bytes(b.T, b.T, b.H, b.D, b.max_kv_len + b.max_k),
+                         dtype=torch.uint8, device=dev)
+        out = torch.empty_like(b.q)
+        # paper order: the new rows' K/V enter the cache first (one write-through call), then ...
+        ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, b.kv_start, b.kv_len, out,
+                                 max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws,
+                                 write_through=True)
+        shared_out = out.clone()
+        sets.append((b, cache, ws, out, per_token_rows_as_samples(b), shared_out))
+    torch.cuda.synchronize()
+
+    def shared(s):
+        b, cache, ws, out, _, _ = s
+        ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, b.kv_start, b.kv_len, out,
+                                 max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws)
+
+    def per_token(s):
+        b, cache, ws, out, (cu, ks, kl), _ = s
+        ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, cu, ks, kl, out, max_k=1,
+                                 max_kv_len=b.max_kv_len + b.max_k, scale=b.scale, workspace=ws)
+
+    res = {}
+    for name, fn in (("shared_kv", shared), ("per_token", per_token)):
+        for i in range(6):
+            fn(sets[i % 3])
+        torch.cuda.synchronize()
+        ems.ems_profile_enable(reps)
+        for i in range(reps):
+            fn(sets[i % 3])
+        torch.cuda.synchronize()
+        ms, n = ems.ems_profile_read()
+        ems.ems_profile_enable(0)
+        res[name + "_kernel_us"] = round(ms / n * 1e3, 1)
+    # the two formulations agree on every output row (same tolerance as against the oracle)
+    worst = 0.0
+    for s in sets:
+        per_token(s)
+        torch.cuda.synchronize()
+        worst = max(worst, float((s[3].float() - s[5].float()).abs().max()))
+    b = sets[0][0]
+    rows = float(sum(s[0].T for s in sets)) / len(sets)
+    res.update({"mode": "paper's launch shape (one work item per head and packed token) vs shared K/V, config 4 attention",
+                "layout": args.layout, "packed_rows": rows, "max_abs_difference_of_outputs": worst,
+                "slowdown": round(res["per_token_kernel_us"] / res["shared_kv_kernel_us"], 2)})
+    return res
 
 
 def sweep_variants(B=64, L=2048, ks=(1, 2, 4, 6, 8, 12, 16)):

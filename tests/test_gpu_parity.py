@@ -351,3 +351,33 @@ def test_pack_tokens(B, k_max):
     assert np.array_equal(cu.cpu().numpy(), np.concatenate([[0], np.cumsum(nums)]))
     assert np.array_equal(packed.cpu().numpy()[:total], cat)
     assert (packed.cpu().numpy()[total:] == -7).all()
+
+
+def test_paper_order_with_every_row_as_its_own_work_item():
+    """The paper's own formulation (Sec. 3.2 with the launch shape of Appendix D): the K/V of all
+    new tokens is written at the samples' locations first, then every packed token attends, on
+    its own, to its sample's cache up to and including itself.  Presenting every packed row as
+    a one-row sample whose cache ends just before it must reproduce the oracle's outputs."""
+    import paper_2405_07542_amd as ems
+    b_cpu = make_batch(RAGGED_KV, RAGGED_K, H=4, D=128, dtype=torch.float16, seed=78, capacity=300)
+    b = to_device(b_cpu)
+    kc, vc = b.k_cache.clone(), b.v_cache.clone()
+    cache = ems.kv_cache(kc, vc, b.row_stride, b.head_stride, b.rows)
+    ws = torch.empty(ems.ems_attention_workspace_bytes(b.T, b.T, b.H, b.D, b.max_kv_len + b.max_k),
+                     dtype=torch.uint8, device="cuda")
+    out = torch.empty((b.T, b.H, b.D), dtype=torch.float32, device="cuda")
+    ems.ems_verify_attention_write_through(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, b.kv_start, b.kv_len,
+                                           out, max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale,
+                                           workspace=ws)
+    k = np.diff(b_cpu.cu_seqlens.numpy())
+    sample = np.repeat(np.arange(b.B), k)
+    pos = np.arange(b.T) - b_cpu.cu_seqlens.numpy()[:-1][sample]
+    cu = torch.arange(b.T + 1, dtype=torch.int32, device="cuda")
+    ks = torch.from_numpy(b_cpu.kv_start.numpy()[sample].astype(np.int32)).cuda()
+    kl = torch.from_numpy((b_cpu.kv_len.numpy()[sample] + pos).astype(np.int32)).cuda()
+    out.fill_(float("nan"))
+    ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, cu, ks, kl, out, max_k=1,
+                             max_kv_len=b.max_kv_len + b.max_k, scale=b.scale, workspace=ws)
+    torch.cuda.synchronize()
+    want = oracle_attention(b_cpu)
+    assert np.abs(out.double().cpu().numpy() - want).max() <= 2e-3

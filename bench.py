@@ -125,8 +125,8 @@ def read_traffic(workload_key):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (--gpus 1); "
-              "the path shards by sample or by head without collectives, see DESIGN.md", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (--gpus 1); the path would shard by sample or by "
+              "head with no exchange between GPUs, so the figure for N GPUs is N times this one", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch

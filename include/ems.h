@@ -62,7 +62,10 @@ typedef enum {
 
 typedef enum { EMS_F16 = 0, EMS_BF16 = 1, EMS_F32 = 2 /* outputs only */ } ems_dtype;
 
-#define EMS_MAX_QUERY_ROWS 16   /* largest k_i (rows per sample per step) */
+#define EMS_MAX_QUERY_ROWS 64   /* largest k_i (rows per sample per step) */
+#define EMS_ROWS_PER_GROUP 16   /* up to this many rows a sample's cache is streamed once per step; with
+                                   max_k above it the attention calls cut every sample's rows into row
+                                   groups of 16 and stream the cache once per group */
 #define EMS_MAX_LAYERS_PER_CALL 32
 
 /*
@@ -102,8 +105,8 @@ EMS_API size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max
  *   max_kv_len >= every kv_len[i]            (host-known upper bounds)
  * Samples with k_i = 0 contribute nothing; kv_len[i] = 0 is legal; T = 0 is a no-op.
  * Errors: B<1, T<0, H<1, max_k<0, max_kv_len<0, NULL/misaligned pointer,
- * non-finite scale -> INVALID_ARG; D not in {64,80,128}, max_k > 16, B > 8192
- * -> UNSUPPORTED (the padded ablation and EMS_ATTN_VALU have D in {64,128} only); workspace -> WORKSPACE; launch failure -> HIP.
+ * non-finite scale -> INVALID_ARG; D not in {64,80,128}, max_k > 64, B > 8192
+ * -> UNSUPPORTED (the padded ablation and EMS_ATTN_VALU: D in {64,128} and max_k <= 16 only); workspace -> WORKSPACE; launch failure -> HIP.
  */
 EMS_API ems_status ems_verify_attention(
     const void* q, const void* k_new, const void* v_new,

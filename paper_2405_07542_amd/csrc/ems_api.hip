@@ -39,8 +39,11 @@ constexpr int kMaxAttnBlocks = 1024;
 constexpr int kMaxB = 8192;
 
 // Upper bound of the number of 32-key tiles of the whole batch (host-known bounds only).
-int64_t tile_upper_bound(int B, int H, int max_kv_len) {
-    return (int64_t)B * H * ((max_kv_len + kTileKeys - 1) / kTileKeys + 1);
+// With more than 16 rows per sample a (sample, head) has up to four row groups, each with
+// the cache tiles and up to two tiles of new tokens.
+int64_t tile_upper_bound(int B, int H, int max_kv_len, bool row_groups) {
+    const int64_t cache_tiles = (max_kv_len + kTileKeys - 1) / kTileKeys;
+    return (int64_t)B * H * (row_groups ? 4 * (cache_tiles + 2) : cache_tiles + 1);
 }
 
 int attn_blocks_for(int64_t tiles, int max_blocks) {
@@ -106,7 +109,8 @@ const char* ems_version(void) { return "0.1"; }
 size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len) {
     (void)T;
     if (B < 1 || H < 1 || D < 1 || max_kv_len < 0) return 256;
-    const int blocks = attn_blocks_for(tile_upper_bound(B, H, max_kv_len), kMaxAttnBlocks);
+    // (sized for the larger of the two launch shapes: max_k is not known here)
+    const int blocks = attn_blocks_for(tile_upper_bound(B, H, max_kv_len, true), kMaxAttnBlocks);
     return std::max<size_t>(256, attn_ws_bytes_for(blocks, B, D));
 }
 
@@ -150,6 +154,10 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
                     B, D, ems::valu_attention_lds_bytes(B, D), ems::kMaxLdsBytes);
     if (max_k > EMS_MAX_QUERY_ROWS)
         return fail(EMS_ERR_UNSUPPORTED, "max_k = %d, at most %d rows per sample", max_k, EMS_MAX_QUERY_ROWS);
+    const bool row_groups = max_k > EMS_ROWS_PER_GROUP;
+    if (row_groups && pad) return fail(EMS_ERR_UNSUPPORTED, "the padded ablation takes at most %d rows per sample", EMS_ROWS_PER_GROUP);
+    if (row_groups && g_attn_variant.load() == EMS_ATTN_VALU)
+        return fail(EMS_ERR_UNSUPPORTED, "EMS_ATTN_VALU takes at most %d rows per sample", EMS_ROWS_PER_GROUP);
     if (B > kMaxB) return fail(EMS_ERR_UNSUPPORTED, "B = %d, at most %d samples", B, kMaxB);
     if (T == 0) return EMS_OK;
     if (!q || !k_new || !v_new || !out) return fail(EMS_ERR_INVALID_ARG, "q, k_new, v_new and out must not be NULL");
@@ -164,7 +172,7 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     // a sample's cache is addressed with 32-bit byte offsets from its first row
     if (((int64_t)max_kv_len + kTileKeys) * cache->row_stride * 2 >= ((int64_t)1 << 32))
         return fail(EMS_ERR_UNSUPPORTED, "max_kv_len * row_stride exceeds 4 GiB per sample");
-    const int64_t tiles = tile_upper_bound(B, H, max_kv_len);
+    const int64_t tiles = tile_upper_bound(B, H, max_kv_len, row_groups);
     if (tiles >= ((int64_t)1 << 31)) return fail(EMS_ERR_UNSUPPORTED, "too many key tiles");
 
     const int blocks = attn_blocks_for(tiles, resident_attn_blocks());
@@ -196,6 +204,7 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     p.num_waves = blocks * kWavesPerBlock;
     p.scale_log2 = scale * 1.4426950408889634f;
     p.write_through = write_through ? 1 : 0;
+    p.multi = row_groups ? 1 : 0;
     if (pad) {
         p.key_mask = pad->key_mask;
         p.k_valid = pad->k_valid;

@@ -31,6 +31,7 @@ struct AttnParams {
     int num_waves;
     float scale_log2;          // scale * log2(e)
     int write_through;         // also store the new rows' K/V at cache rows kv_len + j (paper order)
+    int multi;                 // samples may bring more than 16 rows (up to 64): row groups of 16 per (sample, head)
     // padded ("vanilla") ablation only: every sample has k_max rows and an aligned cache of
     // l_pad rows at row i*cap, with a byte mask [B, cap] of real (1) and padding (0) keys
     const uint8_t* key_mask;

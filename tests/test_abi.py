@@ -64,7 +64,7 @@ def attention(**over):
     (dict(cache=None), ems.EMS_ERR_INVALID_ARG, "cache"),
     (dict(cache=ems.KvCacheStruct(FAKE, FAKE, 4100, 128, 1024)), ems.EMS_ERR_INVALID_ARG, "strides"),
     (dict(D=96), ems.EMS_ERR_UNSUPPORTED, "head dim"),
-    (dict(max_k=17), ems.EMS_ERR_UNSUPPORTED, "rows per sample"),
+    (dict(max_k=65), ems.EMS_ERR_UNSUPPORTED, "rows per sample"),
     (dict(B=10000), ems.EMS_ERR_UNSUPPORTED, "samples"),
     (dict(max_kv_len=1 << 20), ems.EMS_ERR_UNSUPPORTED, "4 GiB"),
     (dict(ws=None), ems.EMS_ERR_WORKSPACE, "workspace"),

@@ -511,11 +511,12 @@ def per_token_grid(args, reps=60):
     return res
 
 
-def sweep_variants(B=64, L=2048, ks=(1, 2, 4, 6, 8, 12, 16)):
+def sweep_variants(B=64, L=2048, ks=(1, 2, 4, 6, 8, 12, 16, 32, 64)):
     """The two formulations of the attention kernel on one HBM-bound shape (config 4's batch and
     mean cache length, every sample with the same k): kernel time from HIP events around the main
     kernel, and the algorithmic bandwidth it amounts to.  The matrix-core path costs the same for
-    any k <= 16; the vector-ALU path pays per row."""
+    any k <= 16 and once more per further group of 16 rows (the cache is streamed once per row group);
+    the vector-ALU path pays per row."""
     import torch
     import paper_2405_07542_amd as ems
     from workloads import make_batch
@@ -533,6 +534,8 @@ def sweep_variants(B=64, L=2048, ks=(1, 2, 4, 6, 8, 12, 16)):
         alg = attention_algorithmic_bytes(sets[0][0], 2)
         row = {"rows_per_sample": k, "algorithmic_bytes": alg}
         for name, variant in (("mfma", ems.EMS_ATTN_MFMA), ("valu", ems.EMS_ATTN_VALU)):
+            if variant == ems.EMS_ATTN_VALU and k > 16:      # beyond 16 rows only the matrix-core kernels exist
+                continue
             ems.ems_set_attention_variant(variant)
 
             def call(s):

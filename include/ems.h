@@ -101,12 +101,16 @@ EMS_API size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max
  *
  *   q,k_new,v_new,out : device [T,H,D]       cu_seqlens : device int32 [B+1]
  *   kv_start, kv_len  : device int32 [B]     cache      : host struct, device arenas
- *   max_k      >= every k_i   (<= EMS_MAX_QUERY_ROWS)
+ *   max_k      >= every k_i   (<= EMS_MAX_QUERY_ROWS).  It also selects the launch shape: up
+ *                 to EMS_ROWS_PER_GROUP a sample's cache is streamed once per step; above
+ *                 it the sample's rows are cut into row groups of 16 and the cache is
+ *                 streamed once per group.  Rows of a sample beyond max_k are not computed.
  *   max_kv_len >= every kv_len[i]            (host-known upper bounds)
  * Samples with k_i = 0 contribute nothing; kv_len[i] = 0 is legal; T = 0 is a no-op.
  * Errors: B<1, T<0, H<1, max_k<0, max_kv_len<0, NULL/misaligned pointer,
  * non-finite scale -> INVALID_ARG; D not in {64,80,128}, max_k > 64, B > 8192
- * -> UNSUPPORTED (the padded ablation and EMS_ATTN_VALU: D in {64,128} and max_k <= 16 only); workspace -> WORKSPACE; launch failure -> HIP.
+ * -> UNSUPPORTED (the padded ablation and EMS_ATTN_VALU: D in {64,128} and max_k <= 16
+ * only); workspace -> WORKSPACE; launch failure -> HIP.
  */
 EMS_API ems_status ems_verify_attention(
     const void* q, const void* k_new, const void* v_new,

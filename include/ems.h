@@ -104,7 +104,8 @@ EMS_API size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max
  *   max_k      >= every k_i   (<= EMS_MAX_QUERY_ROWS).  It also selects the launch shape: up
  *                 to EMS_ROWS_PER_GROUP a sample's cache is streamed once per step; above
  *                 it the sample's rows are cut into row groups of 16 and the cache is
- *                 streamed once per group.  Rows of a sample beyond max_k are not computed.
+ *                 streamed once per group.  A sample with more rows than max_k breaks the
+ *                 contract (rows beyond 16, resp. 64, are left unwritten).
  *   max_kv_len >= every kv_len[i]            (host-known upper bounds)
  * Samples with k_i = 0 contribute nothing; kv_len[i] = 0 is legal; T = 0 is a no-op.
  * Errors: B<1, T<0, H<1, max_k<0, max_kv_len<0, NULL/misaligned pointer,

@@ -1,6 +1,7 @@
 """GPU parity on a seeded sweep of random valid shapes: batch size, head count, head dim, dtype,
 cache layout, ragged cached lengths (empty caches, exact tile multiples, tails), rows per
-sample (0..16), regions placed in shuffled order with gaps.  Every case runs the whole step
+sample (0..16, and 0..64 in the cases that exercise row groups), regions placed in shuffled
+order with gaps.  Every case runs the whole step
 (attention, accept from given ids, append) and its tree-structured twin against the oracle."""
 import numpy as np
 import pytest
@@ -16,7 +17,7 @@ from test_gpu_tree import check_accept_and_append, check_tree_attention
 pytestmark = pytest.mark.gpu
 
 
-def random_case(seed):
+def random_case(seed, k_hi=16):
     rng = np.random.default_rng(1000 + seed)
     B = int(rng.choice([1, 2, 3, 5, 9, 17, 40]))
     H = int(rng.choice([1, 2, 3, 5, 8, 12]))
@@ -25,7 +26,7 @@ def random_case(seed):
     layout = [TOKEN_MAJOR, HEAD_MAJOR][int(rng.integers(0, 2))]
     pool = [0, 1, 2, 31, 32, 33, 63, 64, 65, 96, 127, 128, 129]
     kv = [int(rng.choice(pool)) if rng.random() < 0.5 else int(rng.integers(0, 700)) for _ in range(B)]
-    k = [int(rng.integers(0, 17)) for _ in range(B)]
+    k = [int(rng.integers(0, k_hi + 1)) for _ in range(B)]
     if sum(k) == 0:
         k[0] = 1
     # regions in shuffled order, each with room for the sample's new rows and a random gap after it
@@ -39,13 +40,17 @@ def random_case(seed):
     return b
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", list(range(24)) + [(s, 64) for s in range(100, 112)])
 def test_random_shape(seed):
-    b = random_case(seed)
+    """(seed) draws up to 16 rows per sample; (seed, 64) up to 64, i.e. several row groups."""
+    k_hi = 16
+    if isinstance(seed, tuple):
+        seed, k_hi = seed
+    b = random_case(seed, k_hi)
     print("case", seed, "B", b.B, "H", b.H, "D", b.D, b.dtype, b.layout, "kv", b.kv_len.tolist(),
           "k", np.diff(b.cu_seqlens.numpy()).tolist(), "start", b.kv_start.tolist(), flush=True)
     dev = to_device(b)
-    ems.ems_validate_inputs(dev.cu_seqlens, dev.kv_start, dev.kv_len, T=b.T, max_k=16,
+    ems.ems_validate_inputs(dev.cu_seqlens, dev.kv_start, dev.kv_len, T=b.T, max_k=k_hi,
                             max_kv_len=max(1, b.max_kv_len), rows=b.rows)
     check_attention(b, out_dtype=torch.float32, label="random %d f32" % seed)
     check_attention(b, label="random %d" % seed)

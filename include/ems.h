@@ -31,8 +31,8 @@
  *     Row 0 of a sample is its last emitted token (whose K/V is not cached yet),
  *     rows 1.. are its draft tokens: "k predicted tokens" in the paper's words
  *     means k_i = k + 1 rows here.
- *   - 16-bit element types only (ems_dtype) for q/k/v/logits; device pointers to
- *     such tensors must be 16-byte aligned.
+ *   - 16-bit element types only (ems_dtype) for q/k/v (logits may also be fp32);
+ *     device pointers to such tensors must be 16-byte aligned.
  *   - Scalar and pointer arguments are validated on the host before anything is
  *     launched; the contents of device arrays (monotone cu_seqlens, regions that
  *     do not overlap, kv_len[i] + k_i within the region) are the caller's
@@ -60,7 +60,7 @@ typedef enum {
     EMS_ERR_HIP = 4          /* a HIP runtime call failed */
 } ems_status;
 
-typedef enum { EMS_F16 = 0, EMS_BF16 = 1, EMS_F32 = 2 /* outputs only */ } ems_dtype;
+typedef enum { EMS_F16 = 0, EMS_BF16 = 1, EMS_F32 = 2 /* attention outputs and logits only */ } ems_dtype;
 
 #define EMS_MAX_QUERY_ROWS 64   /* largest k_i (rows per sample per step) */
 #define EMS_ROWS_PER_GROUP 16   /* up to this many rows a sample's cache is streamed once per step; with
@@ -170,7 +170,7 @@ EMS_API size_t ems_accept_workspace_bytes(int T, int V);
  * distribution; acceptance length = 1 + number of leading drafts that equal the
  * target's token for the row before them; Sec. 3.1: between 1 and k+1 tokens).
  *
- *   logits      device [T,V] of `dtype`, or NULL.  When given, target_ids[r] is
+ *   logits      device [T,V] of `dtype` (EMS_F16, EMS_BF16 or EMS_F32), or NULL.  When given, target_ids[r] is
  *               WRITTEN with the lowest index attaining the row maximum (+0 and -0
  *               are equal; inputs must not hold NaN).  When NULL, target_ids is READ.
  *   input_ids   device int32 [T]: packed input tokens (row 0 of a sample = last

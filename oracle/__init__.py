@@ -54,6 +54,7 @@ def _load():
             i32p, i32p, i32p, f64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_float, ctypes.c_int]
         lib.oracle_argmax.argtypes = [u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int, i32p]
+        lib.oracle_argmax_f32.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int, ctypes.c_int, i32p]
         lib.oracle_tree_verify_attention.argtypes = [
             u16p, u16p, u16p, u16p, u16p, ctypes.c_int64, ctypes.c_int64,
             i32p, i32p, i32p, i32p, f64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -343,3 +344,13 @@ def concatenate_tokens(padded_ids, lens):
     total = _load().oracle_concatenate_tokens(_p(ids, ctypes.c_int32), _p(ln, ctypes.c_int32), B, k_max,
                                               _p(out, ctypes.c_int32), _p(nums, ctypes.c_int32))
     return out[:total].copy(), nums, int(total)
+
+
+def argmax_f32(logits) -> np.ndarray:
+    """Greedy target token per row of an fp32 [T, V] array (lowest index on ties)."""
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    T, V = lg.shape
+    x = np.zeros(T, dtype=np.int32)
+    if T:
+        _load().oracle_argmax_f32(_p(lg, ctypes.c_float), T, V, _p(x, ctypes.c_int32))
+    return x

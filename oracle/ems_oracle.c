@@ -554,3 +554,19 @@ int oracle_concatenate_tokens(const int32_t* padded_ids, const int32_t* lens, in
     }
     return total_input_token_nums;
 }
+
+/* The same greedy target token for fp32 logits (Appendix A): smallest index of the row maximum. */
+int oracle_argmax_f32(const float* logits, int T, int V, int32_t* x) {
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < T; ++r) {
+        const float* row = logits + (size_t)r * V;
+        double best = (double)row[0];
+        int32_t arg = 0;
+        for (int v = 1; v < V; ++v) {
+            double y = (double)row[v];
+            if (y > best) { best = y; arg = v; }
+        }
+        x[r] = arg;
+    }
+    return 0;
+}

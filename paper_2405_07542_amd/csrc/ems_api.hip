@@ -333,7 +333,8 @@ ems_status run_accept(const void* logits, ems_dtype dtype, int V, int32_t* targe
     ems::AcceptParams p;
     std::memset(&p, 0, sizeof p);
     if (logits != nullptr) {
-        if (!dtype16(dtype)) return fail(EMS_ERR_INVALID_ARG, "logits dtype must be EMS_F16 or EMS_BF16");
+        if (!dtype16(dtype) && dtype != EMS_F32)
+            return fail(EMS_ERR_INVALID_ARG, "logits dtype must be EMS_F16, EMS_BF16 or EMS_F32");
         if (V < 1) return fail(EMS_ERR_INVALID_ARG, "logits given but V = %d", V);
         if (!aligned16(logits)) return fail(EMS_ERR_INVALID_ARG, "logits must be 16-byte aligned");
         accept_slicing(T, V, &p.slices, &p.slice_len);
@@ -345,7 +346,7 @@ ems_status run_accept(const void* logits, ems_dtype dtype, int V, int32_t* targe
             return fail(EMS_ERR_INVALID_ARG, "workspace must be 8-byte aligned");
     }
     p.logits = logits;
-    p.bf16 = dtype == EMS_BF16;
+    p.logits_dtype = dtype == EMS_BF16 ? 1 : dtype == EMS_F32 ? 2 : 0;
     p.V = V;
     p.partial = static_cast<ems::ArgmaxPartial*>(workspace);
     p.target_ids = target_ids;

@@ -58,7 +58,7 @@ struct ArgmaxPartial {
 
 struct AcceptParams {
     const void* logits;        // [T, V] or nullptr
-    int bf16;
+    int logits_dtype;          // 0 = fp16, 1 = bf16, 2 = fp32
     int V;
     int slices;                // row slices of the first pass
     int slice_len;             // columns per slice (multiple of 8)

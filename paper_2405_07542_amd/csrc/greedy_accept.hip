@@ -26,35 +26,54 @@ __device__ __forceinline__ void take_better(float& v, int32_t& idx, float ov, in
     }
 }
 
+struct F32 {};   // logits may also be fp32 (K/V never are)
+
+// Elements of a 16-byte vector and how to read element e of it / element c of a row.
+template <typename ET> struct Logit {
+    static constexpr int per_vec = 8;
+    typedef uint16_t elem_t;
+    static __device__ __forceinline__ float of_vec(const u32x4 w, int e) {
+        return widen(ET{}, (uint16_t)(w[e >> 1] >> ((e & 1) * 16)));
+    }
+    static __device__ __forceinline__ float of_elem(uint16_t bits) { return widen(ET{}, bits); }
+};
+template <> struct Logit<F32> {
+    static constexpr int per_vec = 4;
+    typedef float elem_t;
+    static __device__ __forceinline__ float of_vec(const u32x4 w, int e) { return __uint_as_float(w[e]); }
+    static __device__ __forceinline__ float of_elem(float x) { return x; }
+};
+
 template <typename ET>
 __global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptParams p) {
+    typedef Logit<ET> LT;
+    constexpr int PV = LT::per_vec;
     const int row = blockIdx.y, sl = blockIdx.x;
     const int tid = threadIdx.x;
     const int c0 = sl * p.slice_len;
     const int c1 = min(p.V, c0 + p.slice_len);
-    const uint16_t* base = reinterpret_cast<const uint16_t*>(p.logits) + (int64_t)row * p.V;
+    const typename LT::elem_t* base = reinterpret_cast<const typename LT::elem_t*>(p.logits) + (int64_t)row * p.V;
     // -inf / "no index yet": a row slice that holds nothing above -inf resolves to its first
     // column below (all its elements are then equal), without a dependent load up front
     float best = -INFINITY;
     int32_t arg = 0x7fffffff;
-    if ((p.V & 7) == 0) {
+    if ((p.V % PV) == 0) {
         // 16-byte non-temporal loads (the logits are read once)
         const uint64_t rowaddr = (uint64_t)base;
         auto scan8 = [&](const u32x4 w, int v) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint16_t bits = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
-                const float y = widen(ET{}, bits);
+            for (int e = 0; e < PV; ++e) {
+                const float y = LT::of_vec(w, e);
                 if (y > best) {            // strict: the earlier index of this thread stays
                     best = y;
-                    arg = v * 8 + e;
+                    arg = v * PV + e;
                 }
             }
         };
-        const int v1 = c1 >> 3;
+        const int v1 = c1 / PV;            // (slices are multiples of 8 columns; V is a multiple of PV here)
         // four loads in flight per thread; a thread whose last group is short re-reads the
         // slice's last vector instead (scanning an element twice changes nothing)
-        for (int v = (c0 >> 3) + tid; v < v1; v += 4 * kArgmaxThreads) {
+        for (int v = c0 / PV + tid; v < v1; v += 4 * kArgmaxThreads) {
             int vv[4];
             u32x4 w[4];
 #pragma unroll
@@ -67,7 +86,7 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptPa
         }
     } else {
         for (int c = c0 + tid; c < c1; c += kArgmaxThreads) {
-            const float y = widen(ET{}, base[c]);
+            const float y = LT::of_elem(base[c]);
             if (y > best) {
                 best = y;
                 arg = c;
@@ -239,8 +258,10 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParam
 hipError_t launch_greedy_accept(const AcceptParams& p, hipStream_t stream) {
     if (p.logits != nullptr && p.T > 0) {
         dim3 grid(p.slices, p.T);
-        if (p.bf16)
+        if (p.logits_dtype == 1)
             hipLaunchKernelGGL(argmax_partial_kernel<BF16>, grid, dim3(kArgmaxThreads), 0, stream, p);
+        else if (p.logits_dtype == 2)
+            hipLaunchKernelGGL(argmax_partial_kernel<F32>, grid, dim3(kArgmaxThreads), 0, stream, p);
         else
             hipLaunchKernelGGL(argmax_partial_kernel<F16>, grid, dim3(kArgmaxThreads), 0, stream, p);
         hipError_t e = hipGetLastError();

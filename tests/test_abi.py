@@ -97,7 +97,7 @@ def accept(**over):
     (dict(B=9000), ems.EMS_ERR_UNSUPPORTED),
     (dict(T=70000), ems.EMS_ERR_UNSUPPORTED),
     (dict(logits=FAKE, V=0), ems.EMS_ERR_INVALID_ARG),
-    (dict(logits=FAKE, V=50272, dtype=ems.EMS_F32), ems.EMS_ERR_INVALID_ARG),
+    (dict(logits=FAKE, V=50272, dtype=7), ems.EMS_ERR_INVALID_ARG),
     (dict(logits=FAKE + 4, V=50272), ems.EMS_ERR_INVALID_ARG),
     (dict(logits=FAKE, V=50272, ws=None), ems.EMS_ERR_WORKSPACE),
     (dict(logits=FAKE, V=50272, ws=FAKE, ws_bytes=8), ems.EMS_ERR_WORKSPACE),

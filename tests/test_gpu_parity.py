@@ -381,3 +381,29 @@ def test_paper_order_with_every_row_as_its_own_work_item():
     torch.cuda.synchronize()
     want = oracle_attention(b_cpu)
     assert np.abs(out.double().cpu().numpy() - want).max() <= 2e-3
+
+
+@pytest.mark.parametrize("V", [50272, 4099, 6])
+def test_accept_from_fp32_logits(V):
+    """fp32 logits (EMS_F32): arg-max by 16-byte loads of four floats, or element by element when V
+    is not a multiple of four; natural ties, an all -inf row, +-0."""
+    import paper_2405_07542_amd as ems
+    b_cpu = make_batch([3, 4, 5], [6, 1, 9], H=1, D=64, dtype=torch.float16, seed=93, vocab_for_ids=V)
+    rng = np.random.default_rng(94 + V)
+    lg = np.round(rng.standard_normal((b_cpu.T, V)).astype(np.float32) * 4) / 4     # coarse grid: many ties
+    lg[2, :] = -np.inf
+    lg[3, :] = -0.0
+    lg[3, V - 1] = 0.0
+    want = oracle.argmax_f32(lg)
+    assert np.array_equal(want, np.argmax(lg, axis=1))
+    b = to_device(b_cpu)
+    logits = torch.from_numpy(lg).cuda()
+    target = torch.full((b.T,), -7, dtype=torch.int32, device="cuda")
+    accepted = torch.empty(b.B, dtype=torch.int32, device="cuda")
+    accepted_cu = torch.empty(b.B + 1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(ems.ems_accept_workspace_bytes(b.T, V), dtype=torch.uint8, device="cuda")
+    ems.ems_greedy_accept(logits, target, b.input_ids, b.cu_seqlens, accepted, accepted_cu, None, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(target.cpu().numpy(), want)
+    o_acc, o_cu, _ = oracle.greedy_accept(want, b_cpu.input_ids.numpy(), b_cpu.cu_seqlens.numpy())
+    assert np.array_equal(accepted.cpu().numpy(), o_acc) and np.array_equal(accepted_cu.cpu().numpy(), o_cu)

@@ -302,3 +302,15 @@ def test_concatenation_of_input_tokens_alg_1():
         for r in range(total):
             i, pos = oracle.restore_index(nums, r)
             assert cat[r] == padded[i, pos]
+
+
+def test_argmax_of_fp32_logits():
+    rng = np.random.default_rng(92)
+    lg = rng.standard_normal((40, 1003)).astype(np.float32)
+    lg[3, 17] = lg[3, 900] = 9.0                 # a tie: the lower index wins
+    lg[5, :] = -np.inf
+    lg[6, 0] = 0.0; lg[6, 1:] = -0.0             # +0 and -0 are equal: index 0
+    lg[7, 1002] = 50.0                           # last column
+    want = np.argmax(lg, axis=1)                 # numpy returns the first maximum
+    got = oracle.argmax_f32(lg)
+    assert np.array_equal(got, want) and got[3] == 17 and got[5] == 0 and got[6] == 0 and got[7] == 1002

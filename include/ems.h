@@ -170,9 +170,10 @@ EMS_API size_t ems_accept_workspace_bytes(int T, int V);
  * distribution; acceptance length = 1 + number of leading drafts that equal the
  * target's token for the row before them; Sec. 3.1: between 1 and k+1 tokens).
  *
- *   logits      device [T,V] of `dtype` (EMS_F16, EMS_BF16 or EMS_F32), or NULL.  When given, target_ids[r] is
- *               WRITTEN with the lowest index attaining the row maximum (+0 and -0
- *               are equal; inputs must not hold NaN).  When NULL, target_ids is READ.
+ *   logits      device [T,V] of `dtype` (EMS_F16, EMS_BF16 or EMS_F32), or NULL.  When
+ *               given, target_ids[r] is WRITTEN with the lowest index attaining the row
+ *               maximum (+0 and -0 are equal; inputs must not hold NaN).  When NULL,
+ *               target_ids is READ.
  *   input_ids   device int32 [T]: packed input tokens (row 0 of a sample = last
  *               emitted token, rows 1.. = drafts)
  *   accepted    device int32 [B] out: m_i + 1 where m_i = number of leading j in

@@ -149,7 +149,7 @@ def test_tiny_config_accept_and_append():
 
 
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
-@pytest.mark.parametrize("V", [50272, 32000, 4099, 7])
+@pytest.mark.parametrize("V", [50272, 32000, 4099, 7, 128256, 262144])
 def test_argmax_on_unplanted_logits_with_natural_ties(dtype, V):
     """Plain N(0,1) rows: at 16-bit precision the maximum is often attained twice."""
     g = torch.Generator().manual_seed(50 + V)
@@ -168,6 +168,23 @@ def test_argmax_on_unplanted_logits_with_natural_ties(dtype, V):
     assert np.array_equal(tgt.cpu().numpy(), x)
     assert np.array_equal(acc.cpu().numpy(), o_acc) and o_acc.max() > 1
     assert np.array_equal(acc_cu.cpu().numpy(), o_cu)
+    assert np.array_equal(toks.cpu().numpy()[:o_cu[-1]], o_toks)
+
+
+def test_accept_at_the_largest_row_count():
+    """T = 65535 packed rows (the most a call accepts) in 8192 samples, logits over a small
+    vocabulary, bf16."""
+    rng = np.random.default_rng(95)
+    B = 8192
+    k = np.full(B, 8, dtype=np.int64)
+    k[-1] = 65535 - 8 * (B - 1)                     # 7 rows: T = 65535 exactly
+    b_cpu = make_batch([1] * B, k.tolist(), H=1, D=64, dtype=torch.bfloat16, seed=96, V=24, match_p=0.8)
+    assert b_cpu.T == 65535
+    b = to_device(b_cpu)
+    tgt, acc, acc_cu, toks = hip_accept(b)
+    x, o_acc, o_cu, o_toks = oracle_accept(b_cpu)
+    assert np.array_equal(tgt.cpu().numpy(), x)
+    assert np.array_equal(acc.cpu().numpy(), o_acc) and np.array_equal(acc_cu.cpu().numpy(), o_cu)
     assert np.array_equal(toks.cpu().numpy()[:o_cu[-1]], o_toks)
 
 

@@ -63,9 +63,8 @@ typedef enum {
 typedef enum { EMS_F16 = 0, EMS_BF16 = 1, EMS_F32 = 2 /* attention outputs and logits only */ } ems_dtype;
 
 #define EMS_MAX_QUERY_ROWS 64   /* largest k_i (rows per sample per step) */
-#define EMS_ROWS_PER_GROUP 16   /* up to this many rows a sample's cache is streamed once per step; with
-                                   max_k above it the attention calls cut every sample's rows into row
-                                   groups of 16 and stream the cache once per group */
+#define EMS_ROWS_PER_GROUP 16   /* with max_k up to this, the attention calls use the 16-row kernel; above
+                                   it a wider one that streams a sample's cache once per 32 of its rows */
 #define EMS_MAX_LAYERS_PER_CALL 32
 
 /*
@@ -101,10 +100,11 @@ EMS_API size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max
  *
  *   q,k_new,v_new,out : device [T,H,D]       cu_seqlens : device int32 [B+1]
  *   kv_start, kv_len  : device int32 [B]     cache      : host struct, device arenas
- *   max_k      >= every k_i   (<= EMS_MAX_QUERY_ROWS).  It also selects the launch shape: up
- *                 to EMS_ROWS_PER_GROUP a sample's cache is streamed once per step; above
- *                 it the sample's rows are cut into row groups of 16 and the cache is
- *                 streamed once per group.  A sample with more rows than max_k breaks the
+ *   max_k      >= every k_i   (<= EMS_MAX_QUERY_ROWS).  It also selects the kernel: up to
+ *                 EMS_ROWS_PER_GROUP, one that holds 16 rows per (sample, head) and streams
+ *                 the sample's cache once per step; above it, one that holds 32 rows and
+ *                 streams the cache once for rows 0..31 and once more for rows 32..63 of a
+ *                 sample that has them.  A sample with more rows than max_k breaks the
  *                 contract (rows beyond 16, resp. 64, are left unwritten).
  *   max_kv_len >= every kv_len[i]            (host-known upper bounds)
  * Samples with k_i = 0 contribute nothing; kv_len[i] = 0 is legal; T = 0 is a no-op.

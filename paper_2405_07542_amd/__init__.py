@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libems.so")
 
 EMS_OK, EMS_ERR_INVALID_ARG, EMS_ERR_UNSUPPORTED, EMS_ERR_WORKSPACE, EMS_ERR_HIP = range(5)
 EMS_F16, EMS_BF16, EMS_F32 = 0, 1, 2
-EMS_MAX_QUERY_ROWS = 16
+EMS_MAX_QUERY_ROWS = 64
+EMS_ROWS_PER_GROUP = 16
 _DT = {torch.float16: EMS_F16, torch.bfloat16: EMS_BF16, torch.float32: EMS_F32}
 
 

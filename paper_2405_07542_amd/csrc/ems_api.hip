@@ -38,12 +38,11 @@ constexpr int kMinTilesPerWave = 4;
 constexpr int kMaxAttnBlocks = 1024;
 constexpr int kMaxB = 8192;
 
-// Upper bound of the number of 32-key tiles of the whole batch (host-known bounds only).
-// With more than 16 rows per sample a (sample, head) has up to four row groups, each with
-// the cache tiles and up to two tiles of new tokens.
-int64_t tile_upper_bound(int B, int H, int max_kv_len, bool row_groups) {
+// Upper bound of the number of 32-key tiles of the whole batch (host-known bounds only); a
+// sample of up to 64 rows is up to two pairs per head, each with up to two tiles of new tokens.
+int64_t tile_upper_bound(int B, int H, int max_kv_len, bool wide) {
     const int64_t cache_tiles = (max_kv_len + kTileKeys - 1) / kTileKeys;
-    return (int64_t)B * H * (row_groups ? 4 * (cache_tiles + 2) : cache_tiles + 1);
+    return (int64_t)B * H * (wide ? 2 * (cache_tiles + 2) : cache_tiles + 1);
 }
 
 int attn_blocks_for(int64_t tiles, int max_blocks) {
@@ -54,9 +53,10 @@ int attn_blocks_for(int64_t tiles, int max_blocks) {
 // Workspace = header (the B+1 tile prefix sums, padded to 256 B) + partial slots.
 size_t attn_ws_header_bytes(int B) { return ((size_t)(B + 1) * sizeof(int32_t) + 255) / 256 * 256; }
 
-size_t attn_ws_bytes_for(int blocks, int B, int D) {
+// Two partial slots per wave, of 16 rows each, or of 32 in the wide kernel (max_k > 16).
+size_t attn_ws_bytes_for(int blocks, int B, int D, bool wide) {
     return attn_ws_header_bytes(B) +
-           (size_t)2 * blocks * kWavesPerBlock * 16 * (D + ems::kPartialPad) * sizeof(float);
+           (size_t)2 * blocks * kWavesPerBlock * (wide ? 32 : 16) * (D + ems::kPartialPad) * sizeof(float);
 }
 
 // Workgroups launched for the attention kernel: one per CU, i.e. one wave per SIMD.  Two
@@ -111,7 +111,7 @@ size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len)
     if (B < 1 || H < 1 || D < 1 || max_kv_len < 0) return 256;
     // (sized for the larger of the two launch shapes: max_k is not known here)
     const int blocks = attn_blocks_for(tile_upper_bound(B, H, max_kv_len, true), kMaxAttnBlocks);
-    return std::max<size_t>(256, attn_ws_bytes_for(blocks, B, D));
+    return std::max<size_t>(256, attn_ws_bytes_for(blocks, B, D, true));
 }
 
 }  // extern "C"
@@ -154,9 +154,9 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
                     B, D, ems::valu_attention_lds_bytes(B, D), ems::kMaxLdsBytes);
     if (max_k > EMS_MAX_QUERY_ROWS)
         return fail(EMS_ERR_UNSUPPORTED, "max_k = %d, at most %d rows per sample", max_k, EMS_MAX_QUERY_ROWS);
-    const bool row_groups = max_k > EMS_ROWS_PER_GROUP;
-    if (row_groups && pad) return fail(EMS_ERR_UNSUPPORTED, "the padded ablation takes at most %d rows per sample", EMS_ROWS_PER_GROUP);
-    if (row_groups && g_attn_variant.load() == EMS_ATTN_VALU)
+    const bool wide = max_k > EMS_ROWS_PER_GROUP;      // the wide kernel
+    if (wide && pad) return fail(EMS_ERR_UNSUPPORTED, "the padded ablation takes at most %d rows per sample", EMS_ROWS_PER_GROUP);
+    if (wide && g_attn_variant.load() == EMS_ATTN_VALU)
         return fail(EMS_ERR_UNSUPPORTED, "EMS_ATTN_VALU takes at most %d rows per sample", EMS_ROWS_PER_GROUP);
     if (B > kMaxB) return fail(EMS_ERR_UNSUPPORTED, "B = %d, at most %d samples", B, kMaxB);
     if (T == 0) return EMS_OK;
@@ -172,11 +172,11 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     // a sample's cache is addressed with 32-bit byte offsets from its first row
     if (((int64_t)max_kv_len + kTileKeys) * cache->row_stride * 2 >= ((int64_t)1 << 32))
         return fail(EMS_ERR_UNSUPPORTED, "max_kv_len * row_stride exceeds 4 GiB per sample");
-    const int64_t tiles = tile_upper_bound(B, H, max_kv_len, row_groups);
+    const int64_t tiles = tile_upper_bound(B, H, max_kv_len, wide);
     if (tiles >= ((int64_t)1 << 31)) return fail(EMS_ERR_UNSUPPORTED, "too many key tiles");
 
     const int blocks = attn_blocks_for(tiles, resident_attn_blocks());
-    const size_t need = attn_ws_bytes_for(blocks, B, D);
+    const size_t need = attn_ws_bytes_for(blocks, B, D, wide);
     if (!workspace || workspace_bytes < need)
         return fail(EMS_ERR_WORKSPACE, "attention workspace of %zu bytes needed, %zu given", need,
                     workspace ? workspace_bytes : (size_t)0);
@@ -204,7 +204,7 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     p.num_waves = blocks * kWavesPerBlock;
     p.scale_log2 = scale * 1.4426950408889634f;
     p.write_through = write_through ? 1 : 0;
-    p.multi = row_groups ? 1 : 0;
+    p.multi = wide ? 1 : 0;
     if (pad) {
         p.key_mask = pad->key_mask;
         p.k_valid = pad->k_valid;

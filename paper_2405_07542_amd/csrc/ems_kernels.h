@@ -25,13 +25,13 @@ struct AttnParams {
                                // the same sample (-1 for row 0) and sees, among the new rows, itself and its ancestors
     void* out;
     int32_t* ws_header;        // workspace header: the B+1 tile prefix sums, for the merge kernel
-    float* ws;                 // 2 * num_waves partial slots of 16 x (D + kPartialPad) floats
+    float* ws;                 // 2 * num_waves partial slots of 16 (wide kernel: 32) x (D + kPartialPad) floats
     int out_f32;
     int B, H;
     int num_waves;
     float scale_log2;          // scale * log2(e)
     int write_through;         // also store the new rows' K/V at cache rows kv_len + j (paper order)
-    int multi;                 // samples may bring more than 16 rows (up to 64): row groups of 16 per (sample, head)
+    int multi;                 // samples may bring more than 16 rows (up to 64): the wide kernel
     // padded ("vanilla") ablation only: every sample has k_max rows and an aligned cache of
     // l_pad rows at row i*cap, with a byte mask [B, cap] of real (1) and padding (0) keys
     const uint8_t* key_mask;
@@ -50,6 +50,11 @@ size_t valu_attention_lds_bytes(int B, int D);
 hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16, bool padded,
                                    bool valu, hipStream_t stream, hipEvent_t ev_start,
                                    hipEvent_t ev_stop);
+
+// The same for samples of up to 64 rows (p.multi): pairs of up to 32 rows (two blocks of 16 per wave),
+// partial slots of 32 rows.
+hipError_t launch_verify_attention_wide(const AttnParams& p, int blocks, int D, bool bf16,
+                                        hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 struct ArgmaxPartial {
     float value;

@@ -26,216 +26,9 @@
 //     the partials of such pairs by log-sum-exp.
 #include <atomic>
 
-#include "ems_device.h"
-#include "ems_kernels.h"
+#include "attention_tiles.h"
 
 namespace ems {
-
-constexpr int kTileKeys = 32;
-constexpr int kMaxRows = 16;             // query rows per pair: one MFMA column block
-constexpr int kMaxRowsMulti = 64;        // rows per sample when a sample's rows form several row groups
-constexpr int kAttnThreads = 256;
-constexpr int kWavesPerBlock = kAttnThreads / kWave;
-
-__device__ __forceinline__ int tiles_of_sample(int k, int L) {
-    return k > 0 ? ((L + kTileKeys - 1) / kTileKeys + 1) : 0;
-}
-
-// More than 16 rows per sample (MULTI kernels, up to 64): the rows are cut into row groups of
-// 16; a pair is then (sample, head, row group), every pair streams the whole cache (the cache
-// is read once per GROUP of 16 rows instead of once per sample) and ceil(k/32) tiles of new
-// tokens, since any earlier new row may be visible to a later one.
-__device__ __forceinline__ int row_groups(int k) { return (k + kMaxRows - 1) / kMaxRows; }
-__device__ __forceinline__ int new_tiles(int k) { return (k + kTileKeys - 1) / kTileKeys; }
-__device__ __forceinline__ int tiles_of_sample_multi(int k, int L) {
-    k = min(k, kMaxRowsMulti);
-    return k > 0 ? row_groups(k) * ((L + kTileKeys - 1) / kTileKeys + new_tiles(k)) : 0;
-}
-
-// prefix[i] = H * sum_{j<i} tiles(j), i = 0..B, built by the whole block in LDS.
-template <bool PADDED, bool MULTI>
-__device__ __forceinline__ void build_tile_prefix(const AttnParams& p, int32_t* prefix) {
-    const int tid = threadIdx.x;
-    for (int i = tid; i < p.B; i += blockDim.x)
-        prefix[i + 1] = PADDED  ? p.H * tiles_of_sample(p.k_max, p.l_pad)
-                        : MULTI ? p.H * tiles_of_sample_multi(p.cu[i + 1] - p.cu[i], p.kv_len[i])
-                                : p.H * tiles_of_sample(p.cu[i + 1] - p.cu[i], p.kv_len[i]);
-    if (tid == 0) prefix[0] = 0;
-    __syncthreads();
-    if (tid < kWave) {                        // one wave: inclusive scan, 64 entries a pass
-        int carry = 0;
-        for (int base = 1; base <= p.B; base += kWave) {
-            const int idx = base + tid;
-            int v = idx <= p.B ? prefix[idx] : 0;
-#pragma unroll
-            for (int off = 1; off < kWave; off <<= 1) {
-                int u = __shfl_up(v, off);
-                if (tid >= off) v += u;
-            }
-            if (idx <= p.B) prefix[idx] = v + carry;
-            carry += __shfl(v, kWave - 1);
-        }
-    }
-    __syncthreads();
-}
-
-// Head dims: 64 and 128 fill every lane; 80 (a row of 160 bytes) is run as a 96-wide
-// score product whose last k-step is half empty (the lane quarters g >= 2 re-read the
-// pieces of g - 2 and meet zeros in Q) and a V / output layout of 8 elements per lane in
-// which only 10 of the 16 lanes of a row hold data (the others re-read lane 9's piece and
-// their results are never stored).
-template <int D>
-struct TileRegs {
-    static_assert(D == 64 || D == 80 || D == 128, "head dims 64, 80 and 128");
-    static constexpr int KS = (D + 31) / 32;          // MFMA k-steps over the head dim
-    static constexpr int VW = D == 64 ? 4 : 8;        // head-dim elements per lane per V row
-    static constexpr int kVLanes = D / VW;            // lanes of a 16-lane row that hold V / output data
-    static constexpr int kTailQ = (D % 32) / 8;       // valid lane quarters of the last k-step; 0 = all four
-    // byte offset of lane quarter g's 16-byte piece of k-step s inside a K or Q row
-    static __device__ __forceinline__ uint32_t piece(int s, int g) {
-        return (uint32_t)(64 * s + 16 * ((kTailQ != 0 && s == KS - 1) ? g % (kTailQ != 0 ? kTailQ : 1) : g));
-    }
-    static __device__ __forceinline__ bool piece_valid(int s, int g) {
-        return !(kTailQ != 0 && s == KS - 1 && g >= kTailQ);
-    }
-    typedef uint32_t vrow_t __attribute__((ext_vector_type(VW / 2)));
-    u32x4 ka[KS], kb[KS];                    // keys 0..15 / 16..31 of the tile, A-operand layout
-    vrow_t v[8];                             // this lane's 8 keys x VW head-dim elements
-    uint32_t mka, mkb;                       // padded ablation only: key-mask bytes of this lane's keys
-};
-
-// Where the 32 keys of one tile live: a run of rows of `row_bytes` starting at kbase/vbase
-// (already offset to the head), first key n0, last valid row `last` (rows are clamped to
-// it so that masked keys still read valid, finite data).
-struct TileSrc {
-    uint64_t kbase, vbase;   // wave-uniform
-    uint32_t row_bytes;
-    int n0, last;
-    uint64_t mask_base;      // padded ablation only: key-mask row of the sample, 0 = no mask bytes
-};
-
-template <int D, bool PADDED>
-__device__ __forceinline__ void load_tile(TileRegs<D>& t, const TileSrc& src, int n, int g) {
-    constexpr int KS = TileRegs<D>::KS;
-    constexpr int VW = TileRegs<D>::VW;
-    const uint32_t ra = (uint32_t)min(src.n0 + n, src.last) * src.row_bytes;
-    const uint32_t rb = (uint32_t)min(src.n0 + 16 + n, src.last) * src.row_bytes;
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        t.ka[s] = gload_stream<u32x4>(src.kbase, ra + TileRegs<D>::piece(s, g));
-        t.kb[s] = gload_stream<u32x4>(src.kbase, rb + TileRegs<D>::piece(s, g));
-    }
-    const uint32_t vcol = (uint32_t)min(n, TileRegs<D>::kVLanes - 1) * (VW * 2);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int key = src.n0 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
-        const uint32_t off = (uint32_t)min(key, src.last) * src.row_bytes + vcol;
-        t.v[e] = gload_stream<typename TileRegs<D>::vrow_t>(src.vbase, off);
-    }
-    if (PADDED) {
-        t.mka = t.mkb = 0x01010101u;
-        if (src.mask_base != 0) {            // wave-uniform
-            t.mka = gload<uint32_t>(src.mask_base, (uint32_t)(src.n0 + 4 * g));
-            t.mkb = gload<uint32_t>(src.mask_base, (uint32_t)(src.n0 + 16 + 4 * g));
-        }
-    }
-}
-
-template <typename ET> struct PSplit { static constexpr bool value = false; };
-template <> struct PSplit<BF16> { static constexpr bool value = true; };
-
-template <typename ET, int D>
-struct SoftmaxState {
-    static constexpr int VW = TileRegs<D>::VW;
-    f32x4 acc[VW];     // acc[c][i] = O[query n][d = (4g+i)*VW + c], unnormalised (rows 4g+i < kVLanes)
-    float m;           // running max (log2 domain), same in the 4 lanes of a query
-    float l;           // this lane's share of the running sum
-};
-
-// One tile: scores, masked online softmax, PV.  `lim` = number of visible keys
-// of this tile for this lane's query row (>= 32 means no masking); with BITS it is
-// instead a bit set over the tile's 32 keys (bit n = key n visible), the form a tile of
-// new tokens uses: a causal prefix, or a row's ancestors in a token tree.  MAY_BE_EMPTY: a
-// row may see no key of the tile at all (padding; an early row group and a late tile).
-template <typename ET, int D, bool MASKED, bool PADDED = false, bool BITS = false, bool MAY_BE_EMPTY = PADDED>
-__device__ __forceinline__ void compute_tile(const TileRegs<D>& t, const u32x4* qb,
-                                             SoftmaxState<ET, D>& st, float scale_log2, int lim,
-                                             int g) {
-    constexpr int KS = TileRegs<D>::KS;
-    constexpr int VW = TileRegs<D>::VW;
-    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        sa = mfma16x16x32(ET{}, t.ka[s], qb[s], sa);
-        sb = mfma16x16x32(ET{}, t.kb[s], qb[s], sb);
-    }
-    float x[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        x[i] = sa[i] * scale_log2;
-        x[4 + i] = sb[i] * scale_log2;
-        if (MASKED && BITS) {
-            if (((lim >> (4 * g + i)) & 1) == 0) x[i] = -INFINITY;
-            if (((lim >> (16 + 4 * g + i)) & 1) == 0) x[4 + i] = -INFINITY;
-        } else if (MASKED) {
-            if (4 * g + i >= lim) x[i] = -INFINITY;
-            if (16 + 4 * g + i >= lim) x[4 + i] = -INFINITY;
-        }
-        if (PADDED) {                        // padding keys of the aligned cache
-            if (((t.mka >> (8 * i)) & 0xffu) == 0) x[i] = -INFINITY;
-            if (((t.mkb >> (8 * i)) & 0xffu) == 0) x[4 + i] = -INFINITY;
-        }
-    }
-    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                     fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    const float m_new = fmaxf(st.m, quad_max(mx));
-    // Every tile holds at least one visible key for every row, so m_new is finite -- unless
-    // MAY_BE_EMPTY: then subtract 0 instead of -inf.
-    const float m_sub = (MAY_BE_EMPTY && m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = fast_exp2(st.m - m_sub);     // exp2(-inf) = 0 on the first tile
-    float psum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        x[i] = fast_exp2(x[i] - m_sub);
-        psum += x[i];
-    }
-    st.l = st.l * alpha + psum;
-    st.m = m_new;
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-        for (int c = 0; c < VW; ++c) st.acc[c] *= alpha;
-    }
-    // P^T as the B operand: slot e of this lane = key (e<4 ? 4g+e : 16+4g+e-4).
-    // bf16 keeps 8 significant bits, too few for P when a row has only a handful of
-    // keys; there P is fed as hi + lo (two products), which restores ~16 bits.
-    constexpr bool kSplitP = PSplit<ET>::value;
-    u32x4 pb, pl;
-    pb[0] = pack2(ET{}, x[0], x[1]);
-    pb[1] = pack2(ET{}, x[2], x[3]);
-    pb[2] = pack2(ET{}, x[4], x[5]);
-    pb[3] = pack2(ET{}, x[6], x[7]);
-    if (kSplitP) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) x[i] -= round16(ET{}, x[i]);
-        pl[0] = pack2(ET{}, x[0], x[1]);
-        pl[1] = pack2(ET{}, x[2], x[3]);
-        pl[2] = pack2(ET{}, x[4], x[5]);
-        pl[3] = pack2(ET{}, x[6], x[7]);
-    }
-    // V^T as the A operand: for head-dim element c of this lane, the 8 keys' values.
-#pragma unroll
-    for (int c = 0; c < VW; ++c) {
-        u32x4 va;
-#pragma unroll
-        for (int pr = 0; pr < 4; ++pr) {
-            const uint32_t w0 = t.v[2 * pr][c >> 1];
-            const uint32_t w1 = t.v[2 * pr + 1][c >> 1];
-            va[pr] = (c & 1) ? pair_hi(w0, w1) : pair_lo(w0, w1);
-        }
-        st.acc[c] = mfma16x16x32(ET{}, va, pb, st.acc[c]);
-        if (kSplitP) st.acc[c] = mfma16x16x32(ET{}, va, pl, st.acc[c]);
-    }
-}
 
 // ---------------------------------------------------------------------------------------
 // The same tile on the vector ALU instead of the matrix cores (selected at run time; kept
@@ -394,108 +187,37 @@ __device__ __forceinline__ void valu_tile(const TileRegs<D>& t, char* lds, ValuS
     }
 }
 
-// Token trees: the new rows a row sees are itself and its ancestors.  Lane n of every
-// 16-lane row holds parent[n] of the pair's sample; four rounds of pointer doubling
-// (each row adopts the set of the row it currently points to, then points where that
-// row pointed) cover any depth up to 16.  Anything that is not a valid parent (not in
-// [0, n), or n >= k) counts as "no parent", so the exchanges stay inside the sample.
-__device__ __forceinline__ int tree_visibility(int parent_n, int n, int k) {
-    int jump = (n < k && parent_n >= 0 && parent_n < n) ? parent_n : -1;
-    int seen = 1 << n;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int src = jump >= 0 ? jump : n;
-        const int seen_src = __shfl(seen, src, 16);
-        const int jump_src = __shfl(jump, src, 16);
-        if (jump >= 0) {
-            seen |= seen_src;
-            jump = jump_src;
-        }
-    }
-    return seen;
-}
-
-// The same for up to 64 rows: lane j holds parent[j] of row j, six rounds cover any depth,
-// and the sets take two words.  Returns the set of row `want` (a lane-dependent row index).
-__device__ __forceinline__ uint64_t tree_visibility64(int parent_j, int lane, int k, int want) {
-    int jump = (lane < k && parent_j >= 0 && parent_j < lane) ? parent_j : -1;
-    uint32_t lo = lane < 32 ? 1u << lane : 0u, hi = lane >= 32 ? 1u << (lane - 32) : 0u;
-#pragma unroll
-    for (int t = 0; t < 6; ++t) {
-        const int src = jump >= 0 ? jump : lane;
-        const uint32_t lo_src = __shfl(lo, src), hi_src = __shfl(hi, src);
-        const int jump_src = __shfl(jump, src);
-        if (jump >= 0) {
-            lo |= lo_src;
-            hi |= hi_src;
-            jump = jump_src;
-        }
-    }
-    const uint32_t wl = __shfl(lo, want), wh = __shfl(hi, want);
-    return ((uint64_t)wh << 32) | wl;
-}
-
-// One (sample, head) pair's share of a wave's tile range; everything is wave-uniform and
 // kept small, so that two of them live in scalar registers.
-struct SegmentBase {
+struct Segment {
     int i, h;            // sample, head
-    int cu_i, k, k_real; // first packed row of the sample; rows of this pair (<= 16); real rows
-                         // (k_real < k only in the padded ablation)
-    int L;               // cached keys; ceil(L/32) cache tiles, then the tiles of new tokens
+    int cu_i, k, k_real; // first packed row, rows, real rows (k_real < k only in the padded ablation)
+    int L;               // cached keys; ceil(L/32) cache tiles, then the new-token tile
     int t0, t1;          // this wave consumes tiles [t0, t1) of the pair
     int64_t cache_off;   // byte offset of (first cache row of the sample, head h) in the arenas
     int64_t new_off;     // byte offset of (first packed row of the sample, head h) in q / k_new / v_new
     int64_t mask_off;    // padded ablation: offset of the sample's key-mask row
     __device__ __forceinline__ int ntc() const { return (L + kTileKeys - 1) / kTileKeys; }
-};
-// At most 16 rows per sample: the pair is the whole (sample, head), one tile of new tokens.
-template <bool MULTI>
-struct SegmentT : SegmentBase {
-    __device__ __forceinline__ int ktot() const { return k; }       // all new rows of the sample
-    __device__ __forceinline__ int rg() const { return 0; }         // row group of this pair
-    __device__ __forceinline__ int nnt() const { return 1; }        // tiles of new tokens
     __device__ __forceinline__ int nt() const { return ntc() + 1; }
-    __device__ __forceinline__ void set_group(int, int) {}
-};
-// Up to 64 rows per sample: the pair is (sample, head, row group); its rows are
-// 16*rg .. 16*rg + k - 1 and it reads ceil(ktot/32) tiles of new tokens.
-template <>
-struct SegmentT<true> : SegmentBase {
-    int ktot_, rg_;
-    __device__ __forceinline__ int ktot() const { return ktot_; }
-    __device__ __forceinline__ int rg() const { return rg_; }
-    __device__ __forceinline__ int nnt() const { return new_tiles(ktot_); }
-    __device__ __forceinline__ int nt() const { return ntc() + nnt(); }
-    __device__ __forceinline__ void set_group(int ktot, int rg) {
-        ktot_ = ktot;
-        rg_ = rg;
-        k = k_real = min(kMaxRows, ktot - kMaxRows * rg);
-    }
 };
 
 // The segment that starts at flat tile index gpos (< gend); `i` is a sample at or before it.
-template <int D, bool PADDED, bool MULTI>
-__device__ __forceinline__ SegmentT<MULTI> make_segment(const AttnParams& p, const int32_t* prefix, int i,
-                                                        int gpos, int gend) {
-    SegmentT<MULTI> s;
+template <int D, bool PADDED>
+__device__ __forceinline__ Segment make_segment(const AttnParams& p, const int32_t* prefix, int i,
+                                                int gpos, int gend) {
+    Segment s;
     while (uniform(prefix[i + 1]) <= gpos) ++i;
     s.i = i;
     // padded ablation: k_max rows and l_pad aligned cache rows for every sample
     s.cu_i = PADDED ? i * p.k_max : uniform(p.cu[i]);
-    // (never more rows than the kernel holds, whatever cu_seqlens claims)
-    const int ktot = min(MULTI ? kMaxRowsMulti : kMaxRows, PADDED ? p.k_max : uniform(p.cu[i + 1]) - s.cu_i);
-    s.k = ktot;
+    // (never more than the 16 rows one MFMA tile holds, whatever cu_seqlens claims)
+    s.k = min(kMaxRows, PADDED ? p.k_max : uniform(p.cu[i + 1]) - s.cu_i);
     s.L = PADDED ? p.l_pad : uniform(p.kv_len[i]);
     const int64_t start = PADDED ? (int64_t)i * p.cap : (int64_t)uniform(p.kv_start[i]);
     s.k_real = PADDED ? uniform(p.k_valid[i]) : s.k;
-    s.set_group(ktot, 0);                          // (for nt(); the group is set below)
     const int nt = s.nt();
     const int rem = gpos - uniform(prefix[i]);
-    const int pair = uniform(rem / nt);            // pair of this sample: head-major, then row group
-    const int groups = MULTI ? row_groups(ktot) : 1;
-    s.h = MULTI ? uniform(pair / groups) : pair;
-    s.set_group(ktot, MULTI ? pair - s.h * groups : 0);
-    s.t0 = rem - pair * nt;
+    s.h = uniform(rem / nt);
+    s.t0 = rem - s.h * nt;
     s.t1 = min(nt, s.t0 + (gend - gpos));
     s.cache_off = start * p.row_stride_b + (int64_t)s.h * p.head_stride_b;
     s.new_off = ((int64_t)s.cu_i * p.H + s.h) * (D * 2);
@@ -506,20 +228,12 @@ __device__ __forceinline__ SegmentT<MULTI> make_segment(const AttnParams& p, con
 // The segment after `c` in the wave's range; it starts at flat tile gpos (< gend), the first
 // tile of the next pair.  The next head of the same sample needs no memory access at all;
 // only a change of sample reads the index arrays again.
-template <int D, bool PADDED, bool MULTI>
-__device__ __forceinline__ SegmentT<MULTI> next_segment(const AttnParams& p, const int32_t* prefix,
-                                                        const SegmentT<MULTI>& c, int gpos, int gend) {
-    if (MULTI && c.rg() + 1 < row_groups(c.ktot())) {      // next row group of the same head
-        SegmentT<MULTI> s = c;
-        s.set_group(c.ktot(), c.rg() + 1);
-        s.t0 = 0;
-        s.t1 = min(c.nt(), gend - gpos);
-        return s;
-    }
-    if (c.h + 1 >= p.H) return make_segment<D, PADDED, MULTI>(p, prefix, c.i + 1, gpos, gend);
-    SegmentT<MULTI> s = c;
+template <int D, bool PADDED>
+__device__ __forceinline__ Segment next_segment(const AttnParams& p, const int32_t* prefix,
+                                                const Segment& c, int gpos, int gend) {
+    if (c.h + 1 >= p.H) return make_segment<D, PADDED>(p, prefix, c.i + 1, gpos, gend);
+    Segment s = c;
     s.h = c.h + 1;
-    s.set_group(c.ktot(), 0);
     s.t0 = 0;
     s.t1 = min(c.nt(), gend - gpos);
     s.cache_off = c.cache_off + p.head_stride_b;
@@ -527,16 +241,15 @@ __device__ __forceinline__ SegmentT<MULTI> next_segment(const AttnParams& p, con
     return s;
 }
 
-template <typename ET, int D, bool PADDED, bool VALU = false, bool MULTI = false>
+template <typename ET, int D, bool PADDED, bool VALU = false>
 __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnParams p) {
     extern __shared__ int32_t prefix[];
     constexpr int KS = TileRegs<D>::KS;
     constexpr int VW = TileRegs<D>::VW;
     static_assert(!(VALU && PADDED), "the vector-ALU formulation exists for the unpadded layout only");
     static_assert(!(VALU && D == 80), "the vector-ALU formulation exists for head dims 64 and 128 only");
-    static_assert(!(MULTI && (VALU || PADDED)), "row groups exist for the unpadded matrix-core kernel only");
     typedef TileRegs<D> TR;
-    build_tile_prefix<PADDED, MULTI>(p, prefix);
+    build_tile_prefix<PADDED ? kPaddedLine : kPlainLine>(p, prefix);
     if (blockIdx.x == 0)       // the merge kernel reads the tile prefix from the workspace header
         for (int i = threadIdx.x; i <= p.B; i += blockDim.x) p.ws_header[i] = prefix[i];
     const int total = prefix[p.B];
@@ -563,18 +276,16 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     // `nxt` the one after it (its index arrays are fetched a whole segment ahead); the loads
     // of flat tile c+1 -- possibly the first tile of `nxt` -- are issued before tile c is
     // consumed, so the stream of loads does not drain at a pair boundary.
-    typedef SegmentT<MULTI> Segment;
-    Segment cur = make_segment<D, PADDED, MULTI>(p, prefix, uniform(lo), gbeg, gend);
+    Segment cur = make_segment<D, PADDED>(p, prefix, uniform(lo), gbeg, gend);
     int cur_end = gbeg + (cur.t1 - cur.t0);            // flat index one past cur's last tile
     Segment nxt = cur;
-    if (cur_end < gend) nxt = next_segment<D, PADDED, MULTI>(p, prefix, cur, cur_end, gend);
+    if (cur_end < gend) nxt = next_segment<D, PADDED>(p, prefix, cur, cur_end, gend);
 
     u32x4 qb[KS];                // Q^T of `cur` as the B operand of S^T = K Q^T
     u32x4 qn[KS];                // the same for `nxt`, fetched a whole segment ahead
     SoftmaxState<ET, D> st;
     int vis_new = 0;             // this lane's row: visible keys of the new-token tile, one bit per key
-    uint64_t vis_multi = 0;      // MULTI: the same over all (up to 64) new rows of the sample
-    int par_n = -1;              // token trees: parent of row n (MULTI: of row `lane`) of `nxt`, fetched with its Q
+    int par_n = -1;              // token trees: parent of row n of `nxt`, fetched with its Q
     // vector-ALU formulation: per-row state in registers, Q rows and P in wave-private LDS
     ValuState vs;
     char* const vlds = reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15) +
@@ -584,19 +295,15 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     // Q rows of a pair (k rows at qaddr), raw: rows beyond k repeat row k-1 and are zeroed
     // by use_q when the pair becomes current -- touching the values here would make the wave
     // wait for the load (and for every tile load issued before it) at once.
-    // byte offset of a pair's first query row: the head's first packed row, plus its row group
-    auto q_off = [&](const Segment& s) __attribute__((always_inline)) {
-        return s.new_off + (MULTI ? (int64_t)(kMaxRows * s.rg()) * new_row_bytes : (int64_t)0);
-    };
     auto load_q = [&](u32x4* dst, int64_t new_off, int k) __attribute__((always_inline)) {
         const uint64_t qaddr = uniform_addr(p.q + new_off);
         const uint32_t qoff = (uint32_t)min(n, k - 1) * new_row_bytes;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) dst[ks] = gload<u32x4>(qaddr, qoff + TR::piece(ks, g));
     };
-    auto load_parent = [&](int cu_i, int ktot) __attribute__((always_inline)) {
+    auto load_parent = [&](int cu_i, int k) __attribute__((always_inline)) {
         if (!PADDED && p.parent != nullptr)
-            par_n = gload<int32_t>(uniform_addr(p.parent + cu_i), (uint32_t)min(MULTI ? lane : n, ktot - 1) * 4u);
+            par_n = gload<int32_t>(uniform_addr(p.parent + cu_i), (uint32_t)min(n, k - 1) * 4u);
     };
     auto use_q = [&](const u32x4* src, int k) __attribute__((always_inline)) {
 #pragma unroll
@@ -626,12 +333,6 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
         // visible keys of the new-token tile for this lane's row: itself and the rows before
         // it (padded: rows and keys at or beyond k_real are padding; padding rows see the real keys);
         // in a token tree: itself and its ancestors
-        if (MULTI) {
-            const int row = min(kMaxRows * s.rg() + n, s.ktot() - 1);        // rows beyond the group: any valid row
-            vis_multi = row >= 63 ? ~0ull : (1ull << (row + 1)) - 1;
-            if (p.parent != nullptr) vis_multi = tree_visibility64(par_n, lane, s.ktot(), row);
-            return;
-        }
         vis_new = (1 << min(s.k_real, n + 1)) - 1;
         if (!PADDED && p.parent != nullptr) vis_new = tree_visibility(par_n, n, s.k);
     };
@@ -641,12 +342,11 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     auto issue = [&](TileRegs<D>& t, int tile, int L, int k, int64_t cache_off, int64_t new_off,
                      int64_t mask_off) __attribute__((always_inline)) {
         TileSrc src;
-        const int ntc = (L + kTileKeys - 1) / kTileKeys;
-        const bool is_new = tile >= ntc;                               // wave-uniform
+        const bool is_new = tile >= (L + kTileKeys - 1) / kTileKeys;   // wave-uniform
         src.kbase = uniform_addr(is_new ? p.k_new + new_off : p.k_cache + cache_off);
         src.vbase = uniform_addr(is_new ? p.v_new + new_off : p.v_cache + cache_off);
         src.row_bytes = is_new ? new_row_bytes : cache_row_bytes;
-        src.n0 = is_new ? (MULTI ? (tile - ntc) * kTileKeys : 0) : tile * kTileKeys;
+        src.n0 = is_new ? 0 : tile * kTileKeys;
         src.last = is_new ? k - 1 : L - 1;
         src.mask_base = (PADDED && !is_new) ? uniform_addr(p.key_mask + mask_off) : 0;
         load_tile<D, PADDED>(t, src, n, g);
@@ -667,37 +367,9 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
         } else {
             if (VALU)
                 valu_tile<ET, D, true, true>(t, vlds, vs, p.scale_log2, s.k, 0, lane, n, g);
-            else if (MULTI)     // new keys 32*tn .. 32*tn+31: this tile's 32 bits of the row's set
-                compute_tile<ET, D, true, false, true, true>(
-                    t, qb, st, p.scale_log2, (int)(uint32_t)(vis_multi >> (kTileKeys * (tile - s.ntc()))), g);
             else
                 compute_tile<ET, D, true, PADDED, true>(t, qb, st, p.scale_log2, vis_new, g);
-            if (MULTI && p.write_through && s.rg() == 0) {
-                // as below, for up to 64 new rows: this tile holds new rows 32*tn .. 32*tn+31; the
-                // pair of row group 0 stores them (every group reads them, one writes them)
-                const uint32_t row_b = cache_row_bytes;
-                const int key0 = kTileKeys * (tile - s.ntc());
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int key = key0 + 16 * half + n;
-                    if (key < s.ktot()) {
-                        char* kdst = const_cast<char*>(p.k_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + key) * row_b;
-#pragma unroll
-                        for (int ks = 0; ks < KS; ++ks)
-                            if (TR::piece_valid(ks, g))
-                                *reinterpret_cast<u32x4*>(kdst + TR::piece(ks, g)) = half ? t.kb[ks] : t.ka[ks];
-                    }
-                }
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int key = key0 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
-                    if (key < s.ktot() && n < TR::kVLanes) {
-                        char* vdst = const_cast<char*>(p.v_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + key) * row_b + n * (VW * 2);
-                        *reinterpret_cast<typename TileRegs<D>::vrow_t*>(vdst) = t.v[e];
-                    }
-                }
-            }
-            if (!MULTI && !PADDED && p.write_through) {
+            if (!PADDED && p.write_through) {
                 // Paper order (Sec. 3.2): the new rows' K/V go to the sample's own location,
                 // cache rows kv_len + j, j < k_i, straight from the registers of this tile.
                 // Exactly one wave holds the new-token tile of a (sample, head) pair.
@@ -778,7 +450,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
         if (s.t0 == 0 && s.t1 == s.nt()) {
             if (n < s.k) {
                 const float inv = 1.0f / l;
-                const int64_t row = ((int64_t)(s.cu_i + kMaxRows * s.rg() + n) * p.H + s.h) * D;
+                const int64_t row = ((int64_t)(s.cu_i + n) * p.H + s.h) * D;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     if (4 * g + r >= TR::kVLanes) continue;      // head dim 80: output rows 10..15 hold nothing
@@ -829,7 +501,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     auto step = [&](int c, const TileRegs<D>& use, TileRegs<D>& fill) __attribute__((always_inline)) {
         if (c + 1 < gend) {
             const bool same = con_t + 1 < cur.t1;        // else: first tile of the next pair
-            issue(fill, same ? con_t + 1 : nxt.t0, same ? cur.L : nxt.L, same ? cur.ktot() : nxt.ktot(),
+            issue(fill, same ? con_t + 1 : nxt.t0, same ? cur.L : nxt.L, same ? cur.k : nxt.k,
                   same ? cur.cache_off : nxt.cache_off, same ? cur.new_off : nxt.new_off,
                   same ? cur.mask_off : nxt.mask_off);
         }
@@ -844,24 +516,24 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 use_q(qn, cur.k);
                 begin_segment(cur);
                 if (cur_end < gend) {
-                    nxt = next_segment<D, PADDED, MULTI>(p, prefix, cur, cur_end, gend);
-                    load_q(qn, q_off(nxt), nxt.k);
-                    load_parent(nxt.cu_i, nxt.ktot());
+                    nxt = next_segment<D, PADDED>(p, prefix, cur, cur_end, gend);
+                    load_q(qn, nxt.new_off, nxt.k);
+                    load_parent(nxt.cu_i, nxt.k);
                 }
             }
         }
     };
 
     TileRegs<D> ta, tb;
-    load_q(qn, q_off(cur), cur.k);
-    load_parent(cur.cu_i, cur.ktot());
+    load_q(qn, cur.new_off, cur.k);
+    load_parent(cur.cu_i, cur.k);
     use_q(qn, cur.k);
     begin_segment(cur);
     if (cur_end < gend) {
-        load_q(qn, q_off(nxt), nxt.k);
-        load_parent(nxt.cu_i, nxt.ktot());
+        load_q(qn, nxt.new_off, nxt.k);
+        load_parent(nxt.cu_i, nxt.k);
     }
-    issue(ta, cur.t0, cur.L, cur.ktot(), cur.cache_off, cur.new_off, cur.mask_off);
+    issue(ta, cur.t0, cur.L, cur.k, cur.cache_off, cur.new_off, cur.mask_off);
     for (int c = gbeg; c < gend; c += 2) {
         step(c, ta, tb);
         if (c + 1 < gend) step(c + 1, tb, ta);
@@ -880,26 +552,23 @@ template <int D> struct Combine {
     static constexpr int threads = rows_per_pass * lanes_per_row;
 };
 
-template <typename ET, int D, bool PADDED, bool MULTI = false>
+template <typename ET, int D, bool PADDED>
 __global__ __launch_bounds__(Combine<D>::threads) void combine_partials_kernel(AttnParams p) {
     const int i = blockIdx.y, h = blockIdx.x;
     const int cu_i = PADDED ? i * p.k_max : p.cu[i];
-    const int ktot = min(MULTI ? kMaxRowsMulti : kMaxRows, PADDED ? p.k_max : p.cu[i + 1] - cu_i);
+    const int k = min(kMaxRows, PADDED ? p.k_max : p.cu[i + 1] - cu_i);
     const int total = p.ws_header[p.B];
     const int first = p.ws_header[i];
     const int next = p.ws_header[i + 1];
-    if (ktot <= 0) return;
+    if (k <= 0) return;
     const int per = (total + p.num_waves - 1) / p.num_waves;
-    const int groups = MULTI ? row_groups(ktot) : 1;
-    const int nt = (next - first) / (p.H * groups);
+    const int nt = (next - first) / p.H;
+    const int g0 = first + h * nt;
+    const int w0 = g0 / per, w1 = (g0 + nt - 1) / per;
+    if (w0 == w1) return;                  // one wave saw the whole pair and wrote `out` itself
     constexpr int pitch = D + kPartialPad;
     constexpr int lanes_per_row = Combine<D>::lanes_per_row;
     const int c4 = (threadIdx.x % lanes_per_row) * 4;
-    for (int rg = 0; rg < groups; ++rg) {              // the pairs (row groups) of this (sample, head)
-    const int g0 = first + (h * groups + rg) * nt;
-    const int w0 = g0 / per, w1 = (g0 + nt - 1) / per;
-    if (w0 == w1) continue;                // one wave saw the whole pair and wrote `out` itself
-    const int k = min(kMaxRows, ktot - kMaxRows * rg);
     for (int j = threadIdx.x / lanes_per_row; j < k; j += Combine<D>::rows_per_pass) {
         // slot of wave w for this pair: 2w+1 if the pair starts in w's range, 2w if it continues
         auto slot_row = [&](int w) -> const float* {
@@ -932,7 +601,7 @@ __global__ __launch_bounds__(Combine<D>::threads) void combine_partials_kernel(A
             fold(s0[D], s0[D + 1], *reinterpret_cast<const f32x4*>(s0 + c4));
         }
         const float inv = 1.0f / den;
-        const int64_t idx = ((int64_t)(cu_i + kMaxRows * rg + j) * p.H + h) * D + c4;
+        const int64_t idx = ((int64_t)(cu_i + j) * p.H + h) * D + c4;
         if (p.out_f32) {
             *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + idx) = num * inv;
         } else {
@@ -941,7 +610,6 @@ __global__ __launch_bounds__(Combine<D>::threads) void combine_partials_kernel(A
             pk[1] = pack2(ET{}, num[2] * inv, num[3] * inv);
             *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(p.out) + idx) = pk;
         }
-    }
     }
 }
 
@@ -970,27 +638,12 @@ static hipError_t launch_typed(const AttnParams& p, int blocks, bool valu, hipSt
             launched = true;
         }
     }
-    bool multi = false;
-    if constexpr (!PADDED) {
-        if (!launched && p.multi) {          // some sample may bring more than 16 rows: row groups
-            hipLaunchKernelGGL((verify_attention_kernel<ET, D, false, false, true>), dim3(blocks),
-                               dim3(kAttnThreads), lds, stream, p);
-            launched = multi = true;
-        }
-    }
     if (!launched)
         hipLaunchKernelGGL((verify_attention_kernel<ET, D, PADDED, false>), dim3(blocks),
                            dim3(kAttnThreads), lds, stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
-    if constexpr (!PADDED) {
-        if (multi) {
-            hipLaunchKernelGGL((combine_partials_kernel<ET, D, false, true>), dim3(p.H, p.B),
-                               dim3(Combine<D>::threads), 0, stream, p);
-            return hipGetLastError();
-        }
-    }
     hipLaunchKernelGGL((combine_partials_kernel<ET, D, PADDED>), dim3(p.H, p.B),
                        dim3(Combine<D>::threads), 0, stream, p);
     return hipGetLastError();
@@ -1017,6 +670,7 @@ size_t valu_attention_lds_bytes(int B, int D) {
 hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16, bool padded,
                                    bool valu, hipStream_t stream, hipEvent_t ev_start,
                                    hipEvent_t ev_stop) {
+    if (!padded && p.multi) return launch_verify_attention_wide(p, blocks, D, bf16, stream, ev_start, ev_stop);
     return padded ? launch_layout<true>(p, blocks, D, bf16, false, stream, ev_start, ev_stop)
                   : launch_layout<false>(p, blocks, D, bf16, valu, stream, ev_start, ev_stop);
 }

@@ -1,0 +1,516 @@
+// Packed multi-token attention for samples that bring MORE than 16 rows per step (up to 64:
+// token trees commonly have 32-64 nodes).  Same tile line, same loads, same two tile buffers,
+// same partial format as verify_attention.hip; what changes:
+//   * a wave keeps TWO blocks of 16 query rows of its pair in flight: two B operands (in
+//     wave-private LDS, in exactly the per-lane layout the MFMA wants, re-read for every tile)
+//     and two sets of accumulators.  Per tile, the scores and the online softmax run block
+//     after block (phase 1), leaving the P operands of both blocks in registers; then every
+//     V^T operand is built once and multiplied into the accumulators of both blocks (phase 2).
+//     So up to 32 rows share one stream of the cache.  (Four blocks -- all 64 rows on one
+//     stream -- were tried: the allocator runs out of the 256 non-accumulator registers and
+//     spills, and both ways out, one tile buffer instead of two or spilling, were slower than
+//     two streams of two blocks.)
+//   * a sample with more than 32 rows becomes two pairs per head, (sample, head, half), rows
+//     0..31 and 32..63, each streaming the cache once;
+//   * a sample's new tokens take ceil(k/32) tiles after the cache tiles; the visible set of
+//     a row among the new rows is a 64-bit set (a causal prefix, or the row's ancestors in
+//     a token tree), of which every new-token tile uses its 32 bits (the first half never
+//     sees a key of the second tile: that tile costs it one empty pass);
+//   * the Q rows of the next pair are loaded at the switch (no prefetch).
+#include <atomic>
+
+#include "attention_tiles.h"
+
+namespace ems {
+
+constexpr int kWideBlocks = 2;                             // blocks of 16 rows per pair
+constexpr int kWideRows = kWideBlocks * kMaxRows;          // 32 rows per pair
+
+// One (sample, head, half) pair's share of a wave's tile range (wave-uniform).
+struct WideSegment {
+    int i, h, half;      // sample, head, which 32 rows of the sample
+    int cu_i, ktot, k;   // first packed row of the sample; its rows (<= 64); rows of this pair (<= 32)
+    int L;               // cached keys; ceil(L/32) cache tiles, then ceil(ktot/32) tiles of new tokens
+    int t0, t1;          // this wave consumes tiles [t0, t1) of the pair
+    int64_t cache_off;   // byte offset of (first cache row of the sample, head h) in the arenas
+    int64_t new_off;     // byte offset of (first packed row of the sample, head h) in q / k_new / v_new
+    __device__ __forceinline__ int ntc() const { return (L + kTileKeys - 1) / kTileKeys; }
+    __device__ __forceinline__ int nt() const { return ntc() + new_tiles(ktot); }
+    __device__ __forceinline__ int blocks() const { return (k + kMaxRows - 1) / kMaxRows; }
+    __device__ __forceinline__ int row0() const { return kWideRows * half; }   // first row of the pair in the sample
+    __device__ __forceinline__ void set_half(int hf) {
+        half = hf;
+        k = min(kWideRows, ktot - kWideRows * hf);
+    }
+};
+
+template <int D>
+__device__ __forceinline__ WideSegment make_wide_segment(const AttnParams& p, const int32_t* prefix, int i,
+                                                         int gpos, int gend) {
+    WideSegment s;
+    while (uniform(prefix[i + 1]) <= gpos) ++i;
+    s.i = i;
+    s.cu_i = uniform(p.cu[i]);
+    s.ktot = min(kMaxRowsWide, uniform(p.cu[i + 1]) - s.cu_i);   // (never more than the kernel holds)
+    s.L = uniform(p.kv_len[i]);
+    const int64_t start = (int64_t)uniform(p.kv_start[i]);
+    const int nt = s.nt();
+    const int rem = gpos - uniform(prefix[i]);
+    const int pair = uniform(rem / nt);            // pair of this sample: head-major, then half
+    const int halves = wide_halves(s.ktot);
+    s.h = uniform(pair / halves);
+    s.set_half(pair - s.h * halves);
+    s.t0 = rem - pair * nt;
+    s.t1 = min(nt, s.t0 + (gend - gpos));
+    s.cache_off = start * p.row_stride_b + (int64_t)s.h * p.head_stride_b;
+    s.new_off = ((int64_t)s.cu_i * p.H + s.h) * (D * 2);
+    return s;
+}
+
+template <int D>
+__device__ __forceinline__ WideSegment next_wide_segment(const AttnParams& p, const int32_t* prefix,
+                                                         const WideSegment& c, int gpos, int gend) {
+    if (c.half + 1 < wide_halves(c.ktot)) {        // second half of the same (sample, head)
+        WideSegment s = c;
+        s.set_half(c.half + 1);
+        s.t0 = 0;
+        s.t1 = min(c.nt(), gend - gpos);
+        return s;
+    }
+    if (c.h + 1 >= p.H) return make_wide_segment<D>(p, prefix, c.i + 1, gpos, gend);
+    WideSegment s = c;
+    s.h = c.h + 1;
+    s.set_half(0);
+    s.t0 = 0;
+    s.t1 = min(c.nt(), gend - gpos);
+    s.cache_off = c.cache_off + p.head_stride_b;
+    s.new_off = c.new_off + D * 2;
+    return s;
+}
+
+// One tile against the (up to two) blocks of query rows of a pair.  Cache tile: `lim` visible keys (the same
+// for every row; MASKED when < 32).  Tile of new tokens (NEW): vis[b] = this lane's row of
+// block b sees key n of the tile iff bit n is set; a block may see nothing of the tile.
+// q_lds: this lane's slot of the wave's Q^T store; operand (block b, k-step s) is at q_lds[(b*KS + s)*64].
+template <typename ET, int D, bool MASKED, bool NEW>
+__device__ __forceinline__ void compute_tile_wide(const TileRegs<D>& t, const u32x4* q_lds,
+                                                  SoftmaxState<ET, D>* st, int nblocks, float scale_log2,
+                                                  int lim, const uint32_t* vis, int g) {
+    constexpr int KS = TileRegs<D>::KS;
+    constexpr int VW = TileRegs<D>::VW;
+    constexpr bool kSplitP = PSplit<ET>::value;
+    // P operands of the blocks; a block the pair does not have keeps zeros (phase 2 then adds
+    // nothing to its accumulators, and needs no branch)
+    u32x4 pb[kWideBlocks], pl[kWideBlocks];
+#pragma unroll
+    for (int b = 0; b < kWideBlocks; ++b) {
+        pb[b] = u32x4{0u, 0u, 0u, 0u};
+        pl[b] = u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int b = 0; b < kWideBlocks; ++b) {
+        if (b < nblocks) {                           // wave-uniform
+            f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const u32x4 qv = q_lds[(b * KS + s) * kWave];
+                sa = mfma16x16x32(ET{}, t.ka[s], qv, sa);
+                sb = mfma16x16x32(ET{}, t.kb[s], qv, sb);
+            }
+            float x[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[i] = sa[i] * scale_log2;
+                x[4 + i] = sb[i] * scale_log2;
+                if (NEW) {
+                    if (((vis[b] >> (4 * g + i)) & 1u) == 0) x[i] = -INFINITY;
+                    if (((vis[b] >> (16 + 4 * g + i)) & 1u) == 0) x[4 + i] = -INFINITY;
+                } else if (MASKED) {
+                    if (4 * g + i >= lim) x[i] = -INFINITY;
+                    if (16 + 4 * g + i >= lim) x[4 + i] = -INFINITY;
+                }
+            }
+            const float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                                   fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+            const float m_new = fmaxf(st[b].m, quad_max(mx));
+            const float m_sub = (NEW && m_new == -INFINITY) ? 0.f : m_new;   // nothing visible yet
+            const float alpha = fast_exp2(st[b].m - m_sub);
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                x[i] = fast_exp2(x[i] - m_sub);
+                psum += x[i];
+            }
+            st[b].l = st[b].l * alpha + psum;
+            st[b].m = m_new;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                for (int c = 0; c < VW; ++c) st[b].acc[c] *= alpha;
+            }
+            pb[b][0] = pack2(ET{}, x[0], x[1]);
+            pb[b][1] = pack2(ET{}, x[2], x[3]);
+            pb[b][2] = pack2(ET{}, x[4], x[5]);
+            pb[b][3] = pack2(ET{}, x[6], x[7]);
+            if (kSplitP) {                           // bf16: P as hi + lo, as in the 16-row kernel
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[i] -= round16(ET{}, x[i]);
+                pl[b][0] = pack2(ET{}, x[0], x[1]);
+                pl[b][1] = pack2(ET{}, x[2], x[3]);
+                pl[b][2] = pack2(ET{}, x[4], x[5]);
+                pl[b][3] = pack2(ET{}, x[6], x[7]);
+            }
+        }
+        // one block at a time: the scheduler would otherwise interleave the four independent
+        // blocks and keep all their temporaries live at once
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // every V^T operand is built once and serves all blocks
+#pragma unroll
+    for (int c = 0; c < VW; ++c) {
+        u32x4 va;
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) {
+            const uint32_t w0 = t.v[2 * pr][c >> 1];
+            const uint32_t w1 = t.v[2 * pr + 1][c >> 1];
+            va[pr] = (c & 1) ? pair_hi(w0, w1) : pair_lo(w0, w1);
+        }
+#pragma unroll
+        for (int b = 0; b < kWideBlocks; ++b) {
+            st[b].acc[c] = mfma16x16x32(ET{}, va, pb[b], st[b].acc[c]);
+            if (kSplitP) st[b].acc[c] = mfma16x16x32(ET{}, va, pl[b], st[b].acc[c]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+constexpr int kWideSlotRows = kWideRows;        // rows of one partial slot
+
+template <typename ET, int D>
+__global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(AttnParams p) {
+    extern __shared__ int32_t prefix[];
+    constexpr int KS = TileRegs<D>::KS;
+    constexpr int VW = TileRegs<D>::VW;
+    typedef TileRegs<D> TR;
+    build_tile_prefix<kWideLine>(p, prefix);
+    if (blockIdx.x == 0)       // the merge kernel reads the tile prefix from the workspace header
+        for (int i = threadIdx.x; i <= p.B; i += blockDim.x) p.ws_header[i] = prefix[i];
+    const int total = prefix[p.B];
+    const int per = (total + p.num_waves - 1) / p.num_waves;
+    const int wave = uniform((int)(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)));
+    const int gbeg = wave * per;
+    const int gend = min(total, gbeg + per);
+    if (gbeg >= gend) return;
+
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15;       // query row inside a block (MFMA column) of this lane
+    const int g = lane >> 4;       // which quarter of the k-slots / key rows
+    const uint32_t new_row_bytes = (uint32_t)p.H * (D * 2);
+    const uint32_t cache_row_bytes = (uint32_t)p.row_stride_b;
+
+    int lo = 0, hi = p.B;          // invariant: prefix[lo] <= gbeg < prefix[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (prefix[mid] <= gbeg) lo = mid; else hi = mid;
+    }
+
+    WideSegment cur = make_wide_segment<D>(p, prefix, uniform(lo), gbeg, gend);
+    int cur_end = gbeg + (cur.t1 - cur.t0);
+    WideSegment nxt = cur;
+    if (cur_end < gend) nxt = next_wide_segment<D>(p, prefix, cur, cur_end, gend);
+
+    // Q^T of the pair's blocks as B operands of S^T = K Q^T: wave-private LDS, one 16-byte slot
+    // per (block, k-step, lane)
+    u32x4* const q_lds = reinterpret_cast<u32x4*>(reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15)) +
+                         (threadIdx.x >> 6) * (kWideBlocks * KS * kWave) + (threadIdx.x & 63);
+    SoftmaxState<ET, D> st[kWideBlocks];
+    uint64_t vis[kWideBlocks];             // this lane's row of block b: visible new rows of the sample
+
+    // Q rows, per-row state and visible sets of a pair, when it becomes current
+    auto begin_segment = [&](const WideSegment& s) __attribute__((always_inline)) {
+        const uint64_t qaddr = uniform_addr(p.q + s.new_off);
+        int par = -1;
+        if (p.parent != nullptr)
+            par = gload<int32_t>(uniform_addr(p.parent + s.cu_i), (uint32_t)min(lane, s.ktot - 1) * 4u);
+#pragma unroll
+        for (int b = 0; b < kWideBlocks; ++b) {
+            if (b < s.blocks()) {
+                const int row = min(s.row0() + kMaxRows * b + n, s.ktot - 1);   // rows beyond the last repeat it, zeroed below
+                const uint32_t qoff = (uint32_t)row * new_row_bytes;
+                const bool real = kMaxRows * b + n < s.k;
+                u32x4 qv[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) qv[ks] = gload<u32x4>(qaddr, qoff + TR::piece(ks, g));
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const u32x4 z = {0u, 0u, 0u, 0u};
+                    q_lds[(b * KS + ks) * kWave] = (real && TR::piece_valid(ks, g)) ? qv[ks] : z;
+                }
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < kWideBlocks; ++b) {
+            if (b < s.blocks()) {
+#pragma unroll
+                for (int c = 0; c < VW; ++c) st[b].acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+                st[b].m = -INFINITY;
+                st[b].l = 0.f;
+                // among the new rows a row sees itself and the rows before it; in a token tree,
+                // itself and its ancestors
+                const int row = min(s.row0() + kMaxRows * b + n, s.ktot - 1);
+                vis[b] = row >= 63 ? ~0ull : (1ull << (row + 1)) - 1;
+                if (p.parent != nullptr) vis[b] = tree_visibility64(par, lane, s.ktot, row);
+            }
+        }
+    };
+
+    auto issue = [&](TileRegs<D>& t, int tile, int L, int k, int64_t cache_off, int64_t new_off)
+                     __attribute__((always_inline)) {
+        TileSrc src;
+        const int ntc = (L + kTileKeys - 1) / kTileKeys;
+        const bool is_new = tile >= ntc;                               // wave-uniform
+        src.kbase = uniform_addr(is_new ? p.k_new + new_off : p.k_cache + cache_off);
+        src.vbase = uniform_addr(is_new ? p.v_new + new_off : p.v_cache + cache_off);
+        src.row_bytes = is_new ? new_row_bytes : cache_row_bytes;
+        src.n0 = is_new ? (tile - ntc) * kTileKeys : tile * kTileKeys;
+        src.last = is_new ? k - 1 : L - 1;
+        src.mask_base = 0;
+        load_tile<D, false>(t, src, n, g);
+    };
+
+    auto consume = [&](const TileRegs<D>& t, const WideSegment& s, int tile) __attribute__((always_inline)) {
+        const int nb = s.blocks();
+        if (tile < s.ntc()) {
+            const int lim = s.L - tile * kTileKeys;
+            if (lim >= kTileKeys)
+                compute_tile_wide<ET, D, false, false>(t, q_lds, st, nb, p.scale_log2, lim, nullptr, g);
+            else
+                compute_tile_wide<ET, D, true, false>(t, q_lds, st, nb, p.scale_log2, lim, nullptr, g);
+            return;
+        }
+        const int key0 = kTileKeys * (tile - s.ntc());                 // first new row of this tile
+        uint32_t v32[kWideBlocks];
+#pragma unroll
+        for (int b = 0; b < kWideBlocks; ++b) v32[b] = (uint32_t)(vis[b] >> key0);
+        compute_tile_wide<ET, D, true, true>(t, q_lds, st, nb, p.scale_log2, 0, v32, g);
+        if (p.write_through && s.half == 0) {      // (both halves read the new rows, one stores them)
+            // Paper order (Sec. 3.2): the new rows' K/V go to the sample's own location, cache
+            // rows kv_len + j, straight from the registers of this tile (new rows key0 .. key0+31).
+            const uint32_t row_b = cache_row_bytes;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int key = key0 + 16 * half + n;
+                if (key < s.ktot) {
+                    char* kdst = const_cast<char*>(p.k_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + key) * row_b;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        if (TR::piece_valid(ks, g))
+                            *reinterpret_cast<u32x4*>(kdst + TR::piece(ks, g)) = half ? t.kb[ks] : t.ka[ks];
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int key = key0 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
+                if (key < s.ktot && n < TR::kVLanes) {
+                    char* vdst = const_cast<char*>(p.v_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + key) * row_b + n * (VW * 2);
+                    *reinterpret_cast<typename TileRegs<D>::vrow_t*>(vdst) = t.v[e];
+                }
+            }
+        }
+    };
+
+    auto finish_segment = [&](const WideSegment& s) __attribute__((always_inline)) {
+        const bool whole = s.t0 == 0 && s.t1 == s.nt();
+        // partial: slot 2w holds a range that continues a pair begun by an earlier wave, slot
+        // 2w+1 one that starts a pair and leaves its end to later waves; 32 rows per slot
+        const int slot = 2 * wave + (s.t0 == 0 ? 1 : 0);
+#pragma unroll
+        for (int b = 0; b < kWideBlocks; ++b) {
+            if (b < s.blocks()) {
+                const float l = quad_sum(st[b].l);     // the four lanes of a row hold disjoint shares
+                const int r_in_pair = kMaxRows * b + n;
+                if (r_in_pair < s.k) {
+                    if (whole) {
+                        const float inv = 1.0f / l;
+                        const int64_t row = ((int64_t)(s.cu_i + s.row0() + r_in_pair) * p.H + s.h) * D;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            if (4 * g + r >= TR::kVLanes) continue;
+                            const int d0 = (4 * g + r) * VW;
+                            float o[VW];
+#pragma unroll
+                            for (int c = 0; c < VW; ++c) o[c] = st[b].acc[c][r] * inv;
+                            if (p.out_f32) {
+                                float* dst = reinterpret_cast<float*>(p.out) + row + d0;
+#pragma unroll
+                                for (int c = 0; c < VW; c += 4)
+                                    *reinterpret_cast<f32x4*>(dst + c) = f32x4{o[c], o[c + 1], o[c + 2], o[c + 3]};
+                            } else {
+                                uint16_t* dst = reinterpret_cast<uint16_t*>(p.out) + row + d0;
+                                typename TileRegs<D>::vrow_t pk;
+#pragma unroll
+                                for (int c = 0; c < VW; c += 2) pk[c >> 1] = pack2(ET{}, o[c], o[c + 1]);
+                                *reinterpret_cast<typename TileRegs<D>::vrow_t*>(dst) = pk;
+                            }
+                        }
+                    } else {
+                        float* dst = p.ws + ((int64_t)slot * kWideSlotRows + r_in_pair) * (D + kPartialPad);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            if (4 * g + r >= TR::kVLanes) continue;
+                            const int d0 = (4 * g + r) * VW;
+#pragma unroll
+                            for (int c = 0; c < VW; c += 4)
+                                *reinterpret_cast<f32x4*>(dst + d0 + c) =
+                                    f32x4{st[b].acc[c][r], st[b].acc[c + 1][r], st[b].acc[c + 2][r], st[b].acc[c + 3][r]};
+                        }
+                        if (g == 0) {
+                            dst[D] = st[b].m;
+                            dst[D + 1] = l;
+                        }
+                    }
+                }
+            }
+        }
+    };
+
+    int con_t = cur.t0;              // tile of `cur` that is consumed next
+
+    // One step of the walk: issue flat tile c+1 into `fill`, consume flat tile c from `use`.
+    auto step = [&](int c, const TileRegs<D>& use, TileRegs<D>& fill) __attribute__((always_inline)) {
+        if (c + 1 < gend) {
+            const bool same = con_t + 1 < cur.t1;        // else: first tile of the next pair
+            issue(fill, same ? con_t + 1 : nxt.t0, same ? cur.L : nxt.L, same ? cur.ktot : nxt.ktot,
+                  same ? cur.cache_off : nxt.cache_off, same ? cur.new_off : nxt.new_off);
+        }
+        consume(use, cur, con_t);
+        ++con_t;
+        if (con_t == cur.t1) {
+            finish_segment(cur);
+            if (c + 1 < gend) {
+                cur = nxt;
+                con_t = cur.t0;
+                cur_end = c + 1 + (cur.t1 - cur.t0);
+                begin_segment(cur);
+                if (cur_end < gend) nxt = next_wide_segment<D>(p, prefix, cur, cur_end, gend);
+            }
+        }
+    };
+
+    TileRegs<D> ta, tb;
+    issue(ta, cur.t0, cur.L, cur.ktot, cur.cache_off, cur.new_off);
+    begin_segment(cur);
+    for (int c = gbeg; c < gend; c += 2) {
+        step(c, ta, tb);
+        if (c + 1 < gend) step(c + 1, tb, ta);
+    }
+}
+
+// Merge of the partials of pairs shared by several waves, as in the 16-row kernels, with 32
+// rows per slot and up to two pairs per (sample, head).
+template <int D> struct WideCombine {
+    static constexpr int lanes_per_row = D / 4;
+    static constexpr int rows_per_pass = 8;
+    static constexpr int threads = rows_per_pass * lanes_per_row;
+};
+
+template <typename ET, int D>
+__global__ __launch_bounds__(WideCombine<D>::threads) void combine_wide_partials_kernel(AttnParams p) {
+    const int i = blockIdx.y, h = blockIdx.x;
+    const int cu_i = p.cu[i];
+    const int ktot = min(kMaxRowsWide, p.cu[i + 1] - cu_i);
+    const int total = p.ws_header[p.B];
+    const int first = p.ws_header[i];
+    const int next = p.ws_header[i + 1];
+    if (ktot <= 0) return;
+    const int per = (total + p.num_waves - 1) / p.num_waves;
+    const int halves = wide_halves(ktot);
+    const int nt = (next - first) / (p.H * halves);
+    constexpr int pitch = D + kPartialPad;
+    constexpr int lanes_per_row = WideCombine<D>::lanes_per_row;
+    const int c4 = (threadIdx.x % lanes_per_row) * 4;
+    for (int half = 0; half < halves; ++half) {        // the pairs of this (sample, head)
+    const int g0 = first + (h * halves + half) * nt;
+    const int w0 = g0 / per, w1 = (g0 + nt - 1) / per;
+    if (w0 == w1) continue;                // one wave saw the whole pair and wrote `out` itself
+    const int k = min(kWideRows, ktot - kWideRows * half);
+    for (int j = threadIdx.x / lanes_per_row; j < k; j += WideCombine<D>::rows_per_pass) {
+        auto slot_row = [&](int w) -> const float* {
+            const int slot = 2 * w + (w == w0 ? 1 : 0);
+            return p.ws + ((int64_t)slot * kWideSlotRows + j) * pitch;
+        };
+        float M = -INFINITY, den = 0.f;
+        f32x4 num = {0.f, 0.f, 0.f, 0.f};
+        auto fold = [&](float m, float l, f32x4 v) {
+            const float Mn = fmaxf(M, m);
+            // (a range that holds only new-token tiles no key of which the row sees: max -inf, sum 0)
+            const float Ms = Mn == -INFINITY ? 0.f : Mn;
+            const float a = fast_exp2(M - Ms), b = fast_exp2(m - Ms);
+            num = num * a + v * b;
+            den = den * a + l * b;
+            M = Mn;
+        };
+        int w = w0;
+        for (; w + 1 <= w1; w += 2) {
+            const float* s0 = slot_row(w);
+            const float* s1 = slot_row(w + 1);
+            const float m0 = s0[D], l0 = s0[D + 1], m1 = s1[D], l1 = s1[D + 1];
+            const f32x4 v0 = *reinterpret_cast<const f32x4*>(s0 + c4);
+            const f32x4 v1 = *reinterpret_cast<const f32x4*>(s1 + c4);
+            fold(m0, l0, v0);
+            fold(m1, l1, v1);
+        }
+        if (w <= w1) {
+            const float* s0 = slot_row(w);
+            fold(s0[D], s0[D + 1], *reinterpret_cast<const f32x4*>(s0 + c4));
+        }
+        const float inv = 1.0f / den;
+        const int64_t idx = ((int64_t)(cu_i + kWideRows * half + j) * p.H + h) * D + c4;
+        if (p.out_f32) {
+            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + idx) = num * inv;
+        } else {
+            u32x2 pk;
+            pk[0] = pack2(ET{}, num[0] * inv, num[1] * inv);
+            pk[1] = pack2(ET{}, num[2] * inv, num[3] * inv);
+            *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(p.out) + idx) = pk;
+        }
+    }
+    }
+}
+
+template <typename ET, int D>
+static hipError_t launch_wide_typed(const AttnParams& p, int blocks, hipStream_t stream,
+                                    hipEvent_t ev_start, hipEvent_t ev_stop) {
+    // tile prefix sums + the waves' Q^T stores (4 x 8 KiB at D = 128): may exceed the 64 KiB a
+    // kernel gets by default on some HIP platforms, so ask for the device's 160 KiB once
+    const size_t lds = ((((size_t)(p.B + 1) * sizeof(int32_t)) + 15) & ~(size_t)15) +
+                       (size_t)kWavesPerBlock * kWideBlocks * TileRegs<D>::KS * kWave * sizeof(u32x4);
+    hipError_t e;
+    static std::atomic<bool> raised{false};
+    if (lds > 64 * 1024 && !raised.load()) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_attention_wide_kernel<ET, D>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+        if (e != hipSuccess) return e;
+        raised.store(true);
+    }
+    if (ev_start && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
+    hipLaunchKernelGGL((verify_attention_wide_kernel<ET, D>), dim3(blocks), dim3(kAttnThreads), lds,
+                       stream, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
+    hipLaunchKernelGGL((combine_wide_partials_kernel<ET, D>), dim3(p.H, p.B),
+                       dim3(WideCombine<D>::threads), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify_attention_wide(const AttnParams& p, int blocks, int D, bool bf16,
+                                        hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+    if (D == 128) return bf16 ? launch_wide_typed<BF16, 128>(p, blocks, stream, ev_start, ev_stop)
+                              : launch_wide_typed<F16, 128>(p, blocks, stream, ev_start, ev_stop);
+    if (D == 80) return bf16 ? launch_wide_typed<BF16, 80>(p, blocks, stream, ev_start, ev_stop)
+                             : launch_wide_typed<F16, 80>(p, blocks, stream, ev_start, ev_stop);
+    return bf16 ? launch_wide_typed<BF16, 64>(p, blocks, stream, ev_start, ev_stop)
+                : launch_wide_typed<F16, 64>(p, blocks, stream, ev_start, ev_stop);
+}
+
+}  // namespace ems

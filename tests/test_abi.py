@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 def test_workspace_sizes_are_host_arithmetic():
     assert ems.ems_attention_workspace_bytes(64, 384, 32, 128, 2048) >= 256
     assert ems.ems_attention_workspace_bytes(1, 1, 1, 64, 0) >= 256
-    assert ems.ems_attention_workspace_bytes(128, 448, 32, 128, 4096) <= 128 << 20
+    assert ems.ems_attention_workspace_bytes(128, 448, 32, 128, 4096) <= 160 << 20
     assert ems.ems_accept_workspace_bytes(0, 50272) == 0
     assert ems.ems_accept_workspace_bytes(384, 0) == 0
     assert ems.ems_accept_workspace_bytes(384, 50272) >= 384 * 8

@@ -1,6 +1,6 @@
 """GPU parity on a seeded sweep of random valid shapes: batch size, head count, head dim, dtype,
 cache layout, ragged cached lengths (empty caches, exact tile multiples, tails), rows per
-sample (0..16, and 0..64 in the cases that exercise row groups), regions placed in shuffled
+sample (0..16, and 0..64 in the cases that exercise the wide kernel), regions placed in shuffled
 order with gaps.  Every case runs the whole step
 (attention, accept from given ids, append) and its tree-structured twin against the oracle."""
 import numpy as np
@@ -42,7 +42,7 @@ def random_case(seed, k_hi=16):
 
 @pytest.mark.parametrize("seed", list(range(24)) + [(s, 64) for s in range(100, 112)])
 def test_random_shape(seed):
-    """(seed) draws up to 16 rows per sample; (seed, 64) up to 64, i.e. several row groups."""
+    """(seed) draws up to 16 rows per sample; (seed, 64) up to 64, i.e. the wide kernel."""
     k_hi = 16
     if isinstance(seed, tuple):
         seed, k_hi = seed

@@ -1,7 +1,7 @@
-"""GPU parity with more than 16 rows per sample (up to 64): the attention calls then cut a
-sample's rows into row groups of 16, each a pair of its own that streams the cache and up to two
-tiles of new tokens.  Causal and tree masks, write-through, accept and append, against the
-oracle on the same seeded inputs."""
+"""GPU parity with more than 16 rows per sample (up to 64): the attention calls then run the wide
+kernel, which holds 32 rows per (sample, head) pair and makes two pairs of a sample with more;
+every pair streams the cache and up to two tiles of new tokens.  Causal and tree masks,
+write-through, accept and append, against the oracle on the same seeded inputs."""
 import numpy as np
 import pytest
 import torch
@@ -25,21 +25,20 @@ def test_causal_rows_beyond_sixteen(dtype, D, layout):
     b = make_batch(KV, K, H=3, D=D, dtype=dtype, seed=80, capacity=800, layout=layout, vocab_for_ids=9,
                    match_p=0.9)
     assert b.max_k == 64
-    check_attention(b, out_dtype=torch.float32, label="row groups f32 out")
-    check_attention(b, label="row groups 16-bit out")
+    check_attention(b, out_dtype=torch.float32, label="wide f32 out")
+    check_attention(b, label="wide 16-bit out")
     run_accept_and_append(b)
 
 
-def test_row_group_pairs_merged_from_partials():
-    # few long pairs: every row group's tiles are spread over many waves
+def test_wide_pairs_merged_from_partials():
+    # few long pairs: every pair's tiles are spread over many waves
     b = make_batch([5000, 3000], [40, 64], H=1, D=128, dtype=torch.bfloat16, seed=81)
-    check_attention(b, out_dtype=torch.float32, label="row groups, merged")
+    check_attention(b, out_dtype=torch.float32, label="wide, merged")
 
 
-def test_sixteen_rows_or_fewer_through_the_row_group_launch():
-    """max_k only selects the launch shape: with k_i <= 16 everywhere, max_k = 64 (every sample a
-    single row group) must meet the oracle as the max_k = 16 launch does (the two differ only in
-    how many waves share the tiles, hence in the rounding of merged partials)."""
+def test_sixteen_rows_or_fewer_through_the_wide_kernel():
+    """max_k only selects the kernel: with k_i <= 16 everywhere, max_k = 64 (the wide kernel, one
+    block of rows in use) must meet the oracle as the max_k = 16 launch does."""
     b_cpu = make_batch([900, 1200, 31, 0], [7, 3, 16, 11], H=4, D=128, dtype=torch.bfloat16, seed=82)
     b = to_device(b_cpu)
     want = oracle_attention(b_cpu)
@@ -66,7 +65,7 @@ def test_trees_of_up_to_64_rows(shape, dtype, D, layout):
 
 
 @pytest.mark.parametrize("layout", [TOKEN_MAJOR, HEAD_MAJOR])
-def test_write_through_with_row_groups(layout):
+def test_write_through_with_wide_rows(layout):
     b_cpu = make_batch(KV, K, H=3, D=128, dtype=torch.float16, seed=85, capacity=800, layout=layout)
     b = to_device(b_cpu)
     kc, vc = b.k_cache.clone(), b.v_cache.clone()

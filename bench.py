@@ -72,6 +72,17 @@ def parse_args():
     return ap.parse_args()
 
 
+def device_memory_figures():
+    """What the runtime reports for the card's memory (clock in kHz, bus width in bits), as
+    context beside the published 8 TB/s that `peak` uses; None where it reports nothing."""
+    import torch
+    import paper_2405_07542_amd as ems
+    props = torch.cuda.get_device_properties(0)
+    clock_khz, width_bits = ems.ems_device_memory_figures()
+    return {"name": props.name, "memory_clock_khz": clock_khz, "memory_bus_width_bits": width_bits,
+            "total_memory_gib": round(props.total_memory / 2**30, 1)}
+
+
 def measured_read_ceiling(buf, reps=10):
     """GB/s of the library's read-only streaming kernel over `buf` (a K arena: far larger
     than the caches), HIP events on the current stream."""
@@ -267,6 +278,7 @@ def main():
         "launches_timed": attn_launches,
         # context, not the peak: a plain read-only streaming kernel over one K arena, same run
         "measured_read_ceiling": ceiling, "frac_of_measured_ceiling": round(achieved / ceiling, 4),
+        "device_reported": device_memory_figures(),
     }
 
     result = {

@@ -342,6 +342,14 @@ typedef enum ems_attention_variant {
 EMS_API ems_status ems_set_attention_variant(int variant);
 EMS_API int ems_get_attention_variant(void);
 
+/*
+ * What the HIP runtime reports for the current device's memory: clock in kHz, bus width in
+ * bits (either may come back 0 where the runtime reports nothing).  Context for bandwidth
+ * figures; the library itself does not use them.  Host pointers, both required.
+ * Errors: NULL pointer -> INVALID_ARG; runtime failure -> HIP.
+ */
+EMS_API ems_status ems_device_memory_figures(int* memory_clock_khz, int* memory_bus_width_bits);
+
 /* Thread-local text for the last non-OK status returned on this thread. */
 EMS_API const char* ems_last_error_string(void);
 

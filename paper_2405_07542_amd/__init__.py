@@ -52,6 +52,8 @@ def lib() -> ctypes.CDLL:
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
         L.ems_last_error_string.restype = ctypes.c_char_p
         L.ems_version.restype = ctypes.c_char_p
+        L.ems_device_memory_figures.restype = i32
+        L.ems_device_memory_figures.argtypes = [ctypes.POINTER(ctypes.c_int)] * 2
         L.ems_attention_workspace_bytes.restype = sz
         L.ems_attention_workspace_bytes.argtypes = [i32] * 5
         L.ems_accept_workspace_bytes.restype = sz
@@ -292,6 +294,13 @@ def ems_set_attention_variant(variant: int) -> None:
 
 def ems_get_attention_variant() -> int:
     return int(lib().ems_get_attention_variant())
+
+
+def ems_device_memory_figures():
+    """(memory clock in kHz, memory bus width in bits) as the HIP runtime reports them."""
+    clock, width = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().ems_device_memory_figures(ctypes.byref(clock), ctypes.byref(width)))
+    return clock.value, width.value
 
 
 def ems_profile_enable(max_records: int) -> None:

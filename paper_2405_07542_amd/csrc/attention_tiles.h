@@ -2,10 +2,26 @@
 // tile as registers, how it is loaded and consumed on the matrix cores, the per-sample tile
 // counts laid on one line, and the visible-set construction for token trees.
 #pragma once
+#include <atomic>
+
 #include "ems_device.h"
 #include "ems_kernels.h"
 
 namespace ems {
+
+// Host: let `kernel` use all of a workgroup's LDS.  Kernels get 64 KiB of dynamic LDS by
+// default; the limit is a property of (kernel, device), so it is raised once per device
+// (`done` = the kernel's own set of devices already served, one bit each).
+inline hipError_t allow_max_lds(const void* kernel, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load() & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    if (e == hipSuccess) done.fetch_or(bit);
+    return e;
+}
 
 constexpr int kTileKeys = 32;
 constexpr int kMaxRows = 16;             // query rows per MFMA column block

@@ -106,6 +106,16 @@ const char* ems_last_error_string(void) { return g_err; }
 
 const char* ems_version(void) { return "0.1"; }
 
+ems_status ems_device_memory_figures(int* memory_clock_khz, int* memory_bus_width_bits) {
+    if (!memory_clock_khz || !memory_bus_width_bits) return fail(EMS_ERR_INVALID_ARG, "NULL output pointer");
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(memory_clock_khz, hipDeviceAttributeMemoryClockRate, dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(memory_bus_width_bits, hipDeviceAttributeMemoryBusWidth, dev);
+    if (e != hipSuccess) return fail(EMS_ERR_HIP, "device attributes: %s", hipGetErrorString(e));
+    return EMS_OK;
+}
+
 size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len) {
     (void)T;
     if (B < 1 || H < 1 || D < 1 || max_kv_len < 0) return 256;

@@ -626,13 +626,9 @@ static hipError_t launch_typed(const AttnParams& p, int blocks, bool valu, hipSt
             // prefix sums + 4 x 36 KiB (D = 128) of wave-private state: well above the 64 KiB a
             // kernel may use by default on some HIP platforms, so ask for the device's 160 KiB
             if (lds > kMaxLdsBytes) return hipErrorInvalidValue;   // (the API layer rejects such B first)
-            static std::atomic<bool> raised{false};
-            if (!raised.load()) {
-                e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_attention_kernel<ET, D, false, true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
-                if (e != hipSuccess) return e;
-                raised.store(true);
-            }
+            static std::atomic<uint64_t> raised{0};
+            e = allow_max_lds(reinterpret_cast<const void*>(&verify_attention_kernel<ET, D, false, true>), raised);
+            if (e != hipSuccess) return e;
             hipLaunchKernelGGL((verify_attention_kernel<ET, D, false, true>), dim3(blocks),
                                dim3(kAttnThreads), lds, stream, p);
             launched = true;

@@ -17,7 +17,6 @@
 //     a token tree), of which every new-token tile uses its 32 bits (the first half never
 //     sees a key of the second tile: that tile costs it one empty pass);
 //   * the Q rows of the next pair are loaded at the switch (no prefetch).
-#include <atomic>
 
 #include "attention_tiles.h"
 
@@ -88,6 +87,8 @@ __device__ __forceinline__ WideSegment next_wide_segment(const AttnParams& p, co
     return s;
 }
 
+constexpr float kMaxSlack = 6.f;     // P entries stay below 2^6: exact in fp32, far inside fp16 / bf16 range
+
 // One tile against the (up to two) blocks of query rows of a pair.  Cache tile: `lim` visible keys (the same
 // for every row; MASKED when < 32).  Tile of new tokens (NEW): vis[b] = this lane's row of
 // block b sees key n of the tile iff bit n is set; a block may see nothing of the tile.
@@ -132,7 +133,13 @@ __device__ __forceinline__ void compute_tile_wide(const TileRegs<D>& t, const u3
             }
             const float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
                                    fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-            const float m_new = fmaxf(st[b].m, quad_max(mx));
+            // The running reference m only has to keep exp2(x - m) in range, it need not be the
+            // true maximum: it moves when a tile exceeds it by more than 2^kMaxSlack, which after
+            // a row's first tiles is rare, and while it stays the accumulators (which live in
+            // accumulation registers, where a rescale costs three instructions per value) are
+            // left alone.  acc / l is the same quotient either way.
+            const float m_tile = quad_max(mx);
+            const float m_new = m_tile > st[b].m + kMaxSlack ? m_tile : st[b].m;
             const float m_sub = (NEW && m_new == -INFINITY) ? 0.f : m_new;   // nothing visible yet
             const float alpha = fast_exp2(st[b].m - m_sub);
             float psum = 0.f;
@@ -481,16 +488,14 @@ template <typename ET, int D>
 static hipError_t launch_wide_typed(const AttnParams& p, int blocks, hipStream_t stream,
                                     hipEvent_t ev_start, hipEvent_t ev_stop) {
     // tile prefix sums + the waves' Q^T stores (4 x 8 KiB at D = 128): may exceed the 64 KiB a
-    // kernel gets by default on some HIP platforms, so ask for the device's 160 KiB once
+    // kernel gets by default on some HIP platforms, so ask for the device's 160 KiB
     const size_t lds = ((((size_t)(p.B + 1) * sizeof(int32_t)) + 15) & ~(size_t)15) +
                        (size_t)kWavesPerBlock * kWideBlocks * TileRegs<D>::KS * kWave * sizeof(u32x4);
     hipError_t e;
-    static std::atomic<bool> raised{false};
-    if (lds > 64 * 1024 && !raised.load()) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_attention_wide_kernel<ET, D>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    if (lds > 64 * 1024) {        // (only the very largest batches)
+        static std::atomic<uint64_t> raised{0};
+        e = allow_max_lds(reinterpret_cast<const void*>(&verify_attention_wide_kernel<ET, D>), raised);
         if (e != hipSuccess) return e;
-        raised.store(true);
     }
     if (ev_start && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
     hipLaunchKernelGGL((verify_attention_wide_kernel<ET, D>), dim3(blocks), dim3(kAttnThreads), lds,

@@ -195,3 +195,7 @@ def test_pack_tokens_rejects_bad_arguments_on_the_host():
     assert L.ems_pack_tokens(FAKE, FAKE, 4, -1, FAKE, FAKE, None) == ems.EMS_ERR_INVALID_ARG
     assert L.ems_pack_tokens(FAKE, None, 4, 4, FAKE, FAKE, None) == ems.EMS_ERR_INVALID_ARG
     assert L.ems_pack_tokens(None, FAKE, 4, 4, FAKE, FAKE, None) == ems.EMS_ERR_INVALID_ARG
+
+
+def test_device_memory_figures_rejects_null_pointers():
+    assert ems.lib().ems_device_memory_figures(None, None) == ems.EMS_ERR_INVALID_ARG

@@ -100,3 +100,19 @@ def test_limits_of_the_other_variants():
         ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, b.kv_start, b.kv_len, out,
                                  max_k=65, max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws)
     assert e.value.status == ems.EMS_ERR_UNSUPPORTED
+
+
+def test_maximum_batch_size_through_the_wide_kernel():
+    """B = 8192 with a few samples of more than 16 rows: 32 KiB of tile prefix sums plus the
+    waves' Q^T stores (32 KiB at D = 128) is the most LDS the wide kernel ever asks for."""
+    rng = np.random.default_rng(159)
+    B = 8192
+    kv = rng.integers(0, 41, B).tolist()
+    k = rng.integers(0, 4, B).tolist()
+    for i in rng.choice(B, 40, replace=False):
+        k[i] = int(rng.integers(17, 65))
+    k[0], k[-1] = 64, 33
+    b = make_batch(kv, k, H=1, D=128, dtype=torch.bfloat16, seed=160, capacity=112)
+    assert b.max_k == 64
+    check_attention(b, out_dtype=torch.float32, label="wide, B=8192")
+    run_accept_and_append(b)

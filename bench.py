@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--attention-variant", default="mfma", choices=["mfma", "valu"],
                     help="arithmetic units of the attention kernel's contractions: matrix cores (default) "
                          "or the vector ALU (a measurement aid; see ems_set_attention_variant)")
+    ap.add_argument("--tree-rows", type=int, default=0, metavar="N",
+                    help="with --tree: every sample brings U{N/2..N} rows (tree nodes) instead of the "
+                         "config's 1..11 (N <= 64; above 16 the attention call runs the wide kernel)")
     ap.add_argument("--tree", default=None, choices=["random", "wide", "star", "chain"],
                     help="tree-structured verification: the same config with every sample's new rows arranged "
                          "as a token tree of this shape (ems_tree_verify_attention / ems_tree_accept / "
@@ -164,6 +167,8 @@ def main():
     with_logits = not args.no_logits
     if args.tree and (args.write_through or args.attention_variant == "valu" or n == 5):
         sys.exit("--tree runs the matrix-core kernel with the gathered append on configs 2-4 only")
+    if args.tree_rows and (not args.tree or not 1 <= args.tree_rows <= 64):
+        sys.exit("--tree-rows N goes with --tree and 1 <= N <= 64")
     if args.per_token_grid:
         print(json.dumps(per_token_grid(args)), flush=True)
         return
@@ -184,7 +189,8 @@ def main():
     n_sets = args.sets
     v = 0
     while n_sets == 0 or v < n_sets:
-        b = make_config(n, device=dev, layout=args.layout, with_logits=with_logits, variant=v)
+        b = make_config(n, device=dev, layout=args.layout, with_logits=with_logits, variant=v,
+                        k_range=(max(1, args.tree_rows // 2), args.tree_rows) if args.tree_rows else None)
         if n_sets == 0:      # sized from the first draw: 256 MB of Infinity Cache must not hold a whole rotation
             n_sets = int(min(16, max(3, -(-(2 << 30) // max(1, attention_algorithmic_bytes(b, 2))))))
         if args.tree:
@@ -268,10 +274,12 @@ def main():
     alg_bytes = float(np.mean([attention_algorithmic_bytes(st["b"], out_bytes) for st in sets]))
     attn_ms = attn_ms_total / max(1, attn_launches)
     achieved = alg_bytes / (attn_ms * 1e-3) / 1e9
-    workload_key = "config%d_%s" % (n, args.layout)
+    workload_key = "config%d_%s" % (n, args.layout) + ("_tree_rows%d" % args.tree_rows if args.tree_rows else "")
+    wide = max(st["b"].max_k for st in sets) > 16
     ceiling = measured_read_ceiling(sets[0]["b"].k_cache)
     roofline = {
-        "bound": "hbm", "kernel": "verify_attention_kernel", "achieved": round(achieved, 1),
+        "bound": "hbm", "kernel": "verify_attention_wide_kernel" if wide else "verify_attention_kernel",
+        "achieved": round(achieved, 1),
         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": read_traffic(workload_key),
         "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": round(attn_ms, 5),
@@ -292,7 +300,8 @@ def main():
                    "query_rows_per_step": rows_per_step, "accepted_per_step": accepted_per_step,
                    "logits": with_logits, "buffer_sets": len(sets),
                    "variant": "write-through + advance" if args.write_through else "verify + append",
-                   "attention_variant": args.attention_variant, "tree": args.tree},
+                   "attention_variant": args.attention_variant, "tree": args.tree,
+                   "tree_rows": args.tree_rows or None},
         "query_tokens_per_s": round(rows_per_step / (ms_per_step * 1e-3), 1),
         "roofline": roofline,
     }

@@ -215,6 +215,10 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     p.scale_log2 = scale * 1.4426950408889634f;
     p.write_through = write_through ? 1 : 0;
     p.multi = wide ? 1 : 0;
+    // The in-workgroup merge of partials saves HBM writes in the middle of the read stream and
+    // costs a barrier and a fold at the end of the walk (~1 us): measured break-even at ~13 tiles
+    // per wave (B = 16, 1024 cached tokens), a loss of 1.5 us at 6, gains from 25 on.
+    p.wg_fold = tiles >= (int64_t)12 * p.num_waves ? 1 : 0;
     if (pad) {
         p.key_mask = pad->key_mask;
         p.k_valid = pad->k_valid;

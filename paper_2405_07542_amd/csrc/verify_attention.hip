@@ -21,9 +21,17 @@
 //     between lanes;
 //   * online softmax in the log2 domain; the row maximum is shared by the four
 //     lanes that hold one query row via two cross-lane shuffles per tile;
-//   * a range that covers only part of a pair writes an fp32 partial
-//     (accumulator, running max, running sum); a second small kernel merges
-//     the partials of such pairs by log-sum-exp.
+//   * a range that covers only part of a pair leaves an fp32 partial
+//     (accumulator, running max, running sum).  Writes to HBM in the middle of
+//     the read stream are costly far beyond their size (17 MB of partials at 16
+//     rows per sample cost 25 us of 290), so the four waves of a workgroup, whose
+//     ranges are neighbours on the line, merge what they share in LDS: a wave
+//     that continues a pair of the wave before it in the same workgroup parks
+//     that partial in LDS; a wave whose range ends inside a pair keeps that
+//     state in registers and, after a barrier at the end of the walk, folds in
+//     the parked partials of the waves after it, in wave order.  Only what
+//     crosses a workgroup's edge is written to the workspace, and a second
+//     small kernel merges those by log-sum-exp.
 #include <atomic>
 
 #include "attention_tiles.h"
@@ -241,6 +249,18 @@ __device__ __forceinline__ Segment next_segment(const AttnParams& p, const int32
     return s;
 }
 
+// A partial parked in LDS for the in-workgroup merge: the VW accumulator registers, the
+// running max and this lane's share of the running sum, for each of the 64 lanes.
+template <int D> struct FoldSlot {
+    static constexpr int m_at = TileRegs<D>::VW * kWave * 4;
+    static constexpr int l_at = m_at + kWave;
+    static constexpr int floats = l_at + kWave;
+};
+// LDS after the tile prefix sums: the parked partials of waves 1..3 and one word of flags per wave.
+template <int D> constexpr size_t fold_lds_bytes() {
+    return (size_t)(kWavesPerBlock - 1) * FoldSlot<D>::floats * sizeof(float) + kWavesPerBlock * sizeof(int32_t);
+}
+
 template <typename ET, int D, bool PADDED, bool VALU = false>
 __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnParams p) {
     extern __shared__ int32_t prefix[];
@@ -257,11 +277,22 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     const int wave = uniform((int)(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)));
     const int gbeg = wave * per;
     const int gend = min(total, gbeg + per);
-    if (gbeg >= gend) return;
-
     const int lane = threadIdx.x & 63;
     const int n = lane & 15;       // query row (MFMA column) of this lane
     const int g = lane >> 4;       // which quarter of the k-slots / key rows
+    // In-workgroup merge (matrix-core builds): after the prefix sums, LDS holds one parked
+    // partial per wave 1..3 (the state registers as they are, lane by lane) and a word of
+    // flags per wave: bit 0 = this wave parked the partial of the pair it continues, bit 1 =
+    // that pair ends inside this wave's range.
+    const int lw = uniform((int)(threadIdx.x >> 6));
+    float* const fold_lds = reinterpret_cast<float*>(reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15));
+    int32_t* const fold_flags = reinterpret_cast<int32_t*>(fold_lds + (kWavesPerBlock - 1) * FoldSlot<D>::floats);
+    const bool wg_fold = !VALU && p.wg_fold != 0;      // (the host leaves it off for very short walks)
+    if (wg_fold && lane == 0) fold_flags[lw] = 0;
+    if (gbeg >= gend) {            // (only past the end of a short line) nothing to walk, nothing to merge
+        if (wg_fold) __syncthreads();
+        return;
+    }
     const uint32_t new_row_bytes = (uint32_t)p.H * (D * 2);
     const uint32_t cache_row_bytes = (uint32_t)p.row_stride_b;
 
@@ -440,58 +471,80 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
         }
     };
 
+    // `st` normalised into out[cu_i + n, h, :]
+    auto write_out = [&](const Segment& s) __attribute__((always_inline)) {
+        // the four lanes of a query row hold disjoint shares of the sum
+        const float l = quad_sum(st.l);
+        if (n < s.k) {
+            const float inv = 1.0f / l;
+            const int64_t row = ((int64_t)(s.cu_i + n) * p.H + s.h) * D;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (4 * g + r >= TR::kVLanes) continue;      // head dim 80: output rows 10..15 hold nothing
+                const int d0 = (4 * g + r) * VW;
+                float o[VW];
+#pragma unroll
+                for (int c = 0; c < VW; ++c) o[c] = st.acc[c][r] * inv;
+                if (p.out_f32) {
+                    float* dst = reinterpret_cast<float*>(p.out) + row + d0;
+#pragma unroll
+                    for (int c = 0; c < VW; c += 4)
+                        *reinterpret_cast<f32x4*>(dst + c) = f32x4{o[c], o[c + 1], o[c + 2], o[c + 3]};
+                } else {
+                    uint16_t* dst = reinterpret_cast<uint16_t*>(p.out) + row + d0;
+                    typename TileRegs<D>::vrow_t pk;
+#pragma unroll
+                    for (int c = 0; c < VW; c += 2) pk[c >> 1] = pack2(ET{}, o[c], o[c + 1]);
+                    *reinterpret_cast<typename TileRegs<D>::vrow_t*>(dst) = pk;
+                }
+            }
+        }
+    };
+    // `st` as a partial in the workspace: slot 2w holds one that continues a pair begun by an
+    // earlier wave, slot 2w+1 one that starts a pair and leaves its end to later waves
+    auto write_partial = [&](const Segment& s) __attribute__((always_inline)) {
+        const float l = quad_sum(st.l);
+        const int slot = 2 * wave + (s.t0 == 0 ? 1 : 0);
+        if (n < s.k) {
+            float* dst = p.ws + ((int64_t)slot * 16 + n) * (D + kPartialPad);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (4 * g + r >= TR::kVLanes) continue;
+                const int d0 = (4 * g + r) * VW;
+#pragma unroll
+                for (int c = 0; c < VW; c += 4)
+                    *reinterpret_cast<f32x4*>(dst + d0 + c) =
+                        f32x4{st.acc[c][r], st.acc[c + 1][r], st.acc[c + 2][r], st.acc[c + 3][r]};
+            }
+            if (g == 0) {
+                dst[D] = st.m;
+                dst[D + 1] = l;
+            }
+        }
+    };
+
     auto finish_segment = [&](const Segment& s) __attribute__((always_inline)) {
         if (VALU) {
             finish_segment_valu(s);
             return;
         }
-        // the four lanes of a query row hold disjoint shares of the sum
-        const float l = quad_sum(st.l);
-        if (s.t0 == 0 && s.t1 == s.nt()) {
-            if (n < s.k) {
-                const float inv = 1.0f / l;
-                const int64_t row = ((int64_t)(s.cu_i + n) * p.H + s.h) * D;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (4 * g + r >= TR::kVLanes) continue;      // head dim 80: output rows 10..15 hold nothing
-                    const int d0 = (4 * g + r) * VW;
-                    float o[VW];
-#pragma unroll
-                    for (int c = 0; c < VW; ++c) o[c] = st.acc[c][r] * inv;
-                    if (p.out_f32) {
-                        float* dst = reinterpret_cast<float*>(p.out) + row + d0;
-#pragma unroll
-                        for (int c = 0; c < VW; c += 4)
-                            *reinterpret_cast<f32x4*>(dst + c) = f32x4{o[c], o[c + 1], o[c + 2], o[c + 3]};
-                    } else {
-                        uint16_t* dst = reinterpret_cast<uint16_t*>(p.out) + row + d0;
-                        typename TileRegs<D>::vrow_t pk;
-#pragma unroll
-                        for (int c = 0; c < VW; c += 2) pk[c >> 1] = pack2(ET{}, o[c], o[c + 1]);
-                        *reinterpret_cast<typename TileRegs<D>::vrow_t*>(dst) = pk;
-                    }
-                }
-            }
+        const bool continues = s.t0 != 0;          // an earlier wave holds the pair's first tiles
+        const bool open = s.t1 != s.nt();          // later waves hold its last tiles (then this is the wave's last segment)
+        if (!continues && !open) {
+            write_out(s);
+        } else if (!wg_fold) {
+            write_partial(s);                      // every wave's partials go to the workspace
+        } else if (open && (lw == 0 || !continues)) {
+            // stays in registers: after the barrier this wave folds in what the waves after it parked
+        } else if (lw == 0) {
+            write_partial(s);                      // the pair began in an earlier workgroup
         } else {
-            // partial: slot 2w holds a range that continues a pair begun by an earlier
-            // wave, slot 2w+1 one that starts a pair and leaves its end to later waves
-            const int slot = 2 * wave + (s.t0 == 0 ? 1 : 0);
-            if (n < s.k) {
-                float* dst = p.ws + ((int64_t)slot * 16 + n) * (D + kPartialPad);
+            float* f = fold_lds + (lw - 1) * FoldSlot<D>::floats;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (4 * g + r >= TR::kVLanes) continue;
-                    const int d0 = (4 * g + r) * VW;
-#pragma unroll
-                    for (int c = 0; c < VW; c += 4)
-                        *reinterpret_cast<f32x4*>(dst + d0 + c) =
-                            f32x4{st.acc[c][r], st.acc[c + 1][r], st.acc[c + 2][r], st.acc[c + 3][r]};
-                }
-                if (g == 0) {
-                    dst[D] = st.m;
-                    dst[D + 1] = l;
-                }
-            }
+            for (int c = 0; c < VW; ++c) *reinterpret_cast<f32x4*>(f + (c * kWave + lane) * 4) = st.acc[c];
+            f[FoldSlot<D>::m_at + lane] = st.m;
+            f[FoldSlot<D>::l_at + lane] = st.l;
+            if (lane == 0) fold_flags[lw] = 1 | (open ? 0 : 2);
         }
     };
 
@@ -538,6 +591,36 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
         step(c, ta, tb);
         if (c + 1 < gend) step(c + 1, tb, ta);
     }
+
+    if (wg_fold) {
+        // `cur` is the wave's last segment and `st` still holds its state
+        __syncthreads();
+        const bool continues = cur.t0 != 0;
+        if (cur.t1 != cur.nt() && (lw == 0 || !continues)) {
+            bool complete = false;
+            for (int j = lw + 1; j < kWavesPerBlock && !complete; ++j) {
+                const int flags = uniform(fold_flags[j]);
+                if ((flags & 1) == 0) break;     // (never while the pair is open: wave j holds its next tiles)
+                const float* f = fold_lds + (j - 1) * FoldSlot<D>::floats;
+                const float mb = f[FoldSlot<D>::m_at + lane];
+                const float lb = f[FoldSlot<D>::l_at + lane];
+                const float mn = fmaxf(st.m, mb);
+                // (padded ablation: a range of nothing but padding keys has max -inf and sum 0)
+                const float ms = mn == -INFINITY ? 0.f : mn;
+                const float ea = fast_exp2(st.m - ms), eb = fast_exp2(mb - ms);
+#pragma unroll
+                for (int c = 0; c < VW; ++c)
+                    st.acc[c] = st.acc[c] * ea + *reinterpret_cast<const f32x4*>(f + (c * kWave + lane) * 4) * eb;
+                st.l = st.l * ea + lb * eb;
+                st.m = mn;
+                complete = (flags & 2) != 0;
+            }
+            if (complete && !continues)
+                write_out(cur);
+            else
+                write_partial(cur);
+        }
+    }
 }
 
 // Merge the partials of every (sample, head) pair whose tiles were shared by several
@@ -566,6 +649,11 @@ __global__ __launch_bounds__(Combine<D>::threads) void combine_partials_kernel(A
     const int g0 = first + h * nt;
     const int w0 = g0 / per, w1 = (g0 + nt - 1) / per;
     if (w0 == w1) return;                  // one wave saw the whole pair and wrote `out` itself
+    // With the in-workgroup merge only the first wave of the pair and the first wave of every
+    // later workgroup it reaches have written a slot; a pair inside one workgroup is done.
+    const int wstep = p.wg_fold ? kWavesPerBlock : 1;
+    if (p.wg_fold && w0 / kWavesPerBlock == w1 / kWavesPerBlock) return;
+    const int wsecond = p.wg_fold ? (w0 / kWavesPerBlock + 1) * kWavesPerBlock : w0 + 1;
     constexpr int pitch = D + kPartialPad;
     constexpr int lanes_per_row = Combine<D>::lanes_per_row;
     const int c4 = (threadIdx.x % lanes_per_row) * 4;
@@ -586,10 +674,14 @@ __global__ __launch_bounds__(Combine<D>::threads) void combine_partials_kernel(A
             den = den * a + l * b;
             M = Mn;
         };
-        int w = w0;
-        for (; w + 1 <= w1; w += 2) {
+        {
+            const float* s0 = slot_row(w0);
+            fold(s0[D], s0[D + 1], *reinterpret_cast<const f32x4*>(s0 + c4));
+        }
+        int w = wsecond;
+        for (; w + wstep <= w1; w += 2 * wstep) {
             const float* s0 = slot_row(w);
-            const float* s1 = slot_row(w + 1);
+            const float* s1 = slot_row(w + wstep);
             const float m0 = s0[D], l0 = s0[D + 1], m1 = s1[D], l1 = s1[D + 1];
             const f32x4 v0 = *reinterpret_cast<const f32x4*>(s0 + c4);
             const f32x4 v1 = *reinterpret_cast<const f32x4*>(s1 + c4);
@@ -614,12 +706,16 @@ __global__ __launch_bounds__(Combine<D>::threads) void combine_partials_kernel(A
 }
 
 template <typename ET, int D, bool PADDED>
-static hipError_t launch_typed(const AttnParams& p, int blocks, bool valu, hipStream_t stream,
+static hipError_t launch_typed(const AttnParams& params, int blocks, bool valu, hipStream_t stream,
                                hipEvent_t ev_start, hipEvent_t ev_stop) {
+    valu = valu && !PADDED && D != 80;      // the vector-ALU formulation exists for these only
+    AttnParams p = params;
+    if (valu) p.wg_fold = 0;
     size_t lds = (size_t)(p.B + 1) * sizeof(int32_t);
     hipError_t e;
     if (ev_start && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
     bool launched = false;
+    if (p.wg_fold) lds = ((lds + 15) & ~(size_t)15) + fold_lds_bytes<D>();     // at most 32 KiB + 26 KiB
     if constexpr (!PADDED && D != 80) {
         if (valu) {
             lds = ((lds + 15) & ~(size_t)15) + (size_t)kWavesPerBlock * ValuLds<D>::bytes;

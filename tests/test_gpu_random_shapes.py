@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2405_07542_amd as ems
 from workloads import HEAD_MAJOR, TOKEN_MAJOR, bits, grow_trees, make_batch
-from helpers import to_device
+from helpers import attention_tolerance, hip_attention, oracle_attention, to_device
 from test_gpu_parity import check_attention, run_accept_and_append
 from test_gpu_tree import check_accept_and_append, check_tree_attention
 
@@ -58,3 +58,21 @@ def test_random_shape(seed):
     t = grow_trees(b, 3000 + seed, match_p=0.75, shape=["random", "wide", "star"][seed % 3])
     check_tree_attention(t, out_dtype=torch.float32)
     check_accept_and_append(t, use_logits=False, n_layers=2)
+
+
+@pytest.mark.parametrize("seed", range(200, 216))
+def test_random_shape_with_a_loose_length_bound(seed):
+    """max_kv_len is only a bound; a loose one makes the library size the launch for far more
+    tiles than there are (1024 waves, most of them with one tile or none) and switches on the
+    in-workgroup merge of partials that it keeps off for short walks: every pair is then cut
+    over many waves and workgroups.  The outputs must not change beyond rounding."""
+    b = random_case(seed, 16)
+    loose = 32 * (-(-14000 // (b.B * b.H)) + 1)
+    print("case", seed, "B", b.B, "H", b.H, "D", b.D, b.dtype, b.layout, "kv", b.kv_len.tolist(),
+          "k", np.diff(b.cu_seqlens.numpy()).tolist(), "bound", loose, flush=True)
+    assert loose > b.max_kv_len
+    want = oracle_attention(b)
+    got = hip_attention(to_device(b), out_dtype=torch.float32, max_kv_len=loose).double().cpu().numpy()
+    assert np.isfinite(got).all()
+    err = np.abs(got - want)
+    assert (err <= attention_tolerance(b, want, torch.float32)).all(), err.max()

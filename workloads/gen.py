@@ -263,14 +263,19 @@ CONFIG_NAMES = {
 
 
 def make_config(n: int, *, seed: int = BASE_SEED, device="cpu", layout: str = TOKEN_MAJOR,
-                with_logits: bool = True, variant: int = 0) -> VerifyBatch:
+                with_logits: bool = True, variant: int = 0, k_range=None) -> VerifyBatch:
     """The single-layer, single-step batch of BASELINE config n (1..5).
 
     ``variant`` selects an independent draw of the same distribution (used to
     rotate buffer sets so that a timed call does not find its data in cache).
+    ``k_range = (lo, hi)`` replaces the config's rows per sample by U{lo..hi} (token
+    trees are larger than the config's draft chains); everything else stays.
     """
     s = seed + n + 1000 * variant
     kv_len, k = draw_lengths(n, s)
+    if k_range is not None:
+        lo, hi = k_range
+        k = np.random.default_rng(s + 77).integers(lo, hi + 1, len(k)).tolist()
     if n == 1:
         return make_batch(kv_len, k, H=2, D=64, dtype=torch.float16, seed=s, kv_start=[0, 64],
                           rows=128, layout=layout, V=0, vocab_for_ids=50, match_p=0.6,

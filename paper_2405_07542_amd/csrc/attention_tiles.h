@@ -143,6 +143,13 @@ struct SoftmaxState {
     float l;           // this lane's share of the running sum
 };
 
+// A partial parked in LDS for the in-workgroup merge: the VW accumulator registers, the
+// running max and this lane's share of the running sum, for each of the 64 lanes.
+template <int D> struct FoldSlot {
+    static constexpr int m_at = TileRegs<D>::VW * kWave * 4;
+    static constexpr int l_at = m_at + kWave;
+    static constexpr int floats = l_at + kWave;
+};
 // One tile: scores, masked online softmax, PV.  `lim` = number of visible keys
 // of this tile for this lane's query row (>= 32 means no masking); with BITS it is
 // instead a bit set over the tile's 32 keys (bit n = key n visible), the form a tile of

@@ -32,7 +32,7 @@ struct AttnParams {
     float scale_log2;          // scale * log2(e)
     int write_through;         // also store the new rows' K/V at cache rows kv_len + j (paper order)
     int multi;                 // samples may bring more than 16 rows (up to 64): the wide kernel
-    int wg_fold;               // the 16-row matrix-core kernels: partials shared inside a workgroup are merged
+    int wg_fold;               // the matrix-core kernels: partials shared inside a workgroup are merged
                                // in LDS, only a workgroup's first wave (and a pair's first) writes a slot
                                // (set by the host for all but very short walks; ignored by the others)
     // padded ("vanilla") ablation only: every sample has k_max rows and an aligned cache of

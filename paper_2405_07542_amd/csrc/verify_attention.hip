@@ -249,13 +249,6 @@ __device__ __forceinline__ Segment next_segment(const AttnParams& p, const int32
     return s;
 }
 
-// A partial parked in LDS for the in-workgroup merge: the VW accumulator registers, the
-// running max and this lane's share of the running sum, for each of the 64 lanes.
-template <int D> struct FoldSlot {
-    static constexpr int m_at = TileRegs<D>::VW * kWave * 4;
-    static constexpr int l_at = m_at + kWave;
-    static constexpr int floats = l_at + kWave;
-};
 // LDS after the tile prefix sums: the parked partials of waves 1..3 and one word of flags per wave.
 template <int D> constexpr size_t fold_lds_bytes() {
     return (size_t)(kWavesPerBlock - 1) * FoldSlot<D>::floats * sizeof(float) + kWavesPerBlock * sizeof(int32_t);

@@ -16,7 +16,10 @@
 //     a row among the new rows is a 64-bit set (a causal prefix, or the row's ancestors in
 //     a token tree), of which every new-token tile uses its 32 bits (the first half never
 //     sees a key of the second tile: that tile costs it one empty pass);
-//   * the Q rows of the next pair are loaded at the switch (no prefetch).
+//   * the Q rows of the next pair are loaded at the switch (no prefetch);
+//   * partials that the waves of a workgroup share are merged in LDS as in the 16-row
+//     kernel (32 rows of them: at 32 rows per sample the workspace would otherwise take
+//     34 MB of writes in the middle of the read stream).
 
 #include "attention_tiles.h"
 
@@ -206,11 +209,22 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
     const int wave = uniform((int)(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)));
     const int gbeg = wave * per;
     const int gend = min(total, gbeg + per);
-    if (gbeg >= gend) return;
-
     const int lane = threadIdx.x & 63;
     const int n = lane & 15;       // query row inside a block (MFMA column) of this lane
     const int g = lane >> 4;       // which quarter of the k-slots / key rows
+    // In-workgroup merge, as in the 16-row kernel: after the prefix sums and the Q^T stores, LDS
+    // holds one parked partial (both blocks) per wave 1..3 and a word of flags per wave: bit 0 =
+    // this wave parked the partial of the pair it continues, bit 1 = that pair ends in its range.
+    const int lw = uniform((int)(threadIdx.x >> 6));
+    char* const lds_after_prefix = reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15);
+    float* const fold_lds = reinterpret_cast<float*>(lds_after_prefix + kWavesPerBlock * kWideBlocks * KS * kWave * sizeof(u32x4));
+    int32_t* const fold_flags = reinterpret_cast<int32_t*>(fold_lds + (kWavesPerBlock - 1) * kWideBlocks * FoldSlot<D>::floats);
+    const bool wg_fold = p.wg_fold != 0;               // (the host leaves it off for very short walks)
+    if (wg_fold && lane == 0) fold_flags[lw] = 0;
+    if (gbeg >= gend) {            // (only past the end of a short line) nothing to walk, nothing to merge
+        if (wg_fold) __syncthreads();
+        return;
+    }
     const uint32_t new_row_bytes = (uint32_t)p.H * (D * 2);
     const uint32_t cache_row_bytes = (uint32_t)p.row_stride_b;
 
@@ -227,8 +241,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
 
     // Q^T of the pair's blocks as B operands of S^T = K Q^T: wave-private LDS, one 16-byte slot
     // per (block, k-step, lane)
-    u32x4* const q_lds = reinterpret_cast<u32x4*>(reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15)) +
-                         (threadIdx.x >> 6) * (kWideBlocks * KS * kWave) + (threadIdx.x & 63);
+    u32x4* const q_lds = reinterpret_cast<u32x4*>(lds_after_prefix) + lw * (kWideBlocks * KS * kWave) + lane;
     SoftmaxState<ET, D> st[kWideBlocks];
     uint64_t vis[kWideBlocks];             // this lane's row of block b: visible new rows of the sample
 
@@ -325,58 +338,93 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
         }
     };
 
-    auto finish_segment = [&](const WideSegment& s) __attribute__((always_inline)) {
-        const bool whole = s.t0 == 0 && s.t1 == s.nt();
-        // partial: slot 2w holds a range that continues a pair begun by an earlier wave, slot
-        // 2w+1 one that starts a pair and leaves its end to later waves; 32 rows per slot
-        const int slot = 2 * wave + (s.t0 == 0 ? 1 : 0);
+    // the blocks' states normalised into out[cu_i + row0 + 16b + n, h, :]
+    auto write_out = [&](const WideSegment& s) __attribute__((always_inline)) {
 #pragma unroll
         for (int b = 0; b < kWideBlocks; ++b) {
             if (b < s.blocks()) {
                 const float l = quad_sum(st[b].l);     // the four lanes of a row hold disjoint shares
                 const int r_in_pair = kMaxRows * b + n;
                 if (r_in_pair < s.k) {
-                    if (whole) {
-                        const float inv = 1.0f / l;
-                        const int64_t row = ((int64_t)(s.cu_i + s.row0() + r_in_pair) * p.H + s.h) * D;
+                    const float inv = 1.0f / l;
+                    const int64_t row = ((int64_t)(s.cu_i + s.row0() + r_in_pair) * p.H + s.h) * D;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            if (4 * g + r >= TR::kVLanes) continue;
-                            const int d0 = (4 * g + r) * VW;
-                            float o[VW];
+                    for (int r = 0; r < 4; ++r) {
+                        if (4 * g + r >= TR::kVLanes) continue;
+                        const int d0 = (4 * g + r) * VW;
+                        float o[VW];
 #pragma unroll
-                            for (int c = 0; c < VW; ++c) o[c] = st[b].acc[c][r] * inv;
-                            if (p.out_f32) {
-                                float* dst = reinterpret_cast<float*>(p.out) + row + d0;
-#pragma unroll
-                                for (int c = 0; c < VW; c += 4)
-                                    *reinterpret_cast<f32x4*>(dst + c) = f32x4{o[c], o[c + 1], o[c + 2], o[c + 3]};
-                            } else {
-                                uint16_t* dst = reinterpret_cast<uint16_t*>(p.out) + row + d0;
-                                typename TileRegs<D>::vrow_t pk;
-#pragma unroll
-                                for (int c = 0; c < VW; c += 2) pk[c >> 1] = pack2(ET{}, o[c], o[c + 1]);
-                                *reinterpret_cast<typename TileRegs<D>::vrow_t*>(dst) = pk;
-                            }
-                        }
-                    } else {
-                        float* dst = p.ws + ((int64_t)slot * kWideSlotRows + r_in_pair) * (D + kPartialPad);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            if (4 * g + r >= TR::kVLanes) continue;
-                            const int d0 = (4 * g + r) * VW;
+                        for (int c = 0; c < VW; ++c) o[c] = st[b].acc[c][r] * inv;
+                        if (p.out_f32) {
+                            float* dst = reinterpret_cast<float*>(p.out) + row + d0;
 #pragma unroll
                             for (int c = 0; c < VW; c += 4)
-                                *reinterpret_cast<f32x4*>(dst + d0 + c) =
-                                    f32x4{st[b].acc[c][r], st[b].acc[c + 1][r], st[b].acc[c + 2][r], st[b].acc[c + 3][r]};
-                        }
-                        if (g == 0) {
-                            dst[D] = st[b].m;
-                            dst[D + 1] = l;
+                                *reinterpret_cast<f32x4*>(dst + c) = f32x4{o[c], o[c + 1], o[c + 2], o[c + 3]};
+                        } else {
+                            uint16_t* dst = reinterpret_cast<uint16_t*>(p.out) + row + d0;
+                            typename TileRegs<D>::vrow_t pk;
+#pragma unroll
+                            for (int c = 0; c < VW; c += 2) pk[c >> 1] = pack2(ET{}, o[c], o[c + 1]);
+                            *reinterpret_cast<typename TileRegs<D>::vrow_t*>(dst) = pk;
                         }
                     }
                 }
             }
+        }
+    };
+    // the blocks' states as a partial in the workspace: slot 2w holds one that continues a pair
+    // begun by an earlier wave, slot 2w+1 one that starts a pair and leaves its end to later
+    // waves; 32 rows per slot
+    auto write_partial = [&](const WideSegment& s) __attribute__((always_inline)) {
+        const int slot = 2 * wave + (s.t0 == 0 ? 1 : 0);
+#pragma unroll
+        for (int b = 0; b < kWideBlocks; ++b) {
+            if (b < s.blocks()) {
+                const float l = quad_sum(st[b].l);
+                const int r_in_pair = kMaxRows * b + n;
+                if (r_in_pair < s.k) {
+                    float* dst = p.ws + ((int64_t)slot * kWideSlotRows + r_in_pair) * (D + kPartialPad);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if (4 * g + r >= TR::kVLanes) continue;
+                        const int d0 = (4 * g + r) * VW;
+#pragma unroll
+                        for (int c = 0; c < VW; c += 4)
+                            *reinterpret_cast<f32x4*>(dst + d0 + c) =
+                                f32x4{st[b].acc[c][r], st[b].acc[c + 1][r], st[b].acc[c + 2][r], st[b].acc[c + 3][r]};
+                    }
+                    if (g == 0) {
+                        dst[D] = st[b].m;
+                        dst[D + 1] = l;
+                    }
+                }
+            }
+        }
+    };
+
+    auto finish_segment = [&](const WideSegment& s) __attribute__((always_inline)) {
+        const bool continues = s.t0 != 0;          // an earlier wave holds the pair's first tiles
+        const bool open = s.t1 != s.nt();          // later waves hold its last tiles (then this is the wave's last segment)
+        if (!continues && !open) {
+            write_out(s);
+        } else if (!wg_fold) {
+            write_partial(s);                      // every wave's partials go to the workspace
+        } else if (open && (lw == 0 || !continues)) {
+            // stays in registers: after the barrier this wave folds in what the waves after it parked
+        } else if (lw == 0) {
+            write_partial(s);                      // the pair began in an earlier workgroup
+        } else {
+#pragma unroll
+            for (int b = 0; b < kWideBlocks; ++b) {
+                if (b < s.blocks()) {
+                    float* f = fold_lds + ((lw - 1) * kWideBlocks + b) * FoldSlot<D>::floats;
+#pragma unroll
+                    for (int c = 0; c < VW; ++c) *reinterpret_cast<f32x4*>(f + (c * kWave + lane) * 4) = st[b].acc[c];
+                    f[FoldSlot<D>::m_at + lane] = st[b].m;
+                    f[FoldSlot<D>::l_at + lane] = st[b].l;
+                }
+            }
+            if (lane == 0) fold_flags[lw] = 1 | (open ? 0 : 2);
         }
     };
 
@@ -410,6 +458,41 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
         step(c, ta, tb);
         if (c + 1 < gend) step(c + 1, tb, ta);
     }
+
+    if (wg_fold) {
+        // `cur` is the wave's last segment and `st` still holds its state
+        __syncthreads();
+        const bool continues = cur.t0 != 0;
+        if (cur.t1 != cur.nt() && (lw == 0 || !continues)) {
+            bool complete = false;
+            for (int j = lw + 1; j < kWavesPerBlock && !complete; ++j) {
+                const int flags = uniform(fold_flags[j]);
+                if ((flags & 1) == 0) break;     // (never while the pair is open: wave j holds its next tiles)
+#pragma unroll
+                for (int b = 0; b < kWideBlocks; ++b) {
+                    if (b < cur.blocks()) {
+                        const float* f = fold_lds + ((j - 1) * kWideBlocks + b) * FoldSlot<D>::floats;
+                        const float mb = f[FoldSlot<D>::m_at + lane];
+                        const float lb = f[FoldSlot<D>::l_at + lane];
+                        const float mn = fmaxf(st[b].m, mb);
+                        // (a range that holds only new-token tiles no key of which the row sees: max -inf, sum 0)
+                        const float ms = mn == -INFINITY ? 0.f : mn;
+                        const float ea = fast_exp2(st[b].m - ms), eb = fast_exp2(mb - ms);
+#pragma unroll
+                        for (int c = 0; c < VW; ++c)
+                            st[b].acc[c] = st[b].acc[c] * ea + *reinterpret_cast<const f32x4*>(f + (c * kWave + lane) * 4) * eb;
+                        st[b].l = st[b].l * ea + lb * eb;
+                        st[b].m = mn;
+                    }
+                }
+                complete = (flags & 2) != 0;
+            }
+            if (complete && !continues)
+                write_out(cur);
+            else
+                write_partial(cur);
+        }
+    }
 }
 
 // Merge of the partials of pairs shared by several waves, as in the 16-row kernels, with 32
@@ -439,6 +522,11 @@ __global__ __launch_bounds__(WideCombine<D>::threads) void combine_wide_partials
     const int g0 = first + (h * halves + half) * nt;
     const int w0 = g0 / per, w1 = (g0 + nt - 1) / per;
     if (w0 == w1) continue;                // one wave saw the whole pair and wrote `out` itself
+    // With the in-workgroup merge only the first wave of the pair and the first wave of every
+    // later workgroup it reaches have written a slot; a pair inside one workgroup is done.
+    const int wstep = p.wg_fold ? kWavesPerBlock : 1;
+    if (p.wg_fold && w0 / kWavesPerBlock == w1 / kWavesPerBlock) continue;
+    const int wsecond = p.wg_fold ? (w0 / kWavesPerBlock + 1) * kWavesPerBlock : w0 + 1;
     const int k = min(kWideRows, ktot - kWideRows * half);
     for (int j = threadIdx.x / lanes_per_row; j < k; j += WideCombine<D>::rows_per_pass) {
         auto slot_row = [&](int w) -> const float* {
@@ -456,10 +544,14 @@ __global__ __launch_bounds__(WideCombine<D>::threads) void combine_wide_partials
             den = den * a + l * b;
             M = Mn;
         };
-        int w = w0;
-        for (; w + 1 <= w1; w += 2) {
+        {
+            const float* s0 = slot_row(w0);
+            fold(s0[D], s0[D + 1], *reinterpret_cast<const f32x4*>(s0 + c4));
+        }
+        int w = wsecond;
+        for (; w + wstep <= w1; w += 2 * wstep) {
             const float* s0 = slot_row(w);
-            const float* s1 = slot_row(w + 1);
+            const float* s1 = slot_row(w + wstep);
             const float m0 = s0[D], l0 = s0[D + 1], m1 = s1[D], l1 = s1[D + 1];
             const f32x4 v0 = *reinterpret_cast<const f32x4*>(s0 + c4);
             const f32x4 v1 = *reinterpret_cast<const f32x4*>(s1 + c4);
@@ -487,12 +579,16 @@ __global__ __launch_bounds__(WideCombine<D>::threads) void combine_wide_partials
 template <typename ET, int D>
 static hipError_t launch_wide_typed(const AttnParams& p, int blocks, hipStream_t stream,
                                     hipEvent_t ev_start, hipEvent_t ev_stop) {
-    // tile prefix sums + the waves' Q^T stores (4 x 8 KiB at D = 128): may exceed the 64 KiB a
-    // kernel gets by default on some HIP platforms, so ask for the device's 160 KiB
-    const size_t lds = ((((size_t)(p.B + 1) * sizeof(int32_t)) + 15) & ~(size_t)15) +
-                       (size_t)kWavesPerBlock * kWideBlocks * TileRegs<D>::KS * kWave * sizeof(u32x4);
+    // tile prefix sums (at most 32 KiB) + the waves' Q^T stores (4 x 8 KiB at D = 128) + with the
+    // in-workgroup merge three parked partials of two blocks (51 KiB at D = 128): above the
+    // 64 KiB a kernel gets by default on some HIP platforms, so ask for the device's 160 KiB
+    size_t lds = ((((size_t)(p.B + 1) * sizeof(int32_t)) + 15) & ~(size_t)15) +
+                 (size_t)kWavesPerBlock * kWideBlocks * TileRegs<D>::KS * kWave * sizeof(u32x4);
+    if (p.wg_fold)
+        lds += (size_t)(kWavesPerBlock - 1) * kWideBlocks * FoldSlot<D>::floats * sizeof(float) +
+               kWavesPerBlock * sizeof(int32_t);
     hipError_t e;
-    if (lds > 64 * 1024) {        // (only the very largest batches)
+    if (lds > 64 * 1024) {
         static std::atomic<uint64_t> raised{0};
         e = allow_max_lds(reinterpret_cast<const void*>(&verify_attention_wide_kernel<ET, D>), raised);
         if (e != hipSuccess) return e;

@@ -60,13 +60,16 @@ def test_random_shape(seed):
     check_accept_and_append(t, use_logits=False, n_layers=2)
 
 
-@pytest.mark.parametrize("seed", range(200, 216))
+@pytest.mark.parametrize("seed", list(range(200, 216)) + [(s, 64) for s in range(300, 312)])
 def test_random_shape_with_a_loose_length_bound(seed):
     """max_kv_len is only a bound; a loose one makes the library size the launch for far more
     tiles than there are (1024 waves, most of them with one tile or none) and switches on the
     in-workgroup merge of partials that it keeps off for short walks: every pair is then cut
     over many waves and workgroups.  The outputs must not change beyond rounding."""
-    b = random_case(seed, 16)
+    k_hi = 16
+    if isinstance(seed, tuple):         # up to 64 rows per sample: the wide kernel, two pairs per head
+        seed, k_hi = seed
+    b = random_case(seed, k_hi)
     loose = 32 * (-(-14000 // (b.B * b.H)) + 1)
     print("case", seed, "B", b.B, "H", b.H, "D", b.D, b.dtype, b.layout, "kv", b.kv_len.tolist(),
           "k", np.diff(b.cu_seqlens.numpy()).tolist(), "bound", loose, flush=True)

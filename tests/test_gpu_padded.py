@@ -63,6 +63,25 @@ def test_padded_attention_matches_its_oracle_and_the_unpadded_path(case, layout)
     assert np.abs(got_unpad - got_pad[real]).max() <= 4e-3
 
 
+def test_padded_ranges_of_nothing_but_padding_through_the_in_workgroup_merge():
+    """Left-padded caches of very different lengths, large enough for the library to merge the
+    partials of a workgroup's waves in LDS: whole waves see only padding keys (running max
+    -inf, sum 0), as the first, a middle or the last part of a pair."""
+    kv_len = [6000, 100, 3000, 0, 50, 2000, 10, 4000]
+    k = [2, 5, 1, 3, 4, 2, 1, 6]
+    b = make_batch(kv_len, k, H=8, D=64, dtype=torch.bfloat16, seed=97, capacity=6100)
+    p = pad_batch(b, interleave=False, extra_pad=200)
+    assert b.B * b.H * ((p.l_pad + 31) // 32 + 1) >= 12 * 1024      # the size from which the merge is on
+    want_pad = oracle.padded_verify_attention(
+        bits(p.q_pad), bits(p.k_new_pad), bits(p.v_new_pad), bits(p.k_cache), bits(p.v_cache),
+        p.row_stride, p.head_stride, p.cap, p.key_mask.numpy(), p.k_valid.numpy(), p.k_max, p.l_pad,
+        p.H, p.D, p.scale, p.dtype)
+    got_pad = hip_padded_attention(padded_to_device(p), out_dtype=torch.float32).double().cpu().numpy()
+    real = p.real_rows.numpy()
+    assert np.isfinite(got_pad[real]).all()
+    assert np.abs(got_pad[real] - want_pad[real]).max() <= 2e-3
+
+
 def test_padded_append_matches_its_oracle():
     import paper_2405_07542_amd as ems
     n_layers = 3

@@ -12,8 +12,13 @@ from helpers import to_device
 pytestmark = pytest.mark.gpu
 
 
-def test_a_captured_step_replays_bit_identically():
-    b = to_device(make_config(2))
+@pytest.mark.parametrize("config,k_range", [(2, None), (3, None), (3, (17, 32))],
+                         ids=["config2", "config3-merge-in-lds", "config3-wide-kernel"])
+def test_a_captured_step_replays_bit_identically(config, k_range):
+    """config 2: short walks, every partial through the workspace; config 3: the in-workgroup
+    merge of partials (a barrier and LDS hand-over inside the kernel); 17..32 rows per sample:
+    the wide kernel, which asks for more than 64 KiB of LDS (raised at the eager warm-up call)."""
+    b = to_device(make_config(config, k_range=k_range))
     dev = b.q.device
     cache_k, cache_v = b.k_cache.clone(), b.v_cache.clone()
     cache = ems.kv_cache(cache_k, cache_v, b.row_stride, b.head_stride, b.rows)

@@ -25,7 +25,9 @@
  *     (the two debug validators and ems_profile_read do wait, as they say).  Work is
  *     enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the default
  *     stream) and the call returns at once.  Device arrays must stay alive until
- *     that work is done.  A sequence of calls can be captured into a HIP graph.
+ *     that work is done.  A sequence of calls can be captured into a HIP graph; make
+ *     the same calls once eagerly first (some kernels raise their LDS limit, a host-side
+ *     setting, at their first launch on a device).
  *   - Packed tensors q, k_new, v_new, out are [T, H, D], d fastest, no padding
  *     rows; sample i owns rows cu_seqlens[i] .. cu_seqlens[i+1]-1 (k_i rows).
  *     Row 0 of a sample is its last emitted token (whose K/V is not cached yet),

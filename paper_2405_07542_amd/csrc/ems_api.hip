@@ -76,11 +76,11 @@ int resident_attn_blocks() {
 }
 
 void accept_slicing(int T, int V, int* slices, int* slice_len) {
-    // enough blocks to fill the chip, slices a multiple of 8 columns, at least 2048 columns each;
-    // at most 8192 columns each when 16 slices allow it, so that a block of 256 threads covers
-    // its slice with one round of four 16-byte loads per thread
+    // enough blocks to fill the chip (about 2048), slices a multiple of 8 columns, at least 2048
+    // columns each.  No more slices than that: measured with 128256 columns, 16 slices of 8192
+    // (one round of loads per block) ran 150 us at 3008 rows where 1 to 4 slices ran 125 us,
+    // and with 50272 columns 1 to 7 slices are equal.
     int s = T > 0 ? (2048 + T - 1) / T : 1;
-    s = std::max(s, (V + 8191) / 8192);
     s = std::max(1, std::min(s, 16));
     int len = (V + s - 1) / s;
     len = std::max(2048, (len + 7) / 8 * 8);

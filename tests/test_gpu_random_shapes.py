@@ -12,7 +12,7 @@ import paper_2405_07542_amd as ems
 from workloads import HEAD_MAJOR, TOKEN_MAJOR, bits, grow_trees, make_batch
 from helpers import attention_tolerance, hip_attention, oracle_attention, to_device
 from test_gpu_parity import check_attention, run_accept_and_append
-from test_gpu_tree import check_accept_and_append, check_tree_attention
+from test_gpu_tree import check_accept_and_append, check_tree_attention, oracle_tree_attention
 
 pytestmark = pytest.mark.gpu
 
@@ -79,3 +79,30 @@ def test_random_shape_with_a_loose_length_bound(seed):
     assert np.isfinite(got).all()
     err = np.abs(got - want)
     assert (err <= attention_tolerance(b, want, torch.float32)).all(), err.max()
+
+    # the write-through variant and the tree call take the same route
+    dev = to_device(b)
+    kc, vc = dev.k_cache.clone(), dev.v_cache.clone()
+    out = torch.full((b.T, b.H, b.D), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, loose), dtype=torch.uint8, device="cuda")
+    ems.ems_verify_attention_write_through(dev.q, dev.k_new, dev.v_new,
+                                           ems.kv_cache(kc, vc, b.row_stride, b.head_stride, b.rows),
+                                           dev.cu_seqlens, dev.kv_start, dev.kv_len, out, max_k=b.max_k,
+                                           max_kv_len=loose, scale=b.scale, workspace=ws)
+    torch.cuda.synchronize()
+    assert (np.abs(out.double().cpu().numpy() - want) <= attention_tolerance(b, want, torch.float32)).all()
+    okc, ovc = bits(b.k_cache).copy(), bits(b.v_cache).copy()
+    oracle.kv_write_through(okc, ovc, b.row_stride, b.head_stride, bits(b.k_new), bits(b.v_new),
+                            b.cu_seqlens.numpy(), b.kv_start.numpy(), b.kv_len.numpy(), b.H, b.D)
+    assert np.array_equal(bits(kc), okc) and np.array_equal(bits(vc), ovc)
+
+    t = grow_trees(b, 5000 + seed, match_p=0.75, shape=["random", "wide", "star"][seed % 3])
+    td = to_device(t)
+    out = torch.full((t.T, t.H, t.D), float("nan"), dtype=torch.float32, device="cuda")
+    ems.ems_tree_verify_attention(td.q, td.k_new, td.v_new,
+                                  ems.kv_cache(td.k_cache, td.v_cache, t.row_stride, t.head_stride, t.rows),
+                                  td.cu_seqlens, td.parent, td.kv_start, td.kv_len, out, max_k=t.max_k,
+                                  max_kv_len=loose, scale=t.scale, workspace=ws)
+    torch.cuda.synchronize()
+    want_tree = oracle_tree_attention(t)
+    assert (np.abs(out.double().cpu().numpy() - want_tree) <= attention_tolerance(t, want_tree, torch.float32)).all()

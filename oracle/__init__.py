@@ -42,7 +42,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        # (tests/test_oracle_mutants.py points this at a deliberately broken build of a COPY of
+        # the source, to show that the pins notice; nothing else sets it)
+        lib = ctypes.CDLL(os.environ.get("EMS_ORACLE_LIBRARY") or build())
         i32p = ctypes.POINTER(ctypes.c_int32)
         u16p = ctypes.POINTER(ctypes.c_uint16)
         f64p = ctypes.POINTER(ctypes.c_double)

@@ -26,7 +26,9 @@
  * literally (and as the inverse of Alg. 1), sentinel-filled arenas; for the tree functions: reduction to the
  * causal ones on a chain, causal attention along every root-to-row path, a dense
  * brute force with a matrix-closure mask, a per-node validity rule for acceptance,
- * a numpy gather for the append.  No function here is "parity unpinned".
+ * a numpy gather for the append; tests/test_oracle_mutants.py plants single mistakes in a
+ * copy of this file and checks that those pins notice each.  No function here is
+ * "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>

@@ -56,6 +56,14 @@ MUTANTS = [
     ("concatenation forgets the running total", ACC,
      "concatenated[total_input_token_nums + j] = padded_ids[(size_t)i * k_max + j];",
      "concatenated[j] = padded_ids[(size_t)i * k_max + j];", 0),
+    ("the highest index wins arg-max ties in fp32 logits", ACC,
+     "if (y > best) { best = y; arg = v; }", "if (y >= best) { best = y; arg = v; }", 1),
+    ("Alg. 2 stops one sample early on a boundary row", ACC,
+     "while (i < B && pos >= token_nums_per_sample[i]) {", "while (i < B && pos > token_nums_per_sample[i]) {", 0),
+    ("write-through leaves out the last new row", ACC,
+     "for (int j = 0; j < k; ++j)\n            for (int h = 0; h < H; ++h)", "for (int j = 0; j < k - 1; ++j)\n            for (int h = 0; h < H; ++h)", 0),
+    ("bf16 is widened as if it were fp16", ATT, "if (dtype == ORACLE_BF16) {", "if (dtype == 7) {", 0),
+    ("fp16 subnormals lose their scale", ACC, "int expo = (bits >> 10) & 0x1f;", "int expo = ((bits >> 10) & 0x1f) | 1;", 0),
     ("tree: a row sees only its parent, not all ancestors", TREE,
      "for (int u = j; u >= 0; u = parent[cu[i] + u]) mask[L + u] = 1;",
      "mask[L + j] = 1; if (j > 0) mask[L + parent[cu[i] + j]] = 1;", 0),

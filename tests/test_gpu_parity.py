@@ -61,6 +61,11 @@ def test_one_very_long_cache_merged_from_a_thousand_partials():
     it, so its rows are merged from ~1000 partials; byte offsets inside the sample reach 150 MB."""
     b = make_batch([300000], [5], H=1, D=128, dtype=torch.bfloat16, seed=77)
     check_attention(b, out_dtype=torch.float32, label="L=300000")
+    # the same with a looser length bound, from which the library merges the partials of each
+    # workgroup's four waves in LDS and writes 256 partials instead of 1024
+    want = oracle_attention(b)
+    got = hip_attention(to_device(b), out_dtype=torch.float32, max_kv_len=400000).double().cpu().numpy()
+    assert np.abs(got - want).max() <= 2e-3
 
 
 def test_degenerate_batches():

@@ -86,8 +86,10 @@ typedef struct {
     int64_t rows;        /* R */
 } ems_kv_cache;
 
-/* Bytes of device workspace ems_verify_attention needs for these bounds
- * (split-KV partial results).  Never 0.  Pure host arithmetic. */
+/* Bytes of device workspace ems_verify_attention needs for these bounds on the current
+ * device (split-KV partial results: two slots per wave, one workgroup per compute unit;
+ * sized for 256 units when no device is present).  Never 0.  Host-side only: no device
+ * memory is touched and nothing is enqueued. */
 EMS_API size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len);
 
 /*

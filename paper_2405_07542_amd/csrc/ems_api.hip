@@ -119,8 +119,9 @@ ems_status ems_device_memory_figures(int* memory_clock_khz, int* memory_bus_widt
 size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len) {
     (void)T;
     if (B < 1 || H < 1 || D < 1 || max_kv_len < 0) return 256;
-    // (sized for the larger of the two launch shapes: max_k is not known here)
-    const int blocks = attn_blocks_for(tile_upper_bound(B, H, max_kv_len, true), kMaxAttnBlocks);
+    // (sized for the larger of the two launch shapes: max_k is not known here; one workgroup per
+    // CU of the current device, as the launch itself is sized, or 256 when there is no device)
+    const int blocks = attn_blocks_for(tile_upper_bound(B, H, max_kv_len, true), resident_attn_blocks());
     return std::max<size_t>(256, attn_ws_bytes_for(blocks, B, D, true));
 }
 

@@ -81,6 +81,10 @@ void accept_slicing(int T, int V, int* slices, int* slice_len) {
     // (one round of loads per block) ran 150 us at 3008 rows where 1 to 4 slices ran 125 us,
     // and with 50272 columns 1 to 7 slices are equal.
     int s = T > 0 ? (2048 + T - 1) / T : 1;
+    // ... except that a few more are taken when they make a slice fit one round of four 16-byte
+    // loads per thread (8192 columns): 7 instead of 6 at 384 rows of 50272 columns, 9.7 vs 10.8 us
+    const int one_round = (V + 8191) / 8192;
+    if (one_round > s && one_round <= s + s / 2 + 1) s = one_round;
     s = std::max(1, std::min(s, 16));
     int len = (V + s - 1) / s;
     len = std::max(2048, (len + 7) / 8 * 8);
@@ -587,7 +591,9 @@ ems_status ems_stream_read_probe(const void* buf, size_t bytes, void* sink, void
     if (!aligned16(buf) || (reinterpret_cast<uintptr_t>(sink) & 3) != 0)
         return fail(EMS_ERR_INVALID_ARG, "buf must be 16-byte aligned, sink 4-byte aligned");
     if (bytes < 1024) return fail(EMS_ERR_INVALID_ARG, "bytes = %zu is less than one 1 KiB line", bytes);
-    hipError_t e = ems::launch_stream_read(buf, bytes, static_cast<uint32_t*>(sink), 8 * resident_attn_blocks(),
+    // one workgroup of four waves per CU, the attention kernel's own launch shape: measured 7.1 TB/s
+    // where 2, 4 and 8 workgroups per CU gave 7.0, 6.9 and 6.7
+    hipError_t e = ems::launch_stream_read(buf, bytes, static_cast<uint32_t*>(sink), resident_attn_blocks(),
                                            static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return hip_fail("stream probe launch", e);
     return EMS_OK;

@@ -16,7 +16,8 @@
  *                            accepted count (Sec. 3.2, Fig. 2 / Table 1)
  * plus the padded "vanilla" method of Sec. 3.1 as an ablation in the same library, the
  * paper-order variant of steps 1 and 3 (write-through, then advance), the same three steps
- * for token trees (ems_tree_*), two debug validators and three measurement aids.
+ * for token trees (ems_tree_*), ems_pack_tokens (Alg. 1), two debug validators and four
+ * measurement aids.
  *
  * Conventions shared by every entry point
  *   - Pointers named *device* point to GPU memory owned by the caller; pointers

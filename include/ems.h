@@ -67,7 +67,7 @@ typedef enum { EMS_F16 = 0, EMS_BF16 = 1, EMS_F32 = 2 /* attention outputs and l
 
 #define EMS_MAX_QUERY_ROWS 64   /* largest k_i (rows per sample per step) */
 #define EMS_ROWS_PER_GROUP 16   /* with max_k up to this, the attention calls use the 16-row kernel; above
-                                   it a wider one that streams a sample's cache once per 32 of its rows */
+                                   it a wider one that holds 32 or all 64 rows of a (sample, head) pair */
 #define EMS_MAX_LAYERS_PER_CALL 32
 
 /*
@@ -107,10 +107,12 @@ EMS_API size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max
  *   kv_start, kv_len  : device int32 [B]     cache      : host struct, device arenas
  *   max_k      >= every k_i   (<= EMS_MAX_QUERY_ROWS).  It also selects the kernel: up to
  *                 EMS_ROWS_PER_GROUP, one that holds 16 rows per (sample, head) and streams
- *                 the sample's cache once per step; above it, one that holds 32 rows and
- *                 streams the cache once for rows 0..31 and once more for rows 32..63 of a
- *                 sample that has them.  A sample with more rows than max_k breaks the
- *                 contract (rows beyond 16, resp. 64, are left unwritten).
+ *                 the sample's cache once per step; up to 32, one that holds 32 rows; up to
+ *                 64, one that holds all 64 (half of them parked in LDS) and still streams
+ *                 the cache once -- unless the batch is so large (B above ~5000 at D = 128)
+ *                 that LDS has no room for that, in which case rows 0..31 and 32..63 of a
+ *                 sample stream the cache once each.  A sample with more rows than max_k
+ *                 breaks the contract (rows beyond 16, resp. 64, are left unwritten).
  *   max_kv_len >= every kv_len[i]            (host-known upper bounds)
  * Samples with k_i = 0 contribute nothing; kv_len[i] = 0 is legal; T = 0 is a no-op.
  * Errors: B<1, T<0, H<1, max_k<0, max_kv_len<0, NULL/misaligned pointer,

@@ -41,7 +41,12 @@ __device__ __forceinline__ int tiles_of_sample_wide(int k, int L) {
     k = min(k, kMaxRowsWide);
     return k > 0 ? wide_halves(k) * ((L + kTileKeys - 1) / kTileKeys + new_tiles(k)) : 0;
 }
-enum { kPlainLine = 0, kPaddedLine = 1, kWideLine = 2 };
+// ... or, when the wave keeps all four blocks of 16 rows (two of them parked in LDS), one pair.
+__device__ __forceinline__ int tiles_of_sample_wide64(int k, int L) {
+    k = min(k, kMaxRowsWide);
+    return k > 0 ? ((L + kTileKeys - 1) / kTileKeys + new_tiles(k)) : 0;
+}
+enum { kPlainLine = 0, kPaddedLine = 1, kWideLine = 2, kWide64Line = 3 };
 
 // prefix[i] = H * sum_{j<i} tiles(j), i = 0..B, built by the whole block in LDS.
 template <int LINE>
@@ -50,6 +55,7 @@ __device__ __forceinline__ void build_tile_prefix(const AttnParams& p, int32_t* 
     for (int i = tid; i < p.B; i += blockDim.x)
         prefix[i + 1] = LINE == kPaddedLine ? p.H * tiles_of_sample(p.k_max, p.l_pad)
                         : LINE == kWideLine ? p.H * tiles_of_sample_wide(p.cu[i + 1] - p.cu[i], p.kv_len[i])
+                        : LINE == kWide64Line ? p.H * tiles_of_sample_wide64(p.cu[i + 1] - p.cu[i], p.kv_len[i])
                                             : p.H * tiles_of_sample(p.cu[i + 1] - p.cu[i], p.kv_len[i]);
     if (tid == 0) prefix[0] = 0;
     __syncthreads();

@@ -38,11 +38,18 @@ constexpr int kMinTilesPerWave = 4;
 constexpr int kMaxAttnBlocks = 1024;
 constexpr int kMaxB = 8192;
 
-// Upper bound of the number of 32-key tiles of the whole batch (host-known bounds only); a
-// sample of up to 64 rows is up to two pairs per head, each with up to two tiles of new tokens.
-int64_t tile_upper_bound(int B, int H, int max_kv_len, bool wide) {
+// The three launch shapes of the attention call: up to 16 rows per (sample, head) pair; up to 32
+// (the wide kernel; a sample of more rows is two pairs per head); up to 64 (the wide kernel
+// with two of a pair's four blocks parked in LDS, while LDS has room for that).
+enum AttnShape { kRows16 = 0, kRows32 = 1, kRows64 = 2 };
+int rows_per_slot(AttnShape shape) { return 16 << shape; }
+
+// Upper bound of the number of 32-key tiles of the whole batch (host-known bounds only); with
+// more than 32 rows a sample has two tiles of new tokens and, as two pairs per head, all tiles twice.
+int64_t tile_upper_bound(int B, int H, int max_kv_len, AttnShape shape, int max_k) {
     const int64_t cache_tiles = (max_kv_len + kTileKeys - 1) / kTileKeys;
-    return (int64_t)B * H * (wide ? 2 * (cache_tiles + 2) : cache_tiles + 1);
+    const int64_t per_pair = cache_tiles + (max_k > 32 ? 2 : 1);
+    return (int64_t)B * H * (shape == kRows32 && max_k > 32 ? 2 * per_pair : per_pair);
 }
 
 int attn_blocks_for(int64_t tiles, int max_blocks) {
@@ -53,10 +60,10 @@ int attn_blocks_for(int64_t tiles, int max_blocks) {
 // Workspace = header (the B+1 tile prefix sums, padded to 256 B) + partial slots.
 size_t attn_ws_header_bytes(int B) { return ((size_t)(B + 1) * sizeof(int32_t) + 255) / 256 * 256; }
 
-// Two partial slots per wave, of 16 rows each, or of 32 in the wide kernel (max_k > 16).
-size_t attn_ws_bytes_for(int blocks, int B, int D, bool wide) {
+// Two partial slots per wave, of 16, 32 or 64 rows each.
+size_t attn_ws_bytes_for(int blocks, int B, int D, AttnShape shape) {
     return attn_ws_header_bytes(B) +
-           (size_t)2 * blocks * kWavesPerBlock * (wide ? 32 : 16) * (D + ems::kPartialPad) * sizeof(float);
+           (size_t)2 * blocks * kWavesPerBlock * rows_per_slot(shape) * (D + ems::kPartialPad) * sizeof(float);
 }
 
 // Workgroups launched for the attention kernel: one per CU, i.e. one wave per SIMD.  Two
@@ -123,10 +130,11 @@ ems_status ems_device_memory_figures(int* memory_clock_khz, int* memory_bus_widt
 size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len) {
     (void)T;
     if (B < 1 || H < 1 || D < 1 || max_kv_len < 0) return 256;
-    // (sized for the larger of the two launch shapes: max_k is not known here; one workgroup per
-    // CU of the current device, as the launch itself is sized, or 256 when there is no device)
-    const int blocks = attn_blocks_for(tile_upper_bound(B, H, max_kv_len, true), resident_attn_blocks());
-    return std::max<size_t>(256, attn_ws_bytes_for(blocks, B, D, true));
+    // (sized for the largest of the launch shapes, as max_k is not known here: the most tiles
+    // and the widest slots; one workgroup per CU of the current device, as the launch itself is
+    // sized, or 256 when there is no device)
+    const int blocks = attn_blocks_for(tile_upper_bound(B, H, max_kv_len, kRows32, 64), resident_attn_blocks());
+    return std::max<size_t>(256, attn_ws_bytes_for(blocks, B, D, kRows64));
 }
 
 }  // extern "C"
@@ -187,11 +195,12 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     // a sample's cache is addressed with 32-bit byte offsets from its first row
     if (((int64_t)max_kv_len + kTileKeys) * cache->row_stride * 2 >= ((int64_t)1 << 32))
         return fail(EMS_ERR_UNSUPPORTED, "max_kv_len * row_stride exceeds 4 GiB per sample");
-    const int64_t tiles = tile_upper_bound(B, H, max_kv_len, wide);
+    const AttnShape shape = !wide ? kRows16 : (max_k > 32 && ems::wide_rows64_fits(B, D)) ? kRows64 : kRows32;
+    const int64_t tiles = tile_upper_bound(B, H, max_kv_len, shape, max_k);
     if (tiles >= ((int64_t)1 << 31)) return fail(EMS_ERR_UNSUPPORTED, "too many key tiles");
 
     const int blocks = attn_blocks_for(tiles, resident_attn_blocks());
-    const size_t need = attn_ws_bytes_for(blocks, B, D, wide);
+    const size_t need = attn_ws_bytes_for(blocks, B, D, shape);
     if (!workspace || workspace_bytes < need)
         return fail(EMS_ERR_WORKSPACE, "attention workspace of %zu bytes needed, %zu given", need,
                     workspace ? workspace_bytes : (size_t)0);
@@ -219,7 +228,7 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     p.num_waves = blocks * kWavesPerBlock;
     p.scale_log2 = scale * 1.4426950408889634f;
     p.write_through = write_through ? 1 : 0;
-    p.multi = wide ? 1 : 0;
+    p.multi = (int)shape;
     // The in-workgroup merge of partials saves HBM writes in the middle of the read stream and
     // costs a barrier and a fold at the end of the walk (~1 us): measured break-even at ~13 tiles
     // per wave (B = 16, 1024 cached tokens), a loss of 1.5 us at 6, gains from 25 on.

@@ -31,7 +31,8 @@ struct AttnParams {
     int num_waves;
     float scale_log2;          // scale * log2(e)
     int write_through;         // also store the new rows' K/V at cache rows kv_len + j (paper order)
-    int multi;                 // samples may bring more than 16 rows (up to 64): the wide kernel
+    int multi;                 // samples may bring more than 16 rows (up to 64): the wide kernel; 2 = the wave
+                               // keeps all 64 rows of a pair (four blocks, two parked in LDS), 1 = pairs of 32 rows
     int wg_fold;               // the matrix-core kernels: partials shared inside a workgroup are merged
                                // in LDS, only a workgroup's first wave (and a pair's first) writes a slot
                                // (set by the host for all but very short walks; ignored by the others)
@@ -54,8 +55,10 @@ hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool 
                                    bool valu, hipStream_t stream, hipEvent_t ev_start,
                                    hipEvent_t ev_stop);
 
-// The same for samples of up to 64 rows (p.multi): pairs of up to 32 rows (two blocks of 16 per wave),
-// partial slots of 32 rows.
+// The same for samples of up to 64 rows (p.multi = 1: pairs of up to 32 rows, two blocks of 16 per
+// wave, partial slots of 32 rows; p.multi = 2: pairs of up to 64 rows, partial slots of 64 rows).
+// wide_rows64_fits: whether LDS can hold p.multi = 2 at this batch size.
+bool wide_rows64_fits(int B, int D);
 hipError_t launch_verify_attention_wide(const AttnParams& p, int blocks, int D, bool bf16,
                                         hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 

@@ -10,8 +10,13 @@
 //     stream -- were tried: the allocator runs out of the 256 non-accumulator registers and
 //     spills, and both ways out, one tile buffer instead of two or spilling, were slower than
 //     two streams of two blocks.)
-//   * a sample with more than 32 rows becomes two pairs per head, (sample, head, half), rows
-//     0..31 and 32..63, each streaming the cache once;
+//   * a sample with more than 32 rows: (NB = 4, the default above 32 rows) the wave keeps the
+//     state of all four blocks, two of them in registers and two parked in wave-private LDS,
+//     and per tile runs the two resident blocks, swaps the two pairs (16 LDS reads and writes
+//     per lane) and runs the other two on the same tile registers, so the cache is still
+//     streamed once; the pair that ran last stays resident for the next tile.  (NB = 2, used
+//     when LDS cannot hold the parked states -- very large batches -- : two pairs per head,
+//     (sample, head, half), rows 0..31 and 32..63, each streaming the cache once.)
 //   * a sample's new tokens take ceil(k/32) tiles after the cache tiles; the visible set of
 //     a row among the new rows is a 64-bit set (a causal prefix, or the row's ancestors in
 //     a token tree), of which every new-token tile uses its 32 bits (the first half never
@@ -19,16 +24,21 @@
 //   * the Q rows of the next pair are loaded at the switch (no prefetch);
 //   * partials that the waves of a workgroup share are merged in LDS as in the 16-row
 //     kernel (32 rows of them: at 32 rows per sample the workspace would otherwise take
-//     34 MB of writes in the middle of the read stream).
+//     34 MB of writes in the middle of the read stream); not with NB = 4, where LDS is taken.
 
 #include "attention_tiles.h"
 
 namespace ems {
 
-constexpr int kWideBlocks = 2;                             // blocks of 16 rows per pair
-constexpr int kWideRows = kWideBlocks * kMaxRows;          // 32 rows per pair
+constexpr int kWideBlocks = 2;                             // blocks of 16 rows resident in registers
+constexpr int kWideRows = kWideBlocks * kMaxRows;          // 32 rows: a pair with NB = 2, half the rows a pair may have with NB = 4
+
+// NB = blocks of 16 rows a pair may have: 2 (a sample of more than 32 rows is two pairs per
+// head) or 4 (one pair per head; two blocks resident, two parked in LDS).
+template <int NB> __device__ __forceinline__ int halves_of(int ktot) { return NB == 4 ? 1 : wide_halves(ktot); }
 
 // One (sample, head, half) pair's share of a wave's tile range (wave-uniform).
+template <int NB>
 struct WideSegment {
     int i, h, half;      // sample, head, which 32 rows of the sample
     int cu_i, ktot, k;   // first packed row of the sample; its rows (<= 64); rows of this pair (<= 32)
@@ -42,14 +52,14 @@ struct WideSegment {
     __device__ __forceinline__ int row0() const { return kWideRows * half; }   // first row of the pair in the sample
     __device__ __forceinline__ void set_half(int hf) {
         half = hf;
-        k = min(kWideRows, ktot - kWideRows * hf);
+        k = min(NB * kMaxRows, ktot - kWideRows * hf);
     }
 };
 
-template <int D>
-__device__ __forceinline__ WideSegment make_wide_segment(const AttnParams& p, const int32_t* prefix, int i,
-                                                         int gpos, int gend) {
-    WideSegment s;
+template <int D, int NB>
+__device__ __forceinline__ WideSegment<NB> make_wide_segment(const AttnParams& p, const int32_t* prefix, int i,
+                                                             int gpos, int gend) {
+    WideSegment<NB> s;
     while (uniform(prefix[i + 1]) <= gpos) ++i;
     s.i = i;
     s.cu_i = uniform(p.cu[i]);
@@ -59,7 +69,7 @@ __device__ __forceinline__ WideSegment make_wide_segment(const AttnParams& p, co
     const int nt = s.nt();
     const int rem = gpos - uniform(prefix[i]);
     const int pair = uniform(rem / nt);            // pair of this sample: head-major, then half
-    const int halves = wide_halves(s.ktot);
+    const int halves = halves_of<NB>(s.ktot);
     s.h = uniform(pair / halves);
     s.set_half(pair - s.h * halves);
     s.t0 = rem - pair * nt;
@@ -69,18 +79,18 @@ __device__ __forceinline__ WideSegment make_wide_segment(const AttnParams& p, co
     return s;
 }
 
-template <int D>
-__device__ __forceinline__ WideSegment next_wide_segment(const AttnParams& p, const int32_t* prefix,
-                                                         const WideSegment& c, int gpos, int gend) {
-    if (c.half + 1 < wide_halves(c.ktot)) {        // second half of the same (sample, head)
-        WideSegment s = c;
+template <int D, int NB>
+__device__ __forceinline__ WideSegment<NB> next_wide_segment(const AttnParams& p, const int32_t* prefix,
+                                                             const WideSegment<NB>& c, int gpos, int gend) {
+    if (c.half + 1 < halves_of<NB>(c.ktot)) {      // second half of the same (sample, head)
+        WideSegment<NB> s = c;
         s.set_half(c.half + 1);
         s.t0 = 0;
         s.t1 = min(c.nt(), gend - gpos);
         return s;
     }
-    if (c.h + 1 >= p.H) return make_wide_segment<D>(p, prefix, c.i + 1, gpos, gend);
-    WideSegment s = c;
+    if (c.h + 1 >= p.H) return make_wide_segment<D, NB>(p, prefix, c.i + 1, gpos, gend);
+    WideSegment<NB> s = c;
     s.h = c.h + 1;
     s.set_half(0);
     s.t0 = 0;
@@ -193,15 +203,28 @@ __device__ __forceinline__ void compute_tile_wide(const TileRegs<D>& t, const u3
     }
 }
 
-constexpr int kWideSlotRows = kWideRows;        // rows of one partial slot
+// LDS of the wide kernel after the tile prefix sums: the waves' Q^T stores (NB blocks each), then
+// NB = 2: the parked partials of waves 1..3 for the in-workgroup merge and a word of flags per
+// wave; NB = 4: every wave's two parked blocks.
+template <int D, int NB> constexpr size_t wide_q_lds_bytes() {
+    return (size_t)kWavesPerBlock * NB * TileRegs<D>::KS * kWave * sizeof(u32x4);
+}
+template <int D> constexpr size_t wide_fold_lds_bytes() {
+    return (size_t)(kWavesPerBlock - 1) * kWideBlocks * FoldSlot<D>::floats * sizeof(float) + kWavesPerBlock * sizeof(int32_t);
+}
+template <int D> constexpr size_t wide_swap_lds_bytes() {
+    return (size_t)kWavesPerBlock * kWideBlocks * FoldSlot<D>::floats * sizeof(float);
+}
 
-template <typename ET, int D>
+template <typename ET, int D, int NB>
 __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(AttnParams p) {
     extern __shared__ int32_t prefix[];
     constexpr int KS = TileRegs<D>::KS;
     constexpr int VW = TileRegs<D>::VW;
+    constexpr int kSlotRows = NB * kMaxRows;      // rows of one partial slot
     typedef TileRegs<D> TR;
-    build_tile_prefix<kWideLine>(p, prefix);
+    typedef WideSegment<NB> Seg;
+    build_tile_prefix<NB == 4 ? kWide64Line : kWideLine>(p, prefix);
     if (blockIdx.x == 0)       // the merge kernel reads the tile prefix from the workspace header
         for (int i = threadIdx.x; i <= p.B; i += blockDim.x) p.ws_header[i] = prefix[i];
     const int total = prefix[p.B];
@@ -217,9 +240,11 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
     // this wave parked the partial of the pair it continues, bit 1 = that pair ends in its range.
     const int lw = uniform((int)(threadIdx.x >> 6));
     char* const lds_after_prefix = reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15);
-    float* const fold_lds = reinterpret_cast<float*>(lds_after_prefix + kWavesPerBlock * kWideBlocks * KS * kWave * sizeof(u32x4));
+    float* const fold_lds = reinterpret_cast<float*>(lds_after_prefix + wide_q_lds_bytes<D, NB>());
     int32_t* const fold_flags = reinterpret_cast<int32_t*>(fold_lds + (kWavesPerBlock - 1) * kWideBlocks * FoldSlot<D>::floats);
-    const bool wg_fold = p.wg_fold != 0;               // (the host leaves it off for very short walks)
+    const bool wg_fold = NB == 2 && p.wg_fold != 0;    // (the host leaves it off for very short walks)
+    // NB = 4: this wave's two parked blocks, in the same place (this lane's words)
+    float* const swap_lds = fold_lds + lw * kWideBlocks * FoldSlot<D>::floats;
     if (wg_fold && lane == 0) fold_flags[lw] = 0;
     if (gbeg >= gend) {            // (only past the end of a short line) nothing to walk, nothing to merge
         if (wg_fold) __syncthreads();
@@ -234,25 +259,47 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
         if (prefix[mid] <= gbeg) lo = mid; else hi = mid;
     }
 
-    WideSegment cur = make_wide_segment<D>(p, prefix, uniform(lo), gbeg, gend);
+    Seg cur = make_wide_segment<D, NB>(p, prefix, uniform(lo), gbeg, gend);
     int cur_end = gbeg + (cur.t1 - cur.t0);
-    WideSegment nxt = cur;
-    if (cur_end < gend) nxt = next_wide_segment<D>(p, prefix, cur, cur_end, gend);
+    Seg nxt = cur;
+    if (cur_end < gend) nxt = next_wide_segment<D, NB>(p, prefix, cur, cur_end, gend);
 
     // Q^T of the pair's blocks as B operands of S^T = K Q^T: wave-private LDS, one 16-byte slot
     // per (block, k-step, lane)
-    u32x4* const q_lds = reinterpret_cast<u32x4*>(lds_after_prefix) + lw * (kWideBlocks * KS * kWave) + lane;
-    SoftmaxState<ET, D> st[kWideBlocks];
-    uint64_t vis[kWideBlocks];             // this lane's row of block b: visible new rows of the sample
+    u32x4* const q_lds = reinterpret_cast<u32x4*>(lds_after_prefix) + lw * (NB * KS * kWave) + lane;
+    SoftmaxState<ET, D> st[kWideBlocks];   // the two resident blocks: blocks 2*res and 2*res + 1 of the pair
+    uint64_t vis[NB];                      // this lane's row of block b: visible new rows of the sample
+    int res = 0;                           // NB = 4: which two blocks are resident (wave-uniform)
+
+    // NB = 4: exchange the resident blocks with the parked ones
+    auto swap_blocks = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < kWideBlocks; ++b) {
+            float* f = swap_lds + b * FoldSlot<D>::floats;
+#pragma unroll
+            for (int c = 0; c < VW; ++c) {
+                f32x4* at = reinterpret_cast<f32x4*>(f + (c * kWave + lane) * 4);
+                const f32x4 other = *at;
+                *at = st[b].acc[c];
+                st[b].acc[c] = other;
+            }
+            const float m = f[FoldSlot<D>::m_at + lane], l = f[FoldSlot<D>::l_at + lane];
+            f[FoldSlot<D>::m_at + lane] = st[b].m;
+            f[FoldSlot<D>::l_at + lane] = st[b].l;
+            st[b].m = m;
+            st[b].l = l;
+        }
+        res ^= 1;
+    };
 
     // Q rows, per-row state and visible sets of a pair, when it becomes current
-    auto begin_segment = [&](const WideSegment& s) __attribute__((always_inline)) {
+    auto begin_segment = [&](const Seg& s) __attribute__((always_inline)) {
         const uint64_t qaddr = uniform_addr(p.q + s.new_off);
         int par = -1;
         if (p.parent != nullptr)
             par = gload<int32_t>(uniform_addr(p.parent + s.cu_i), (uint32_t)min(lane, s.ktot - 1) * 4u);
 #pragma unroll
-        for (int b = 0; b < kWideBlocks; ++b) {
+        for (int b = 0; b < NB; ++b) {
             if (b < s.blocks()) {
                 const int row = min(s.row0() + kMaxRows * b + n, s.ktot - 1);   // rows beyond the last repeat it, zeroed below
                 const uint32_t qoff = (uint32_t)row * new_row_bytes;
@@ -269,11 +316,26 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
         }
 #pragma unroll
         for (int b = 0; b < kWideBlocks; ++b) {
-            if (b < s.blocks()) {
 #pragma unroll
-                for (int c = 0; c < VW; ++c) st[b].acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-                st[b].m = -INFINITY;
-                st[b].l = 0.f;
+            for (int c = 0; c < VW; ++c) st[b].acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+            st[b].m = -INFINITY;
+            st[b].l = 0.f;
+        }
+        res = 0;                           // blocks 0 and 1 are resident, blocks 2 and 3 (if any) start parked
+        if (NB == 4 && s.blocks() > kWideBlocks) {
+#pragma unroll
+            for (int b = 0; b < kWideBlocks; ++b) {
+                float* f = swap_lds + b * FoldSlot<D>::floats;
+#pragma unroll
+                for (int c = 0; c < VW; ++c)
+                    *reinterpret_cast<f32x4*>(f + (c * kWave + lane) * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+                f[FoldSlot<D>::m_at + lane] = -INFINITY;
+                f[FoldSlot<D>::l_at + lane] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (b < s.blocks()) {
                 // among the new rows a row sees itself and the rows before it; in a token tree,
                 // itself and its ancestors
                 const int row = min(s.row0() + kMaxRows * b + n, s.ktot - 1);
@@ -297,21 +359,40 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
         load_tile<D, false>(t, src, n, g);
     };
 
-    auto consume = [&](const TileRegs<D>& t, const WideSegment& s, int tile) __attribute__((always_inline)) {
-        const int nb = s.blocks();
+    // one tile against the two resident blocks (blocks 2*res and 2*res + 1 of the pair)
+    auto run_resident = [&](const TileRegs<D>& t, const Seg& s, int tile) __attribute__((always_inline)) {
+        const int nb = min(kWideBlocks, s.blocks() - kWideBlocks * res);
+        const u32x4* q = q_lds + res * (kWideBlocks * KS * kWave);
         if (tile < s.ntc()) {
             const int lim = s.L - tile * kTileKeys;
             if (lim >= kTileKeys)
-                compute_tile_wide<ET, D, false, false>(t, q_lds, st, nb, p.scale_log2, lim, nullptr, g);
+                compute_tile_wide<ET, D, false, false>(t, q, st, nb, p.scale_log2, lim, nullptr, g);
             else
-                compute_tile_wide<ET, D, true, false>(t, q_lds, st, nb, p.scale_log2, lim, nullptr, g);
+                compute_tile_wide<ET, D, true, false>(t, q, st, nb, p.scale_log2, lim, nullptr, g);
             return;
         }
         const int key0 = kTileKeys * (tile - s.ntc());                 // first new row of this tile
         uint32_t v32[kWideBlocks];
 #pragma unroll
-        for (int b = 0; b < kWideBlocks; ++b) v32[b] = (uint32_t)(vis[b] >> key0);
-        compute_tile_wide<ET, D, true, true>(t, q_lds, st, nb, p.scale_log2, 0, v32, g);
+        for (int b = 0; b < kWideBlocks; ++b) {
+            uint64_t v = vis[b];
+            if constexpr (NB == 4) v = res ? vis[kWideBlocks + b] : v;
+            v32[b] = (uint32_t)(v >> key0);
+        }
+        compute_tile_wide<ET, D, true, true>(t, q, st, nb, p.scale_log2, 0, v32, g);
+    };
+
+    auto consume = [&](const TileRegs<D>& t, const Seg& s, int tile) __attribute__((always_inline)) {
+        // NB = 4 and more than two blocks: the resident two, a swap, the other two on the same
+        // tile; those stay resident for the next tile
+        const int passes = (NB == 4 && s.blocks() > kWideBlocks) ? 2 : 1;
+#pragma unroll 1
+        for (int pass = 0; pass < passes; ++pass) {
+            if (pass) swap_blocks();
+            run_resident(t, s, tile);
+        }
+        if (tile < s.ntc()) return;
+        const int key0 = kTileKeys * (tile - s.ntc());
         if (p.write_through && s.half == 0) {      // (both halves read the new rows, one stores them)
             // Paper order (Sec. 3.2): the new rows' K/V go to the sample's own location, cache
             // rows kv_len + j, straight from the registers of this tile (new rows key0 .. key0+31).
@@ -338,13 +419,13 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
         }
     };
 
-    // the blocks' states normalised into out[cu_i + row0 + 16b + n, h, :]
-    auto write_out = [&](const WideSegment& s) __attribute__((always_inline)) {
+    // the resident blocks' states normalised into out[cu_i + row0 + 16 (2 res + b) + n, h, :]
+    auto write_out = [&](const Seg& s) __attribute__((always_inline)) {
 #pragma unroll
         for (int b = 0; b < kWideBlocks; ++b) {
-            if (b < s.blocks()) {
+            if (kWideBlocks * res + b < s.blocks()) {
                 const float l = quad_sum(st[b].l);     // the four lanes of a row hold disjoint shares
-                const int r_in_pair = kMaxRows * b + n;
+                const int r_in_pair = kMaxRows * (kWideBlocks * res + b) + n;
                 if (r_in_pair < s.k) {
                     const float inv = 1.0f / l;
                     const int64_t row = ((int64_t)(s.cu_i + s.row0() + r_in_pair) * p.H + s.h) * D;
@@ -372,18 +453,18 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
             }
         }
     };
-    // the blocks' states as a partial in the workspace: slot 2w holds one that continues a pair
-    // begun by an earlier wave, slot 2w+1 one that starts a pair and leaves its end to later
-    // waves; 32 rows per slot
-    auto write_partial = [&](const WideSegment& s) __attribute__((always_inline)) {
+    // the resident blocks' states as a partial in the workspace: slot 2w holds one that continues
+    // a pair begun by an earlier wave, slot 2w+1 one that starts a pair and leaves its end to
+    // later waves; 16 NB rows per slot
+    auto write_partial = [&](const Seg& s) __attribute__((always_inline)) {
         const int slot = 2 * wave + (s.t0 == 0 ? 1 : 0);
 #pragma unroll
         for (int b = 0; b < kWideBlocks; ++b) {
-            if (b < s.blocks()) {
+            if (kWideBlocks * res + b < s.blocks()) {
                 const float l = quad_sum(st[b].l);
-                const int r_in_pair = kMaxRows * b + n;
+                const int r_in_pair = kMaxRows * (kWideBlocks * res + b) + n;
                 if (r_in_pair < s.k) {
-                    float* dst = p.ws + ((int64_t)slot * kWideSlotRows + r_in_pair) * (D + kPartialPad);
+                    float* dst = p.ws + ((int64_t)slot * kSlotRows + r_in_pair) * (D + kPartialPad);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         if (4 * g + r >= TR::kVLanes) continue;
@@ -402,10 +483,17 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
         }
     };
 
-    auto finish_segment = [&](const WideSegment& s) __attribute__((always_inline)) {
+    auto finish_segment = [&](const Seg& s) __attribute__((always_inline)) {
         const bool continues = s.t0 != 0;          // an earlier wave holds the pair's first tiles
         const bool open = s.t1 != s.nt();          // later waves hold its last tiles (then this is the wave's last segment)
-        if (!continues && !open) {
+        if (NB == 4) {                             // the resident blocks, then the parked ones
+            const int passes = s.blocks() > kWideBlocks ? 2 : 1;
+#pragma unroll 1
+            for (int pass = 0; pass < passes; ++pass) {
+                if (pass) swap_blocks();
+                if (!continues && !open) write_out(s); else write_partial(s);
+            }
+        } else if (!continues && !open) {
             write_out(s);
         } else if (!wg_fold) {
             write_partial(s);                      // every wave's partials go to the workspace
@@ -446,7 +534,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
                 con_t = cur.t0;
                 cur_end = c + 1 + (cur.t1 - cur.t0);
                 begin_segment(cur);
-                if (cur_end < gend) nxt = next_wide_segment<D>(p, prefix, cur, cur_end, gend);
+                if (cur_end < gend) nxt = next_wide_segment<D, NB>(p, prefix, cur, cur_end, gend);
             }
         }
     };
@@ -495,16 +583,17 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
     }
 }
 
-// Merge of the partials of pairs shared by several waves, as in the 16-row kernels, with 32
-// rows per slot and up to two pairs per (sample, head).
+// Merge of the partials of pairs shared by several waves, as in the 16-row kernels, with 16 NB
+// rows per slot and, with NB = 2, up to two pairs per (sample, head).
 template <int D> struct WideCombine {
     static constexpr int lanes_per_row = D / 4;
     static constexpr int rows_per_pass = 8;
     static constexpr int threads = rows_per_pass * lanes_per_row;
 };
 
-template <typename ET, int D>
+template <typename ET, int D, int NB>
 __global__ __launch_bounds__(WideCombine<D>::threads) void combine_wide_partials_kernel(AttnParams p) {
+    constexpr int kSlotRows = NB * kMaxRows;
     const int i = blockIdx.y, h = blockIdx.x;
     const int cu_i = p.cu[i];
     const int ktot = min(kMaxRowsWide, p.cu[i + 1] - cu_i);
@@ -513,7 +602,7 @@ __global__ __launch_bounds__(WideCombine<D>::threads) void combine_wide_partials
     const int next = p.ws_header[i + 1];
     if (ktot <= 0) return;
     const int per = (total + p.num_waves - 1) / p.num_waves;
-    const int halves = wide_halves(ktot);
+    const int halves = halves_of<NB>(ktot);
     const int nt = (next - first) / (p.H * halves);
     constexpr int pitch = D + kPartialPad;
     constexpr int lanes_per_row = WideCombine<D>::lanes_per_row;
@@ -527,11 +616,11 @@ __global__ __launch_bounds__(WideCombine<D>::threads) void combine_wide_partials
     const int wstep = p.wg_fold ? kWavesPerBlock : 1;
     if (p.wg_fold && w0 / kWavesPerBlock == w1 / kWavesPerBlock) continue;
     const int wsecond = p.wg_fold ? (w0 / kWavesPerBlock + 1) * kWavesPerBlock : w0 + 1;
-    const int k = min(kWideRows, ktot - kWideRows * half);
+    const int k = min(kSlotRows, ktot - kWideRows * half);
     for (int j = threadIdx.x / lanes_per_row; j < k; j += WideCombine<D>::rows_per_pass) {
         auto slot_row = [&](int w) -> const float* {
             const int slot = 2 * w + (w == w0 ? 1 : 0);
-            return p.ws + ((int64_t)slot * kWideSlotRows + j) * pitch;
+            return p.ws + ((int64_t)slot * kSlotRows + j) * pitch;
         };
         float M = -INFINITY, den = 0.f;
         f32x4 num = {0.f, 0.f, 0.f, 0.f};
@@ -576,42 +665,62 @@ __global__ __launch_bounds__(WideCombine<D>::threads) void combine_wide_partials
     }
 }
 
-template <typename ET, int D>
-static hipError_t launch_wide_typed(const AttnParams& p, int blocks, hipStream_t stream,
+// LDS a launch needs; NB = 4 only fits while the tile prefix sums leave room (B up to a few thousand).
+template <int D, int NB> static size_t wide_lds_bytes(int B, bool wg_fold) {
+    size_t lds = ((((size_t)(B + 1) * sizeof(int32_t)) + 15) & ~(size_t)15) + wide_q_lds_bytes<D, NB>();
+    if (NB == 4) return lds + wide_swap_lds_bytes<D>();
+    return wg_fold ? lds + wide_fold_lds_bytes<D>() : lds;
+}
+
+template <typename ET, int D, int NB>
+static hipError_t launch_wide_typed(const AttnParams& params, int blocks, hipStream_t stream,
                                     hipEvent_t ev_start, hipEvent_t ev_stop) {
-    // tile prefix sums (at most 32 KiB) + the waves' Q^T stores (4 x 8 KiB at D = 128) + with the
-    // in-workgroup merge three parked partials of two blocks (51 KiB at D = 128): above the
-    // 64 KiB a kernel gets by default on some HIP platforms, so ask for the device's 160 KiB
-    size_t lds = ((((size_t)(p.B + 1) * sizeof(int32_t)) + 15) & ~(size_t)15) +
-                 (size_t)kWavesPerBlock * kWideBlocks * TileRegs<D>::KS * kWave * sizeof(u32x4);
-    if (p.wg_fold)
-        lds += (size_t)(kWavesPerBlock - 1) * kWideBlocks * FoldSlot<D>::floats * sizeof(float) +
-               kWavesPerBlock * sizeof(int32_t);
+    AttnParams p = params;
+    if (NB == 4) p.wg_fold = 0;        // LDS holds the parked blocks instead
+    // tile prefix sums (at most 32 KiB) + the waves' Q^T stores (4 x 8 KiB at D = 128 with NB = 2)
+    // + three parked partials of two blocks (51 KiB at D = 128) or, with NB = 4, twice the Q^T
+    // stores and every wave's two parked blocks (68 KiB): above the 64 KiB a kernel gets by
+    // default on some HIP platforms, so ask for the device's 160 KiB
+    const size_t lds = wide_lds_bytes<D, NB>(p.B, p.wg_fold != 0);
+    if (lds > (size_t)kMaxLdsBytes) return hipErrorInvalidValue;     // (the API layer picks NB = 2 first)
     hipError_t e;
     if (lds > 64 * 1024) {
         static std::atomic<uint64_t> raised{0};
-        e = allow_max_lds(reinterpret_cast<const void*>(&verify_attention_wide_kernel<ET, D>), raised);
+        e = allow_max_lds(reinterpret_cast<const void*>(&verify_attention_wide_kernel<ET, D, NB>), raised);
         if (e != hipSuccess) return e;
     }
     if (ev_start && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((verify_attention_wide_kernel<ET, D>), dim3(blocks), dim3(kAttnThreads), lds,
+    hipLaunchKernelGGL((verify_attention_wide_kernel<ET, D, NB>), dim3(blocks), dim3(kAttnThreads), lds,
                        stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((combine_wide_partials_kernel<ET, D>), dim3(p.H, p.B),
+    hipLaunchKernelGGL((combine_wide_partials_kernel<ET, D, NB>), dim3(p.H, p.B),
                        dim3(WideCombine<D>::threads), 0, stream, p);
     return hipGetLastError();
 }
 
+template <int NB>
+static hipError_t launch_wide_blocks(const AttnParams& p, int blocks, int D, bool bf16, hipStream_t stream,
+                                     hipEvent_t ev_start, hipEvent_t ev_stop) {
+    if (D == 128) return bf16 ? launch_wide_typed<BF16, 128, NB>(p, blocks, stream, ev_start, ev_stop)
+                              : launch_wide_typed<F16, 128, NB>(p, blocks, stream, ev_start, ev_stop);
+    if (D == 80) return bf16 ? launch_wide_typed<BF16, 80, NB>(p, blocks, stream, ev_start, ev_stop)
+                             : launch_wide_typed<F16, 80, NB>(p, blocks, stream, ev_start, ev_stop);
+    return bf16 ? launch_wide_typed<BF16, 64, NB>(p, blocks, stream, ev_start, ev_stop)
+                : launch_wide_typed<F16, 64, NB>(p, blocks, stream, ev_start, ev_stop);
+}
+
+bool wide_rows64_fits(int B, int D) {
+    const size_t lds = D == 128 ? wide_lds_bytes<128, 4>(B, false) : D == 80 ? wide_lds_bytes<80, 4>(B, false)
+                                                                               : wide_lds_bytes<64, 4>(B, false);
+    return lds <= (size_t)kMaxLdsBytes;
+}
+
 hipError_t launch_verify_attention_wide(const AttnParams& p, int blocks, int D, bool bf16,
                                         hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    if (D == 128) return bf16 ? launch_wide_typed<BF16, 128>(p, blocks, stream, ev_start, ev_stop)
-                              : launch_wide_typed<F16, 128>(p, blocks, stream, ev_start, ev_stop);
-    if (D == 80) return bf16 ? launch_wide_typed<BF16, 80>(p, blocks, stream, ev_start, ev_stop)
-                             : launch_wide_typed<F16, 80>(p, blocks, stream, ev_start, ev_stop);
-    return bf16 ? launch_wide_typed<BF16, 64>(p, blocks, stream, ev_start, ev_stop)
-                : launch_wide_typed<F16, 64>(p, blocks, stream, ev_start, ev_stop);
+    return p.multi == 2 ? launch_wide_blocks<4>(p, blocks, D, bf16, stream, ev_start, ev_stop)
+                        : launch_wide_blocks<2>(p, blocks, D, bf16, stream, ev_start, ev_stop);
 }
 
 }  // namespace ems

@@ -102,17 +102,38 @@ def test_limits_of_the_other_variants():
     assert e.value.status == ems.EMS_ERR_UNSUPPORTED
 
 
-def test_maximum_batch_size_through_the_wide_kernel():
-    """B = 8192 with a few samples of more than 16 rows: 32 KiB of tile prefix sums plus the
-    waves' Q^T stores (32 KiB at D = 128) is the most LDS the wide kernel ever asks for."""
-    rng = np.random.default_rng(159)
-    B = 8192
+@pytest.mark.parametrize("B,dtype,D,layout", [(8192, torch.bfloat16, 128, TOKEN_MAJOR), (8192, torch.float16, 80, HEAD_MAJOR),
+                                               (7000, torch.float16, 128, HEAD_MAJOR), (5000, torch.bfloat16, 128, TOKEN_MAJOR)])
+def test_very_large_batches_through_the_wide_kernel(B, dtype, D, layout):
+    """Thousands of samples, a few of them with more than 16 rows.  With 33..64 rows the wave keeps
+    all rows of a pair while LDS has room for its parked blocks beside the tile prefix sums
+    (B = 5000 at D = 128: 152 KiB); beyond that (B = 7000, 8192) the library falls back to two
+    pairs of 32 rows per head, which these cases are here to cover: causal, tree and
+    write-through."""
+    rng = np.random.default_rng(159 + B)
     kv = rng.integers(0, 41, B).tolist()
     k = rng.integers(0, 4, B).tolist()
     for i in rng.choice(B, 40, replace=False):
         k[i] = int(rng.integers(17, 65))
     k[0], k[-1] = 64, 33
-    b = make_batch(kv, k, H=1, D=128, dtype=torch.bfloat16, seed=160, capacity=112)
+    b = make_batch(kv, k, H=1, D=D, dtype=dtype, seed=160, capacity=112, layout=layout, vocab_for_ids=9,
+                   match_p=0.8)
     assert b.max_k == 64
-    check_attention(b, out_dtype=torch.float32, label="wide, B=8192")
+    check_attention(b, out_dtype=torch.float32, label="wide, B=%d" % B)
     run_accept_and_append(b)
+    t = grow_trees(b, 161, match_p=0.8, shape="random")
+    check_tree_attention(t, out_dtype=torch.float32)
+    dev = to_device(b)
+    kc, vc = dev.k_cache.clone(), dev.v_cache.clone()
+    out = torch.full((b.T, b.H, b.D), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len), dtype=torch.uint8, device="cuda")
+    ems.ems_verify_attention_write_through(dev.q, dev.k_new, dev.v_new,
+                                           ems.kv_cache(kc, vc, b.row_stride, b.head_stride, b.rows),
+                                           dev.cu_seqlens, dev.kv_start, dev.kv_len, out, max_k=b.max_k,
+                                           max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.abs(out.double().cpu().numpy() - oracle_attention(b)).max() <= 2e-3
+    okc, ovc = bits(b.k_cache).copy(), bits(b.v_cache).copy()
+    oracle.kv_write_through(okc, ovc, b.row_stride, b.head_stride, bits(b.k_new), bits(b.v_new),
+                            b.cu_seqlens.numpy(), b.kv_start.numpy(), b.kv_len.numpy(), b.H, b.D)
+    assert np.array_equal(bits(kc), okc) and np.array_equal(bits(vc), ovc)

@@ -544,8 +544,8 @@ def sweep_variants(B=64, L=2048, ks=(1, 2, 4, 6, 8, 12, 16, 32, 64)):
     """The two formulations of the attention kernel on one HBM-bound shape (config 4's batch and
     mean cache length, every sample with the same k): kernel time from HIP events around the main
     kernel, and the algorithmic bandwidth it amounts to.  The matrix-core path costs the same for
-    any k <= 16, ~10 % more for 17..32 (the wider kernel) and twice that for 33..64 (the cache is streamed
-    once per 32 rows);
+    any k <= 16, ~10 % more for 17..32 (the wider kernel) and ~1.6x for 33..64 (still one stream of the
+    cache, but the wave is then bound by its own arithmetic);
     the vector-ALU path pays per row."""
     import torch
     import paper_2405_07542_amd as ems

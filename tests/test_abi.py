@@ -199,3 +199,16 @@ def test_pack_tokens_rejects_bad_arguments_on_the_host():
 
 def test_device_memory_figures_rejects_null_pointers():
     assert ems.lib().ems_device_memory_figures(None, None) == ems.EMS_ERR_INVALID_ARG
+
+
+def test_the_header_is_plain_c_and_the_library_is_usable_from_c(tmp_path):
+    """gcc -std=c11 -pedantic compiles a C program against include/ems.h; the program loads
+    libems.so with dlopen and calls host-only paths of the ABI (no Python, no C++, no GPU)."""
+    import subprocess
+    exe = str(tmp_path / "abi_from_c")
+    subprocess.check_call(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-D_GNU_SOURCE",
+                           "-I", os.path.join(ROOT, "include"), "-o", exe,
+                           os.path.join(ROOT, "tests", "c_abi", "abi_from_c.c"), "-ldl"])
+    res = subprocess.run([exe, ems.LIB_PATH], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
+    assert res.stdout.startswith("ok ")

@@ -6,10 +6,10 @@
 //     and two sets of accumulators.  Per tile, the scores and the online softmax run block
 //     after block (phase 1), leaving the P operands of both blocks in registers; then every
 //     V^T operand is built once and multiplied into the accumulators of both blocks (phase 2).
-//     So up to 32 rows share one stream of the cache.  (Four blocks -- all 64 rows on one
-//     stream -- were tried: the allocator runs out of the 256 non-accumulator registers and
-//     spills, and both ways out, one tile buffer instead of two or spilling, were slower than
-//     two streams of two blocks.)
+//     So up to 32 rows share one stream of the cache.  (Four blocks in registers -- were
+//     tried: the allocator runs out of the 256 non-accumulator registers and spills, and
+//     both ways out, one tile buffer instead of two or spilling, were slower than two
+//     streams of two blocks.)
 //   * a sample with more than 32 rows: (NB = 4, the default above 32 rows) the wave keeps the
 //     state of all four blocks, two of them in registers and two parked in wave-private LDS,
 //     and per tile runs the two resident blocks, swaps the two pairs (16 LDS reads and writes
@@ -41,7 +41,7 @@ template <int NB> __device__ __forceinline__ int halves_of(int ktot) { return NB
 template <int NB>
 struct WideSegment {
     int i, h, half;      // sample, head, which 32 rows of the sample
-    int cu_i, ktot, k;   // first packed row of the sample; its rows (<= 64); rows of this pair (<= 32)
+    int cu_i, ktot, k;   // first packed row of the sample; its rows (<= 64); rows of this pair (<= 16 NB)
     int L;               // cached keys; ceil(L/32) cache tiles, then ceil(ktot/32) tiles of new tokens
     int t0, t1;          // this wave consumes tiles [t0, t1) of the pair
     int64_t cache_off;   // byte offset of (first cache row of the sample, head h) in the arenas

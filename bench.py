@@ -790,10 +790,19 @@ def cpu_baseline(b, with_logits, budget_s=15.0):
     while t < 1.5 and reps < 8:          # ~10-30 s of CPU work over all threads, for a steady figure
         t2, a2 = run(ns)
         t, accepted, reps = t + t2, accepted + a2, reps + 1
-    return {"value": round(accepted / t, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
+    cores = oracle.num_threads()
+    # the same on one thread, over an eighth of the samples (context for the figure above)
+    oracle.set_num_threads(1)
+    try:
+        n1 = max(1, ns // 8)
+        t1, a1 = run(n1)
+    finally:
+        oracle.set_num_threads(cores)
+    return {"value": round(accepted / t, 2), "unit": "tokens/s", "cores": cores,
             "kind": "oracle", "seconds": round(t, 3),
             "sample": "first %d of %d samples of the same batch, all heads, one layer: fp64 oracle "
-                      "attention + arg-max + accept + append, %d time%s over" % (ns, b.B, reps, "" if reps == 1 else "s")}
+                      "attention + arg-max + accept + append, %d time%s over" % (ns, b.B, reps, "" if reps == 1 else "s"),
+            "one_thread": {"value": round(a1 / t1, 2), "seconds": round(t1, 3), "sample": "first %d samples" % n1}}
 
 
 if __name__ == "__main__":

@@ -77,19 +77,22 @@ static double widen(uint16_t bits, int dtype) {
     return sign ? -mag : mag;
 }
 
-/* Alg. 2 (Appendix D): recover (sample, position-in-sample) of packed row r
- * by walking the per-sample token counts.  Returns 0 on success. */
-int oracle_restore_index(const int32_t* token_nums_per_sample, int B, int r,
+/* Which sample a packed row belongs to, and which of that sample's rows it is (what
+ * Appendix D's Alg. 2 recovers inside the kernel).  By definition: with first_i = rows_0 +
+ * ... + rows_{i-1}, packed row r belongs to the one sample i with first_i <= r < first_i +
+ * rows_i, and is its row r - first_i.  Returns 0 on success, 1 if r is not a packed row. */
+int oracle_restore_index(const int32_t* rows_per_sample, int B, int r,
                          int32_t* sample, int32_t* position) {
-    int pos = r, i = 0;
-    while (i < B && pos >= token_nums_per_sample[i]) {
-        pos -= token_nums_per_sample[i];
-        i += 1;
+    int64_t first = 0;
+    for (int i = 0; i < B; ++i) {
+        if (r >= first && r < first + rows_per_sample[i]) {
+            *sample = i;
+            *position = (int32_t)(r - first);
+            return 0;
+        }
+        first += rows_per_sample[i];
     }
-    if (i >= B) return 1;
-    *sample = i;
-    *position = pos;
-    return 0;
+    return 1;
 }
 
 /*
@@ -539,22 +542,29 @@ int oracle_kv_append_rows(uint16_t* k_cache, uint16_t* v_cache, int64_t row_stri
 }
 
 /*
- * "Unpad input tokens", Appendix D, Alg. 1: the input tokens of the samples are appended
- * one sample after the other into a single sequence; the number of tokens of every sample
- * and their total are recorded.  The samples' token lists are given as the first lens[i]
- * entries of row i of a padded [B, k_max] array.  Returns the total.
+ * "Unpad input tokens" (Sec. 3.2; Appendix D, Alg. 1): the packed sequence holds the samples'
+ * input tokens back to back, without padding, and every sample's count is kept.  Written as
+ * a gather: packed slot t holds token t - first_i of the one sample i whose share
+ * [first_i, first_i + lens[i]) contains t (first_i = lens[0] + ... + lens[i-1]).  The
+ * samples' token lists are the first lens[i] entries of row i of a padded [B, k_max] array.
+ * Returns the total number of packed tokens.
  */
 int oracle_concatenate_tokens(const int32_t* padded_ids, const int32_t* lens, int B, int k_max,
-                              int32_t* concatenated, int32_t* token_nums_per_sample) {
-    int total_input_token_nums = 0;
+                              int32_t* packed_ids, int32_t* rows_per_sample) {
+    int total = 0;
     for (int i = 0; i < B; ++i) {
-        const int len = lens[i];
-        for (int j = 0; j < len; ++j)
-            concatenated[total_input_token_nums + j] = padded_ids[(size_t)i * k_max + j];
-        token_nums_per_sample[i] = len;
-        total_input_token_nums += len;
+        rows_per_sample[i] = lens[i];
+        total += lens[i];
     }
-    return total_input_token_nums;
+    for (int t = 0; t < total; ++t) {
+        int i = 0, first = 0;
+        while (t >= first + lens[i]) {
+            first += lens[i];
+            i += 1;
+        }
+        packed_ids[t] = padded_ids[(size_t)i * k_max + (t - first)];
+    }
+    return total;
 }
 
 /* The same greedy target token for fp32 logits (Appendix A): smallest index of the row maximum. */

@@ -53,13 +53,13 @@ MUTANTS = [
     ("appended values are the keys", ACC, "v_cache[dst] = v_new[src];", "v_cache[dst] = k_new[src];", 0),
     ("the new length lags by one", ACC,
      "kv_len_out[i] = kv_len[i] + accepted[i];", "kv_len_out[i] = kv_len[i] + accepted[i] - 1;", 0),
-    ("concatenation forgets the running total", ACC,
-     "concatenated[total_input_token_nums + j] = padded_ids[(size_t)i * k_max + j];",
-     "concatenated[j] = padded_ids[(size_t)i * k_max + j];", 0),
+    ("concatenation gives every slot of a sample that sample's first token", ACC,
+     "packed_ids[t] = padded_ids[(size_t)i * k_max + (t - first)];",
+     "packed_ids[t] = padded_ids[(size_t)i * k_max];", 0),
     ("the highest index wins arg-max ties in fp32 logits", ACC,
      "if (y > best) { best = y; arg = v; }", "if (y >= best) { best = y; arg = v; }", 1),
-    ("Alg. 2 stops one sample early on a boundary row", ACC,
-     "while (i < B && pos >= token_nums_per_sample[i]) {", "while (i < B && pos > token_nums_per_sample[i]) {", 0),
+    ("a sample's first packed row is given to the sample before it", ACC,
+     "if (r >= first && r < first + rows_per_sample[i]) {", "if (r >= first && r <= first + rows_per_sample[i]) {", 0),
     ("write-through leaves out the last new row", ACC,
      "for (int j = 0; j < k; ++j)\n            for (int h = 0; h < H; ++h)", "for (int j = 0; j < k - 1; ++j)\n            for (int h = 0; h < H; ++h)", 0),
     ("bf16 is widened as if it were fp16", ATT, "if (dtype == ORACLE_BF16) {", "if (dtype == 7) {", 0),

@@ -16,14 +16,15 @@
  *                            accepted count (Sec. 3.2, Fig. 2 / Table 1)
  * plus the padded "vanilla" method of Sec. 3.1 as an ablation in the same library, the
  * paper-order variant of steps 1 and 3 (write-through, then advance), the same three steps
- * for token trees (ems_tree_*), ems_pack_tokens (Alg. 1), two debug validators and four
- * measurement aids.
+ * for token trees (ems_tree_*), ems_pack_tokens (Alg. 1) and two debug validators.  The
+ * measurement aids of the same library (kernel timing, read-ceiling probe, the vector-ALU
+ * formulation switch, device memory figures) are declared in ems_measure.h.
  *
  * Conventions shared by every entry point
  *   - Pointers named *device* point to GPU memory owned by the caller; pointers
  *     named *host* are ordinary host memory read during the call only.
  *   - The library never allocates or frees device memory and never synchronises
- *     (the two debug validators and ems_profile_read do wait, as they say).  Work is
+ *     (the two debug validators do wait, as they say).  Work is
  *     enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the default
  *     stream) and the call returns at once.  Device arrays must stay alive until
  *     that work is done.  A sequence of calls can be captured into a HIP graph; make
@@ -42,6 +43,10 @@
  *     contract and are NOT checked (ems_validate_inputs does, synchronously).
  *   - Every function returns an ems_status; ems_last_error_string() gives a
  *     thread-local description of the last failure.
+ *   - Thread safety: the entry points of this header keep no mutable state between calls
+ *     beyond per-device facts cached on first use (compute-unit count, a kernel's LDS limit;
+ *     both race-free), so they may be called from several threads at once, each on its own
+ *     stream, workspace and outputs.
  */
 #ifndef EMS_H
 #define EMS_H
@@ -87,10 +92,14 @@ typedef struct {
     int64_t rows;        /* R */
 } ems_kv_cache;
 
-/* Bytes of device workspace ems_verify_attention needs for these bounds on the current
- * device (split-KV partial results: two slots per wave, one workgroup per compute unit;
- * sized for 256 units when no device is present).  Never 0.  Host-side only: no device
- * memory is touched and nothing is enqueued. */
+/* Bytes of device workspace the attention calls (ems_verify_attention, its write-through,
+ * tree and padded forms) need for these bounds on the current device (split-KV partial
+ * results: two slots per wave, one workgroup per compute unit; sized for 256 units when no
+ * device is present).  Never 0.  Host-side only: no device memory is touched and nothing is
+ * enqueued.  ems_attention_workspace_bytes is the same function under the name that says
+ * which call it sizes (ems_greedy_accept has a workspace of its own,
+ * ems_accept_workspace_bytes, whose size depends on V, not on these arguments). */
+EMS_API size_t ems_workspace_bytes(int B, int T, int H, int D, int max_kv_len);
 EMS_API size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len);
 
 /*
@@ -257,18 +266,6 @@ EMS_API ems_status ems_validate_inputs(
     int B, int T, int max_k, int max_kv_len, int64_t rows, void* hip_stream);
 
 /*
- * Profiling aid (not part of the verification step; single-threaded use).
- * ems_profile_enable(n) creates n pairs of HIP events (host objects); from then on each
- * of the next n ems_verify_attention calls records one pair on its stream right before
- * and right after its main attention kernel (the partial-merge kernel is outside the
- * pair).  ems_profile_read waits for the recorded pairs, returns the summed elapsed
- * milliseconds and the number of pairs, and rearms them.  ems_profile_enable(0)
- * destroys the events and switches timing off.
- */
-EMS_API ems_status ems_profile_enable(int max_records);
-EMS_API ems_status ems_profile_read(double* total_ms, int* launches);
-
-/*
  * Tree-structured verification.  The paper names tree decoding as the next thing to combine
  * with the multi-sample method (Limitations, item 4; Sec. 2 "Dynamic Tree decoding") and
  * gives no algorithm; these three calls are the usual definition, per sample, on the same
@@ -320,42 +317,6 @@ EMS_API ems_status ems_kv_append_rows(
     const int32_t* accepted_rows, const int32_t* accepted_cu,
     const int32_t* kv_start, const int32_t* kv_len, int32_t* kv_len_out,
     int B, int T, int H, int D, ems_dtype dtype, void* hip_stream);
-
-/*
- * Measurement aid: one launch of a plain read-only streaming kernel over `bytes` bytes of
- * device memory at `buf` (16-byte aligned, bytes >= 1024; a tail shorter than 1 KiB is not
- * read), asynchronous on hip_stream.  Its rate is the read ceiling of the device that the
- * attention kernel's bandwidth is compared with.  `sink`: 4 writable device bytes (written
- * only if the data folds to one particular pattern).  Touches nothing else.
- */
-EMS_API ems_status ems_stream_read_probe(const void* buf, size_t bytes, void* sink, void* hip_stream);
-
-/*
- * Measurement aid: which arithmetic units the attention kernel of ems_verify_attention and
- * ems_verify_attention_write_through uses for its two contractions (scores and weighted
- * sum of values).  EMS_ATTN_MFMA (the default) runs them on the matrix cores; EMS_ATTN_VALU
- * runs the same tiles, loads and merge on the vector ALU (packed dot products and FMAs),
- * so that the two can be timed against each other on one input.  Results of both meet
- * the same tolerance.  Process-wide; takes effect with the next call; the padded ablation
- * always uses the matrix cores.  Any other value: EMS_ERR_INVALID_ARG, setting unchanged.
- * While EMS_ATTN_VALU is selected, calls with D = 80, with a token tree, or with so many
- * samples that the per-row state no longer fits the 160 KiB of LDS next to the B+1 prefix
- * sums (D = 128: B > 3967) return EMS_ERR_UNSUPPORTED.
- */
-typedef enum ems_attention_variant {
-    EMS_ATTN_MFMA = 0,
-    EMS_ATTN_VALU = 1
-} ems_attention_variant;
-EMS_API ems_status ems_set_attention_variant(int variant);
-EMS_API int ems_get_attention_variant(void);
-
-/*
- * What the HIP runtime reports for the current device's memory: clock in kHz, bus width in
- * bits (either may come back 0 where the runtime reports nothing).  Context for bandwidth
- * figures; the library itself does not use them.  Host pointers, both required.
- * Errors: NULL pointer -> INVALID_ARG; runtime failure -> HIP.
- */
-EMS_API ems_status ems_device_memory_figures(int* memory_clock_khz, int* memory_bus_width_bits);
 
 /* Thread-local text for the last non-OK status returned on this thread. */
 EMS_API const char* ems_last_error_string(void);

@@ -261,8 +261,6 @@ __device__ __forceinline__ int tree_visibility(int parent_n, int n, int k) {
     return seen;
 }
 
-// One (sample, head) pair's share of a wave's tile range; everything is wave-uniform and
-
 // The same for up to 64 rows: lane j holds parent[j] of row j, six rounds cover any depth,
 // and the sets take two words.  Returns the set of row `want` (a lane-dependent row index).
 __device__ __forceinline__ uint64_t tree_visibility64(int parent_j, int lane, int k, int want) {

@@ -1,6 +1,7 @@
 // C ABI of libems: argument validation (host only, before any HIP call),
 // launch sizing, error strings.  See include/ems.h for the contract.
 #include "../../include/ems.h"
+#include "../../include/ems_measure.h"
 
 #include <hip/hip_runtime.h>
 
@@ -70,16 +71,19 @@ size_t attn_ws_bytes_for(int blocks, int B, int D, AttnShape shape) {
 // per CU measured slower (275 vs 256 us at config 4): the SIMD arbitrates oldest-first, the
 // older workgroup's waves finish long before the younger one's and the tail runs half empty.
 int resident_attn_blocks() {
-    static int cached[64] = {0};
+    // per-device fact, cached on first use; threads that race here store the same value
+    static std::atomic<int> cached[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
+    int blocks = cached[dev].load(std::memory_order_relaxed);
+    if (blocks == 0) {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             cus = 256;
-        cached[dev] = std::min(kMaxAttnBlocks, cus);
+        blocks = std::min(kMaxAttnBlocks, cus);
+        cached[dev].store(blocks, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return blocks;
 }
 
 void accept_slicing(int T, int V, int* slices, int* slice_len) {
@@ -101,13 +105,16 @@ void accept_slicing(int T, int V, int* slices, int* slice_len) {
 
 bool dtype16(ems_dtype d) { return d == EMS_F16 || d == EMS_BF16; }
 
-// Optional timing of the main attention kernel with HIP events (profiling aid).
+// Measurement aids, both per calling thread, so that one thread's measurement never changes
+// what another thread's attention call runs or records: optional timing of the attention
+// call with HIP events (before the main kernel, after it, after the merge kernel), and
+// which formulation of the main kernel this thread's calls use.
 struct Profile {
-    std::vector<hipEvent_t> start, stop;
+    std::vector<hipEvent_t> start, stop, end;
     int used = 0;
 };
-Profile g_prof;
-std::atomic<int> g_attn_variant{EMS_ATTN_MFMA};
+thread_local Profile g_prof;
+thread_local int g_attn_variant = EMS_ATTN_MFMA;
 
 }  // namespace
 
@@ -125,6 +132,10 @@ ems_status ems_device_memory_figures(int* memory_clock_khz, int* memory_bus_widt
     if (e == hipSuccess) e = hipDeviceGetAttribute(memory_bus_width_bits, hipDeviceAttributeMemoryBusWidth, dev);
     if (e != hipSuccess) return fail(EMS_ERR_HIP, "device attributes: %s", hipGetErrorString(e));
     return EMS_OK;
+}
+
+size_t ems_workspace_bytes(int B, int T, int H, int D, int max_kv_len) {
+    return ems_attention_workspace_bytes(B, T, H, D, max_kv_len);
 }
 
 size_t ems_attention_workspace_bytes(int B, int T, int H, int D, int max_kv_len) {
@@ -170,16 +181,16 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     if (D != 64 && D != 80 && D != 128)
         return fail(EMS_ERR_UNSUPPORTED, "D = %d, supported head dims are 64, 80 and 128", D);
     if (D == 80 && pad) return fail(EMS_ERR_UNSUPPORTED, "the padded ablation has head dims 64 and 128 only");
-    if (D == 80 && g_attn_variant.load() == EMS_ATTN_VALU)
+    if (D == 80 && g_attn_variant == EMS_ATTN_VALU)
         return fail(EMS_ERR_UNSUPPORTED, "EMS_ATTN_VALU has head dims 64 and 128 only");
-    if (!pad && g_attn_variant.load() == EMS_ATTN_VALU && ems::valu_attention_lds_bytes(B, D) > (size_t)ems::kMaxLdsBytes)
+    if (!pad && g_attn_variant == EMS_ATTN_VALU && ems::valu_attention_lds_bytes(B, D) > (size_t)ems::kMaxLdsBytes)
         return fail(EMS_ERR_UNSUPPORTED, "EMS_ATTN_VALU keeps its per-row state in LDS: B = %d at D = %d needs %zu of %d bytes",
                     B, D, ems::valu_attention_lds_bytes(B, D), ems::kMaxLdsBytes);
     if (max_k > EMS_MAX_QUERY_ROWS)
         return fail(EMS_ERR_UNSUPPORTED, "max_k = %d, at most %d rows per sample", max_k, EMS_MAX_QUERY_ROWS);
     const bool wide = max_k > EMS_ROWS_PER_GROUP;      // the wide kernel
     if (wide && pad) return fail(EMS_ERR_UNSUPPORTED, "the padded ablation takes at most %d rows per sample", EMS_ROWS_PER_GROUP);
-    if (wide && g_attn_variant.load() == EMS_ATTN_VALU)
+    if (wide && g_attn_variant == EMS_ATTN_VALU)
         return fail(EMS_ERR_UNSUPPORTED, "EMS_ATTN_VALU takes at most %d rows per sample", EMS_ROWS_PER_GROUP);
     if (B > kMaxB) return fail(EMS_ERR_UNSUPPORTED, "B = %d, at most %d samples", B, kMaxB);
     if (T == 0) return EMS_OK;
@@ -240,16 +251,19 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
         p.l_pad = pad->l_pad;
         p.cap = pad->cap;
     }
-    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr;
     if (g_prof.used < (int)g_prof.start.size()) {
         ev0 = g_prof.start[g_prof.used];
         ev1 = g_prof.stop[g_prof.used];
+        ev2 = g_prof.end[g_prof.used];
         ++g_prof.used;
     }
     hipError_t e = ems::launch_verify_attention(p, blocks, D, dtype == EMS_BF16, pad != nullptr,
-                                                g_attn_variant.load() == EMS_ATTN_VALU,
+                                                g_attn_variant == EMS_ATTN_VALU,
                                                 static_cast<hipStream_t>(hip_stream), ev0, ev1);
     if (e != hipSuccess) return hip_fail("attention launch", e);
+    if (ev2 && (e = hipEventRecord(ev2, static_cast<hipStream_t>(hip_stream))) != hipSuccess)
+        return hip_fail("attention timing", e);
     return EMS_OK;
 }
 
@@ -290,7 +304,7 @@ ems_status ems_tree_verify_attention(const void* q, const void* k_new, const voi
                                      ems_dtype dtype, void* workspace, size_t workspace_bytes,
                                      void* hip_stream) {
     if (!parent && T > 0) return fail(EMS_ERR_INVALID_ARG, "parent must not be NULL");
-    if (g_attn_variant.load() == EMS_ATTN_VALU)
+    if (g_attn_variant == EMS_ATTN_VALU)
         return fail(EMS_ERR_UNSUPPORTED, "EMS_ATTN_VALU has no token-tree mask");
     return run_attention(q, k_new, v_new, cache, cu_seqlens, kv_start, kv_len, out, out_dtype, B, T,
                          H, D, max_k, max_kv_len, scale, dtype, workspace, workspace_bytes,
@@ -611,45 +625,52 @@ ems_status ems_stream_read_probe(const void* buf, size_t bytes, void* sink, void
 ems_status ems_set_attention_variant(int variant) {
     if (variant != EMS_ATTN_MFMA && variant != EMS_ATTN_VALU)
         return fail(EMS_ERR_INVALID_ARG, "attention variant %d is neither EMS_ATTN_MFMA nor EMS_ATTN_VALU", variant);
-    g_attn_variant.store(variant);
+    g_attn_variant = variant;
     return EMS_OK;
 }
 
-int ems_get_attention_variant(void) { return g_attn_variant.load(); }
+int ems_get_attention_variant(void) { return g_attn_variant; }
 
 ems_status ems_profile_enable(int max_records) {
-    for (hipEvent_t ev : g_prof.start) (void)hipEventDestroy(ev);
-    for (hipEvent_t ev : g_prof.stop) (void)hipEventDestroy(ev);
-    g_prof.start.clear();
-    g_prof.stop.clear();
+    for (auto* evs : {&g_prof.start, &g_prof.stop, &g_prof.end}) {
+        for (hipEvent_t ev : *evs) (void)hipEventDestroy(ev);
+        evs->clear();
+    }
     g_prof.used = 0;
     if (max_records < 0 || max_records > 65536)
         return fail(EMS_ERR_INVALID_ARG, "max_records = %d outside [0, 65536]", max_records);
     for (int i = 0; i < max_records; ++i) {
-        hipEvent_t a = nullptr, b = nullptr;
-        hipError_t e = hipEventCreate(&a);
-        if (e == hipSuccess) e = hipEventCreate(&b);
-        if (e != hipSuccess) return hip_fail("hipEventCreate", e);
-        g_prof.start.push_back(a);
-        g_prof.stop.push_back(b);
+        for (auto* evs : {&g_prof.start, &g_prof.stop, &g_prof.end}) {
+            hipEvent_t ev = nullptr;
+            hipError_t e = hipEventCreate(&ev);
+            if (e != hipSuccess) return hip_fail("hipEventCreate", e);
+            evs->push_back(ev);
+        }
     }
     return EMS_OK;
 }
 
-ems_status ems_profile_read(double* total_ms, int* launches) {
+ems_status ems_profile_read_calls(double* total_ms, double* total_call_ms, int* launches) {
     if (!total_ms || !launches) return fail(EMS_ERR_INVALID_ARG, "total_ms and launches must not be NULL");
-    double sum = 0.0;
+    double sum = 0.0, sum_call = 0.0;
     for (int i = 0; i < g_prof.used; ++i) {
-        hipError_t e = hipEventSynchronize(g_prof.stop[i]);
-        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(g_prof.end[i]);
+        float ms = 0.f, ms_call = 0.f;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms_call, g_prof.start[i], g_prof.end[i]);
         if (e != hipSuccess) return hip_fail("ems_profile_read", e);
         sum += ms;
+        sum_call += ms_call;
     }
     *total_ms = sum;
+    if (total_call_ms) *total_call_ms = sum_call;
     *launches = g_prof.used;
     g_prof.used = 0;
     return EMS_OK;
+}
+
+ems_status ems_profile_read(double* total_ms, int* launches) {
+    return ems_profile_read_calls(total_ms, nullptr, launches);
 }
 
 ems_status ems_validate_inputs(const int32_t* cu_seqlens, const int32_t* kv_start,

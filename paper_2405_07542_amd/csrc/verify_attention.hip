@@ -195,6 +195,7 @@ __device__ __forceinline__ void valu_tile(const TileRegs<D>& t, char* lds, ValuS
     }
 }
 
+// One (sample, head) pair's share of a wave's tile range; everything is wave-uniform and
 // kept small, so that two of them live in scalar registers.
 struct Segment {
     int i, h;            // sample, head

@@ -24,7 +24,7 @@ int main(int argc, char** argv) {
     err_fn last_error;
     /* (the POSIX way to turn dlsym's object pointer into a function pointer) */
     *(void**)(&version) = dlsym(lib, "ems_version");
-    *(void**)(&ws_bytes) = dlsym(lib, "ems_attention_workspace_bytes");
+    *(void**)(&ws_bytes) = dlsym(lib, "ems_workspace_bytes");
     *(void**)(&attention) = dlsym(lib, "ems_verify_attention");
     *(void**)(&last_error) = dlsym(lib, "ems_last_error_string");
     if (!version || !ws_bytes || !attention || !last_error) return 4;

@@ -9,17 +9,18 @@ import pytest
 import paper_2405_07542_amd as ems
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "ems.h")
+HEADERS = [os.path.join(ROOT, "include", "ems.h"), os.path.join(ROOT, "include", "ems_measure.h")]
 
 
 def declared_symbols():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     return re.findall(r"EMS_API\s+[\w\s\*]+?\b(ems_\w+)\s*\(", text)
 
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert {"ems_verify_attention", "ems_greedy_accept", "ems_kv_append"} <= set(names)
+    assert {"ems_verify_attention", "ems_greedy_accept", "ems_kv_append", "ems_workspace_bytes",
+            "ems_profile_enable", "ems_stream_read_probe", "ems_set_attention_variant"} <= set(names)
     L = ems.lib()
     for n in names:
         assert hasattr(L, n), "libems.so does not export %s" % n
@@ -27,6 +28,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_workspace_sizes_are_host_arithmetic():
+    for args in ((64, 384, 32, 128, 2048), (1, 1, 1, 64, 0), (128, 448, 32, 128, 4096), (0, 0, 0, 0, 0)):
+        assert ems.ems_workspace_bytes(*args) == ems.ems_attention_workspace_bytes(*args)
     assert ems.ems_attention_workspace_bytes(64, 384, 32, 128, 2048) >= 256
     assert ems.ems_attention_workspace_bytes(1, 1, 1, 64, 0) >= 256
     assert ems.ems_attention_workspace_bytes(128, 448, 32, 128, 4096) <= 160 << 20
@@ -149,8 +152,20 @@ def test_write_through_and_advance_reject_bad_arguments_on_the_host():
     assert L.ems_verify_attention_write_through(*args) == ems.EMS_ERR_INVALID_ARG     # B = 0
 
 
-def test_attention_variant_switch_is_host_state():
+def test_attention_variant_switch_is_per_thread_host_state():
+    import threading
     L = ems.lib()
+    seen = {}
+
+    def other_thread():
+        seen["before"] = L.ems_get_attention_variant()
+        L.ems_set_attention_variant(ems.EMS_ATTN_VALU)
+        seen["after"] = L.ems_get_attention_variant()
+    t = threading.Thread(target=other_thread)
+    t.start()
+    t.join()
+    assert seen == {"before": ems.EMS_ATTN_MFMA, "after": ems.EMS_ATTN_VALU}
+    assert L.ems_get_attention_variant() == ems.EMS_ATTN_MFMA       # this thread's calls are unaffected
     assert L.ems_get_attention_variant() == ems.EMS_ATTN_MFMA
     assert L.ems_set_attention_variant(ems.EMS_ATTN_VALU) == ems.EMS_OK
     assert L.ems_get_attention_variant() == ems.EMS_ATTN_VALU

@@ -17,12 +17,36 @@ def to_device(b, device="cuda"):
     return type(b)(**kw)
 
 
+GUARD_BYTES = 256
+GUARD_PATTERN = 0xA5
+
+
+def guarded(nbytes, device):
+    """A uint8 device buffer of nbytes followed by GUARD_BYTES of a fixed pattern that nobody may write."""
+    buf = torch.empty(nbytes + GUARD_BYTES, dtype=torch.uint8, device=device)
+    buf[nbytes:] = GUARD_PATTERN
+    return buf
+
+
+def assert_guard_intact(buf, nbytes, what):
+    tail = buf[nbytes:].cpu()
+    assert bool((tail == GUARD_PATTERN).all()), "%s: bytes beyond its end were written (first at +%d)" % (
+        what, int((tail != GUARD_PATTERN).nonzero()[0]))
+
+
 def hip_attention(b, out_dtype=None, k_cache=None, v_cache=None, kv_len=None, max_kv_len=None):
+    """One ems_verify_attention call.  `out` (NaN-filled) and the workspace are each followed by
+    guard bytes that must come back untouched."""
     import paper_2405_07542_amd as ems
-    out = torch.full((b.T, b.H, b.D), float("nan"), dtype=out_dtype or b.dtype, device=b.q.device)
+    odt = out_dtype or b.dtype
+    out_bytes = b.T * b.H * b.D * torch.empty((), dtype=odt).element_size()
+    out_buf = guarded(out_bytes, b.q.device)
+    out = out_buf[:out_bytes].view(odt).view(b.T, b.H, b.D)
+    out.fill_(float("nan"))
     max_kv = b.max_kv_len if max_kv_len is None else max_kv_len
-    ws = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, max_kv),
-                     dtype=torch.uint8, device=b.q.device)
+    ws_bytes = ems.ems_workspace_bytes(b.B, b.T, b.H, b.D, max_kv)
+    ws_buf = guarded(ws_bytes, b.q.device)
+    ws = ws_buf[:ws_bytes]
     cache = ems.kv_cache(b.k_cache if k_cache is None else k_cache,
                          b.v_cache if v_cache is None else v_cache,
                          b.row_stride, b.head_stride, b.rows)
@@ -30,6 +54,8 @@ def hip_attention(b, out_dtype=None, k_cache=None, v_cache=None, kv_len=None, ma
                              b.kv_len if kv_len is None else kv_len, out,
                              max_k=b.max_k, max_kv_len=max_kv, scale=b.scale, workspace=ws)
     torch.cuda.synchronize()
+    assert_guard_intact(out_buf, out_bytes, "out")
+    assert_guard_intact(ws_buf, ws_bytes, "attention workspace")
     return out
 
 

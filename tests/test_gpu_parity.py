@@ -13,15 +13,18 @@ from helpers import (attention_tolerance, hip_accept, hip_attention, oracle_acce
 pytestmark = pytest.mark.gpu
 
 
-def check_attention(b_cpu, out_dtype=None, label=""):
+def check_attention(b_cpu, out_dtype=None, label="", plain_bar=False, want=None):
+    """plain_bar: assert the stated max-abs 2e-3 as it is, also for a bf16 output (the widened
+    bound of helpers.attention_tolerance is for bf16 outputs of short caches only, where the
+    rounding of the result itself exceeds the bar)."""
     print("attention case:", label or b_cpu.name, "B", b_cpu.B, "H", b_cpu.H, "D", b_cpu.D,
           b_cpu.dtype, b_cpu.layout, "out", out_dtype, flush=True)
     b = to_device(b_cpu)
     got = hip_attention(b, out_dtype=out_dtype).double().cpu().numpy()
-    want = oracle_attention(b_cpu)
+    want = oracle_attention(b_cpu) if want is None else want
     assert np.isfinite(got).all(), "non-finite output (a sentinel row was read, or a row was not written)"
     err = np.abs(got - want)
-    tol = attention_tolerance(b_cpu, want, out_dtype or b_cpu.dtype)
+    tol = np.full(want.shape, 2e-3) if plain_bar else attention_tolerance(b_cpu, want, out_dtype or b_cpu.dtype)
     worst = np.unravel_index(np.argmax(err - tol), err.shape)
     assert (err <= tol).all(), "max err %.3e at %s (tol %.3e)" % (err[worst], worst, tol[worst])
     return float(err.max())
@@ -112,11 +115,16 @@ def test_attention_is_deterministic():
 @pytest.mark.parametrize("n,layout", [(2, TOKEN_MAJOR), (2, HEAD_MAJOR), (3, TOKEN_MAJOR),
                                       (4, TOKEN_MAJOR), (4, HEAD_MAJOR)])
 def test_baseline_configs_full_size(n, layout):
-    """Configs 2-4 at full size, every output element against the oracle, plus
-    acceptance on the full [T, 50272] logits and the append into the arena."""
+    """Configs 2-4 at full size, every output element against the oracle at the stated bar
+    itself -- max-abs 2e-3, with the fp32 output and with the 16-bit output (config 4's is
+    bf16: its caches hold >= 1024 rows, so |out| stays far below the 0.5 from which bf16's own
+    rounding would exceed the bar) -- plus acceptance on the full [T, 50272] logits and the
+    append into the arena."""
     b_cpu = make_config(n, layout=layout)
-    err = check_attention(b_cpu)
-    print("config", n, layout, "max abs err %.3e" % err, flush=True)
+    want = oracle_attention(b_cpu)
+    err32 = check_attention(b_cpu, out_dtype=torch.float32, plain_bar=True, want=want)
+    err16 = check_attention(b_cpu, plain_bar=True, want=want)
+    print("config", n, layout, "max abs err: fp32 out %.3e, 16-bit out %.3e (bar 2e-3)" % (err32, err16), flush=True)
     run_accept_and_append(b_cpu)
 
 

@@ -1,8 +1,8 @@
 """GPU parity of the multi-layer, multi-step verify loop (BASELINE config 5) against the oracle
 carried through the same steps: accepted counts, offsets, lengths and cache bytes bit-exact,
 attention within 2e-3.  At full size (32 layers, B=128, 20 steps, ~75 GB of caches) the oracle
-follows three sampled layers; the other layers' caches are cross-checked against a plain
-index-copy of the accepted rows."""
+follows three sampled layers through all 20 steps; the other layers' caches are cross-checked
+against a plain index-copy of the accepted rows."""
 import numpy as np
 import pytest
 import torch
@@ -14,7 +14,9 @@ from helpers import attention_tolerance
 pytestmark = pytest.mark.gpu
 
 
-def run_and_check(loop, oracle_layers, attn_steps):
+def run_and_check(loop, oracle_layers, attn_steps, plain_bar=True):
+    """plain_bar: the stated max-abs 2e-3 as it is; False only for bf16 outputs over short caches,
+    whose own rounding (2^-8 |x|) exceeds the bar once |x| > 0.5 (helpers.attention_tolerance)."""
     from paper_2405_07542_amd.verify_loop import VerifyLoopRunner
     B, H, D = loop.B, loop.H, loop.D
     kv_len = loop.kv_len0.clone()
@@ -31,6 +33,7 @@ def run_and_check(loop, oracle_layers, attn_steps):
     # a layer the oracle does not follow: remember what must have been appended where
     other = next((l for l in range(loop.n_layers) if l not in oracle_layers), None)
     expect_rows = []
+    worst = 0.0
     for s, st in enumerate(loop.steps):
         print("verify loop step", s, "T", st.T, flush=True)
         cu = st.cu_seqlens.cpu().numpy()
@@ -51,8 +54,10 @@ def run_and_check(loop, oracle_layers, attn_steps):
                                                H, D, loop.scale, loop.dtype)
                 got = runner.out[l][:st.T].double().cpu().numpy()
                 assert np.isfinite(got).all()
-                tol = attention_tolerance(None, want, loop.dtype)      # outputs are in the input dtype
-                assert (np.abs(got - want) <= tol).all(), "layer %d step %d" % (l, s)
+                err = np.abs(got - want)                     # outputs are in the input dtype
+                worst = max(worst, float(err.max()))
+                tol = 2e-3 if plain_bar else attention_tolerance(None, want, loop.dtype)
+                assert (err <= tol).all(), "layer %d step %d: max abs err %.3e" % (l, s, err.max())
             new_len = oracle.kv_append(o_k[l], o_v[l], loop.row_stride, loop.head_stride, bits(st.k_new[l]),
                                        bits(st.v_new[l]), cu, acc, starts, o_len, H, D)
         if other is not None:
@@ -71,14 +76,16 @@ def run_and_check(loop, oracle_layers, attn_steps):
         want = torch.stack([loop.steps[s].k_new[other][r] for _, s, r in expect_rows])
         assert torch.equal(got.view(torch.int16), want.view(torch.int16))
     assert (o_len - loop.kv_len0.cpu().numpy()).min() >= len(loop.steps)
+    print("verify loop: attention max abs err %.3e over layers %s, steps %s (bar 2e-3)"
+          % (worst, list(oracle_layers), list(attn_steps)), flush=True)
 
 
 def test_small_loop_every_layer_every_step():
     loop = make_verify_loop(n_layers=3, n_steps=5, B=9, H=4, D=128, V=4096, device="cuda", mean_len=150,
                             max_len=400, dtype=torch.bfloat16, seed=123)
-    run_and_check(loop, oracle_layers=[0, 1, 2], attn_steps=range(5))
+    run_and_check(loop, oracle_layers=[0, 1, 2], attn_steps=range(5), plain_bar=False)
 
 
 def test_config5_full_size_sampled_layers():
     loop = make_verify_loop(device="cuda")              # 32 layers, B=128, 20 steps, fp16
-    run_and_check(loop, oracle_layers=[0, 15, 31], attn_steps=(0, 10, 19))
+    run_and_check(loop, oracle_layers=[0, 15, 31], attn_steps=range(20))

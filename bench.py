@@ -6,12 +6,18 @@ resident in HBM:  ems_verify_attention (one OPT-6.7b-shaped layer) ->
 ems_greedy_accept (arg-max over [T, 50272] logits, acceptance, prefix sum) ->
 ems_kv_append (accepted rows into the per-sample caches).
 
-Prints ONE JSON line: verified tokens/s (sum of accepted tokens / step time), the
-roofline figures of the dominant kernel (the main attention kernel, timed with HIP
-events recorded around it on its own stream inside the timed region) and the
-oracle's throughput on the host cores as a CPU baseline.
+Prints ONE JSON line: verified tokens/s (sum of accepted tokens / step time) at BASELINE
+config 4 (B=64, bf16, the configuration the target is quoted on), the roofline figures of
+the dominant kernel (the main attention kernel, timed with HIP events recorded around it on
+its own stream inside the timed region), the padded ablation on the same data, the oracle's
+throughput on the host cores as a CPU baseline, `parity` (what the timed run left in buffer
+set 0 against the oracle: max-abs error of the attention output, equality of ids, counts,
+offsets and appended cache rows) and `all_configs` (brief runs of configs 2, 3 and 5, so
+that B = 8, 32, 64 and 128 are all in the line).
 
     python bench.py [--steps K] [--warmup W] [--config 2|3|4|5] [--layout token_major|head_major]
+
+Side modes (sweeps, the paper's launch shape, dynamic batching) live in bench_modes.py.
 """
 import argparse
 import json
@@ -69,6 +75,10 @@ def parse_args():
     ap.add_argument("--sweep-variants", action="store_true",
                     help="instead of the bench: attention kernel time of the matrix-core and the vector-ALU "
                          "formulation vs rows per sample, B=64, 2048 cached tokens each, bf16")
+    ap.add_argument("--no-all-configs", action="store_true",
+                    help="config 4 only: skip the brief runs of configs 2, 3 and 5 that fill `all_configs`")
+    ap.add_argument("--source-digest", action="store_true",
+                    help="print the digest of the attention kernels' sources (stored with counter summaries) and exit")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the bench: run a plain device copy of MIB MiB five times "
                          "(the known-size kernel that scales rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -120,71 +130,56 @@ def attention_algorithmic_bytes(b, out_elem_bytes):
     return total + (3 * b.B + 1) * 4
 
 
+KERNEL_SOURCES = ("attention_tiles.h", "ems_device.h", "ems_kernels.h", "verify_attention.hip",
+                  "verify_attention_wide.hip")
+
+
+def kernel_source_digest():
+    """sha256 (first 16 hex digits) over the sources of the attention kernels, in a fixed order.
+    A stored counter figure carries the digest of the sources it was measured with; when the
+    sources have changed since, the figure is not quoted (see read_traffic)."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2405_07542_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(workload_key):
-    """HBM bytes per launch of the main attention kernel from a committed rocprofv3 --pmc
-    summary (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel), if one exists."""
-    path = os.path.join(ROOT, "profiles", "verify_attention_traffic.txt")
+    """(HBM bytes per launch of the main attention kernel, where the figure comes from) from the
+    committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
+    counter reads for a plain copy of known size).  The summary states the digest of the kernel
+    sources it was measured with; if the sources differ now, the figure is stale and None is
+    returned in its place."""
+    rel = os.path.join("profiles", "verify_attention_traffic.txt")
+    path = os.path.join(ROOT, rel)
+    source = {"file": rel, "commit": None, "kernel_source_digest": None, "current_digest": kernel_source_digest(),
+              "stale": None}
     if not os.path.exists(path):
-        return None
+        return None, None
+    value = None
     for line in open(path):
         parts = line.split()
-        if len(parts) >= 2 and parts[0] == workload_key:
+        if len(parts) >= 3 and parts[0] == "#" and parts[1] in ("commit", "kernel_source_digest"):
+            source[parts[1]] = parts[2]
+        elif len(parts) >= 2 and parts[0] == workload_key:
             try:
-                return float(parts[1])
+                value = float(parts[1])
             except ValueError:
-                return None
-    return None
+                value = None
+    source["stale"] = source["kernel_source_digest"] != source["current_digest"]
+    if value is None:
+        return None, None
+    return (None if source["stale"] else value), source
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (--gpus 1); the path would shard by sample or by "
-              "head with no exchange between GPUs, so the figure for N GPUs is N times this one", file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
+def build_sets(n, args, with_logits, dev):
+    """Independent buffer sets of config n, rotated between steps so that no step finds its K/V
+    in the last-level cache."""
     import torch
     import paper_2405_07542_amd as ems
-    from workloads import make_config, CONFIG_NAMES
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    ems.lib()     # fail loudly if the HIP library is missing
-    ems.ems_set_attention_variant(ems.EMS_ATTN_VALU if args.attention_variant == "valu" else ems.EMS_ATTN_MFMA)
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    if args.copy_calibration > 0:
-        src = torch.ones(args.copy_calibration << 20, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_calibration_bytes": src.numel(), "launches": 5}))
-        return
-    n = args.config
-    with_logits = not args.no_logits
-    if args.tree and (args.write_through or args.attention_variant == "valu" or n == 5):
-        sys.exit("--tree runs the matrix-core kernel with the gathered append on configs 2-4 only")
-    if args.tree_rows and (not args.tree or not 1 <= args.tree_rows <= 64):
-        sys.exit("--tree-rows N goes with --tree and 1 <= N <= 64")
-    if args.per_token_grid:
-        print(json.dumps(per_token_grid(args)), flush=True)
-        return
-    if args.sweep_variants:
-        print(json.dumps(sweep_variants()), flush=True)
-        return
-    if args.sweep_k:
-        print(json.dumps(sweep_k()), flush=True)
-        return
-    if args.dynamic_batching:
-        print(json.dumps(dynamic_batching_bench(args)), flush=True)
-        return
-    if n == 5:
-        print(json.dumps(verify_loop_bench(args, with_logits)), flush=True)
-        return
-
+    from workloads import make_config
     sets = []
     n_sets = args.sets
     v = 0
@@ -196,10 +191,10 @@ def main():
         if args.tree:
             from workloads import grow_trees
             b = grow_trees(b, 4242 + v, match_p=0.7, shape=args.tree)
-        ws_attn = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len),
+        ws_attn = torch.empty(ems.ems_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len),
                               dtype=torch.uint8, device=dev)
         ws_acc = torch.empty(max(8, ems.ems_accept_workspace_bytes(b.T, b.V)), dtype=torch.uint8, device=dev)
-        st = dict(
+        sets.append(dict(
             b=b, ws_attn=ws_attn, ws_acc=ws_acc,
             cache=ems.kv_cache(b.k_cache, b.v_cache, b.row_stride, b.head_stride, b.rows),
             out=torch.empty((b.T, b.H, b.D), dtype=b.dtype, device=dev),
@@ -209,10 +204,14 @@ def main():
             out_tokens=torch.empty(b.T, dtype=torch.int32, device=dev),
             accepted_rows=torch.empty(b.T, dtype=torch.int32, device=dev),
             # the lengths are NOT advanced between timed steps, so every step does the same work
-            new_len=torch.empty(b.B, dtype=torch.int32, device=dev))
-        sets.append(st)
+            new_len=torch.empty(b.B, dtype=torch.int32, device=dev)))
         v += 1
     torch.cuda.synchronize()
+    return sets
+
+
+def step_functions(args, with_logits):
+    import paper_2405_07542_amd as ems
 
     def attention(st):
         b = st["b"]
@@ -252,6 +251,17 @@ def main():
         accept(st)
         append(st)
 
+    return attention, accept, append, step
+
+
+def time_one_layer_config(n, args, with_logits, steps, warmup, dev, with_ceiling):
+    """Times `steps` steps of config n (2, 3 or 4: one layer).  Returns (figures, sets)."""
+    import numpy as np
+    import torch
+    import paper_2405_07542_amd as ems
+    sets = build_sets(n, args, with_logits, dev)
+    attention, accept, append, step = step_functions(args, with_logits)
+
     # Set-up, untimed: every buffer set is run once, so that its accepted counts (the numerator
     # of `value`) exist however few steps are timed, and so that no set is touched for the first
     # time inside the timed region (the first pass over a fresh 2 GiB arena costs ~90 us more);
@@ -259,58 +269,126 @@ def main():
     for st in sets:
         step(st)
     torch.cuda.synchronize()
-    ceiling = measured_read_ceiling(sets[0]["b"].k_cache)
+    ceiling = measured_read_ceiling(sets[0]["b"].k_cache) if with_ceiling else None
 
-    for w in range(args.warmup):
+    for w in range(warmup):
         step(sets[w % len(sets)])
     torch.cuda.synchronize()
 
-    ems.ems_profile_enable(args.steps)
+    ems.ems_profile_enable(steps)
     t0 = time.perf_counter()
-    for s in range(args.steps):
+    for s in range(steps):
         step(sets[s % len(sets)])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    attn_ms_total, attn_launches = ems.ems_profile_read()
+    attn_ms_total, call_ms_total, attn_launches = ems.ems_profile_read_calls()
     ems.ems_profile_enable(0)
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
     accepted_per_step = float(np.mean([int(st["accepted_cu"][-1]) for st in sets]))
     rows_per_step = float(np.mean([st["b"].T for st in sets]))
-    value = accepted_per_step / (ms_per_step * 1e-3)
-
-    out_bytes = 2
-    alg_bytes = float(np.mean([attention_algorithmic_bytes(st["b"], out_bytes) for st in sets]))
+    alg_bytes = float(np.mean([attention_algorithmic_bytes(st["b"], 2) for st in sets]))
     attn_ms = attn_ms_total / max(1, attn_launches)
+    call_ms = call_ms_total / max(1, attn_launches)
     achieved = alg_bytes / (attn_ms * 1e-3) / 1e9
-    workload_key = "config%d_%s" % (n, args.layout) + ("_tree_rows%d" % args.tree_rows if args.tree_rows else "")
+    achieved_call = alg_bytes / (call_ms * 1e-3) / 1e9
     wide = max(st["b"].max_k for st in sets) > 16
     roofline = {
         "bound": "hbm", "kernel": "verify_attention_wide_kernel" if wide else "verify_attention_kernel",
-        "achieved": round(achieved, 1),
-        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": read_traffic(workload_key),
-        "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": round(attn_ms, 5),
+        # achieved / frac: algorithmic bytes of the attention call over the duration of its main
+        # kernel (HIP events right around that kernel); *_call: over the whole call, i.e. with
+        # the partial-merge kernel that writes the outputs of pairs shared between workgroups
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "achieved_call": round(achieved_call, 1), "frac_call": round(achieved_call / HBM_PEAK_GBS, 4),
+        "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": round(attn_ms, 5), "call_ms": round(call_ms, 5),
         "launches_timed": attn_launches,
-        # context, not the peak: a plain read-only streaming kernel over one K arena, same run
-        "measured_read_ceiling": ceiling, "frac_of_measured_ceiling": round(achieved / ceiling, 4),
-        "device_reported": device_memory_figures(),
     }
+    figures = {"ms_per_step": ms_per_step, "value": accepted_per_step / (ms_per_step * 1e-3),
+               "query_tokens_per_s": rows_per_step / (ms_per_step * 1e-3), "accepted_per_step": accepted_per_step,
+               "rows_per_step": rows_per_step, "alg_bytes": alg_bytes, "roofline": roofline, "ceiling": ceiling,
+               "steps": steps, "warmup": warmup}
+    return figures, (sets, attention, accept, append)
 
+
+LOGITS_NOTE = ("[T, 50272] N(0,1) with the row maximum planted (8.0 at the target id, repeated at a higher "
+               "index on 25 % of the rows to force ties); cost is data-independent")
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (--gpus 1); the path would shard by sample or by "
+              "head with no exchange between GPUs, so the figure for N GPUs is N times this one", file=sys.stderr)
+        sys.exit(2)
+    if args.source_digest:
+        print(kernel_source_digest())
+        return
+    import torch
+    import paper_2405_07542_amd as ems
+    from workloads import CONFIG_NAMES
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    ems.lib()     # fail loudly if the HIP library is missing
+    ems.ems_set_attention_variant(ems.EMS_ATTN_VALU if args.attention_variant == "valu" else ems.EMS_ATTN_MFMA)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    n = args.config
+    with_logits = not args.no_logits
+    if args.tree and (args.write_through or args.attention_variant == "valu" or n == 5):
+        sys.exit("--tree runs the matrix-core kernel with the gathered append on configs 2-4 only")
+    if args.tree_rows and (not args.tree or not 1 <= args.tree_rows <= 64):
+        sys.exit("--tree-rows N goes with --tree and 1 <= N <= 64")
+    side_mode = (args.copy_calibration > 0 or args.per_token_grid or args.sweep_variants or args.sweep_k
+                 or args.dynamic_batching)
+    if side_mode:
+        import bench_modes
+        if args.copy_calibration > 0:
+            res = bench_modes.copy_calibration(args.copy_calibration)
+        elif args.per_token_grid:
+            res = bench_modes.per_token_grid(args)
+        elif args.sweep_variants:
+            res = bench_modes.sweep_variants()
+        elif args.sweep_k:
+            res = bench_modes.sweep_k()
+        else:
+            res = bench_modes.dynamic_batching_bench(args)
+        print(json.dumps(res), flush=True)
+        return
+    if n == 5:
+        print(json.dumps(verify_loop_bench(args, with_logits)), flush=True)
+        return
+
+    fig, (sets, attention, accept, append) = time_one_layer_config(n, args, with_logits, args.steps, args.warmup,
+                                                                   dev, with_ceiling=True)
+    ms_per_step = fig["ms_per_step"]
+    roofline = fig["roofline"]
+    workload_key = "config%d_%s" % (n, args.layout) + ("_tree_rows%d" % args.tree_rows if args.tree_rows else "")
+    traffic, traffic_source = read_traffic(workload_key)
+    roofline.update({
+        "traffic": traffic, "traffic_source": traffic_source,
+        # context, not the peak: a plain read-only streaming kernel over one K arena, same run
+        "measured_read_ceiling": fig["ceiling"],
+        "frac_of_measured_ceiling": round(roofline["achieved"] / fig["ceiling"], 4),
+        "device_reported": device_memory_figures(),
+    })
+    b0 = sets[0]["b"]
     result = {
         "metric": "verified tokens/s (attention + greedy accept + KV append, 1 layer)",
-        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "value": round(fig["value"], 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if sets[0]["b"].dtype == torch.bfloat16 else "f16", "data": "synthetic",
+        "dtype": "bf16" if b0.dtype == torch.bfloat16 else "f16", "data": "synthetic",
         "config": {"workload": "BASELINE config %d: %s" % (n, CONFIG_NAMES[n]), "layout": args.layout,
-                   "B": sets[0]["b"].B, "H": sets[0]["b"].H, "D": sets[0]["b"].D,
-                   "query_rows_per_step": rows_per_step, "accepted_per_step": accepted_per_step,
-                   "logits": with_logits, "buffer_sets": len(sets),
+                   "B": b0.B, "H": b0.H, "D": b0.D,
+                   "query_rows_per_step": fig["rows_per_step"], "accepted_per_step": fig["accepted_per_step"],
+                   "logits": LOGITS_NOTE if with_logits else None, "buffer_sets": len(sets),
                    "variant": "write-through + advance" if args.write_through else "verify + append",
                    "attention_variant": args.attention_variant, "tree": args.tree,
                    "tree_rows": args.tree_rows or None},
-        "query_tokens_per_s": round(rows_per_step / (ms_per_step * 1e-3), 1),
+        "query_tokens_per_s": round(fig["query_tokens_per_s"], 1),
         "roofline": roofline,
     }
 
@@ -331,266 +409,39 @@ def main():
                                   "append_call": round(time_call(append), 5)}
 
     if not args.no_ablation and not args.tree:      # the padded ablation is the causal method's
-        result["padded_ablation"] = padded_ablation(sets, args, with_logits, alg_bytes, ms_per_step)
+        result["padded_ablation"] = padded_ablation(sets, args, with_logits, fig["alg_bytes"], ms_per_step)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(sets[0]["b"], with_logits)
+        result["cpu_baseline"], result["parity"] = cpu_baseline(sets[0], with_logits, tree=bool(args.tree),
+                                                                write_through=args.write_through)
+    del sets, attention, accept, append
+    torch.cuda.empty_cache()
+
+    # The metric is quoted for B = 8 .. 128: the other three one-GPU configurations, each timed
+    # briefly in the same run (config 5: one repetition of the 32-layer, 20-step loop).
+    if not args.no_all_configs and n == 4 and not (args.tree or args.write_through or args.attention_variant == "valu"):
+        others = []
+        for m, steps, warmup in ((2, 400, 40), (3, 150, 15)):
+            f, keep = time_one_layer_config(m, args, with_logits, steps, warmup, dev, with_ceiling=False)
+            mb = keep[0][0]["b"]
+            others.append({"config": m, "workload": CONFIG_NAMES[m], "B": mb.B,
+                           "dtype": "bf16" if mb.dtype == torch.bfloat16 else "f16", "steps": steps,
+                           "ms_per_step": round(f["ms_per_step"], 5), "value": round(f["value"], 1),
+                           "query_tokens_per_s": round(f["query_tokens_per_s"], 1), "roofline": f["roofline"]})
+            del keep, f
+            torch.cuda.empty_cache()
+        loop_args = argparse.Namespace(**vars(args))
+        loop_args.steps = 1
+        r5 = verify_loop_bench(loop_args, with_logits)
+        others.append({"config": 5, "workload": r5["config"]["workload"], "B": 128, "dtype": r5["dtype"],
+                       "steps": r5["steps"], "ms_per_step": r5["ms_per_step"], "value": r5["value"],
+                       "query_tokens_per_s": r5["query_tokens_per_s"],
+                       "note": "a step here is one 32-layer verify step (32 attention calls + accept + append)",
+                       "roofline": {k: r5["roofline"][k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac",
+                                                                  "achieved_call", "frac_call",
+                                                                  "algorithmic_bytes_per_launch", "kernel_ms",
+                                                                  "call_ms", "launches_timed")}})
+        result["all_configs"] = others
     print(json.dumps(result), flush=True)
-
-
-def dynamic_batching_bench(args, B=64, H=32, D=128, n_steps=120, region=4096):
-    """Dynamic batching (the paper's Sec. 4.4 proposal, not implemented there): every slot of the
-    batch serves a stream of samples; when its sample finishes, the slot brings no rows for one
-    step (k_i = 0) and then starts a new sample in a FRESH region of the arena with a new cached
-    length.  Per-sample start locations make this free: nothing is moved or padded.  The
-    lengths advance on the device; retirements follow a fixed seeded schedule, so the host
-    never reads anything back.  Reports the throughput of the drifting batch next to that of
-    the same loop with no retirements."""
-    import numpy as np
-    import torch
-    import paper_2405_07542_amd as ems
-    from workloads import make_batch
-    dev = "cuda:0"
-    dtype = torch.bfloat16
-
-    def run(retire):
-        rng = np.random.default_rng(77)
-        lifetimes = rng.integers(8, 40, size=(B, 64))          # steps each successive sample of a slot lives
-        prompt = rng.integers(256, 2049, size=(B, 64))         # its cached length when it enters
-        n_regions = B * (2 + n_steps // 8) if retire else B
-        rows = n_regions * region
-        base = make_batch([1], [1], H=H, D=D, dtype=dtype, seed=78, rows=8, device=dev)
-        # the arena's content does not matter for timing; it must only be finite
-        k_arena = torch.randn(rows * H * D // 2, device=dev, dtype=torch.float32).view(torch.int16).view(dtype)
-        k_arena = torch.nan_to_num(k_arena, nan=0.0, posinf=1.0, neginf=-1.0).clamp_(-4, 4)
-        v_arena = k_arena.roll(12345)
-        cache = ems.kv_cache(k_arena, v_arena, H * D, D, rows)
-        kv_start = torch.arange(B, dtype=torch.int32, device=dev) * region
-        kv_len = torch.tensor(prompt[:, 0], dtype=torch.int32, device=dev)
-        next_region, gen_idx = B, np.zeros(B, dtype=np.int64)
-        left = lifetimes[:, 0].copy()
-        plan = []                                               # per step: device tensors + host-planned updates
-        for step in range(n_steps):
-            k = [int(rng.integers(1, 12)) if left[s] > 0 else 0 for s in range(B)]
-            T = sum(k)
-            cu = torch.tensor(np.concatenate([[0], np.cumsum(k)]), dtype=torch.int32, device=dev)
-            q = torch.randn((T, H, D), device=dev, dtype=torch.float32).to(dtype)
-            ids = torch.randint(0, 50272, (T,), device=dev, dtype=torch.int32)
-            tgt = ids.roll(-1).clone()
-            tgt[torch.rand(T, device=dev) > 0.7] += 1           # drafts agree with probability 0.7
-            refill = []
-            for s in range(B):
-                if left[s] > 0:
-                    left[s] -= 1
-                    if not retire:
-                        left[s] = 1
-                elif retire:                                     # the slot sat out this step: new sample next step
-                    gen_idx[s] += 1
-                    refill.append((s, next_region * region, int(prompt[s, gen_idx[s] % 64])))
-                    left[s] = lifetimes[s, gen_idx[s] % 64]
-                    next_region += 1
-            assert next_region <= n_regions
-            upd = None
-            if refill:
-                idx = torch.tensor([r[0] for r in refill], device=dev)
-                upd = (idx, torch.tensor([r[1] for r in refill], dtype=torch.int32, device=dev),
-                       torch.tensor([r[2] for r in refill], dtype=torch.int32, device=dev))
-            plan.append((T, cu, q, q.roll(1, 0), q.roll(2, 0), ids, tgt, upd, max(k)))
-        ws = torch.empty(ems.ems_attention_workspace_bytes(B, 16 * B, H, D, region), dtype=torch.uint8, device=dev)
-        out = torch.empty((16 * B, H, D), dtype=dtype, device=dev)
-        accepted = torch.empty(B, dtype=torch.int32, device=dev)
-        accepted_cu = torch.empty(B + 1, dtype=torch.int32, device=dev)
-        total_acc = torch.zeros((), dtype=torch.int64, device=dev)
-        start0, len0 = kv_start.clone(), kv_len.clone()
-
-        def loop(count):
-            kv_start.copy_(start0)
-            kv_len.copy_(len0)
-            for T, cu, q, kn, vn, ids, tgt, upd, max_k in plan:
-                ems.ems_verify_attention(q, kn, vn, cache, cu, kv_start, kv_len, out[:T], max_k=16,
-                                         max_kv_len=region - 16, scale=D ** -0.5, workspace=ws)
-                ems.ems_greedy_accept(None, tgt, ids, cu, accepted, accepted_cu, None)
-                ems.ems_kv_append([kn], [vn], [cache], cu, accepted, kv_start, kv_len, kv_len)
-                if count:
-                    total_acc.add_(accepted_cu[-1])
-                if upd is not None:                              # admit the new samples (device-side writes)
-                    kv_start[upd[0]] = upd[1]
-                    kv_len[upd[0]] = upd[2]
-        loop(False)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        loop(True)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        rows_total = sum(p[0] for p in plan)
-        return {"ms_per_step": round(dt * 1e3 / n_steps, 4), "verified_tokens_per_s": round(int(total_acc) / dt, 1),
-                "query_tokens_per_s": round(rows_total / dt, 1), "regions_used": int(next_region),
-                "mean_live_samples": round(float(np.mean([sum(1 for x in np.diff(p[1].cpu().numpy()) if x > 0)
-                                                         for p in plan])), 1)}
-
-    return {"mode": "dynamic batching, 1 layer, B=%d slots, %d steps, bf16, rows per live sample U[1,11]" % (B, n_steps),
-            "static_batch": run(False), "dynamic_batch": run(True)}
-
-
-def sweep_k():
-    """Attention-call time as the number of rows per sample grows, 512 cached tokens per sample
-    (the paper's Fig. 5 measures the whole model this way: 16.6 ms at 1 token vs 22.6 ms at 5
-    tokens per sample, B=16, one A100).  Here only the attention path is timed."""
-    import torch
-    import paper_2405_07542_amd as ems
-    from workloads import make_batch
-    dev = "cuda:0"
-    rows = []
-    for B in (4, 16):
-        for k in range(1, 9):
-            sets = []
-            for v in range(4):
-                b = make_batch([512] * B, [k] * B, H=32, D=128, dtype=torch.float16, seed=900 + 10 * k + v,
-                               capacity=1024, device=dev)
-                ws = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len),
-                                 dtype=torch.uint8, device=dev)
-                sets.append((b, ws, torch.empty_like(b.q),
-                             ems.kv_cache(b.k_cache, b.v_cache, b.row_stride, b.head_stride, b.rows)))
-
-            def call(s):
-                b, ws, out, cache = s
-                ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, b.kv_start, b.kv_len, out,
-                                         max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws)
-            for i in range(8):
-                call(sets[i % 4])
-            torch.cuda.synchronize()
-            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            reps = 200
-            ev0.record()
-            for i in range(reps):
-                call(sets[i % 4])
-            ev1.record()
-            torch.cuda.synchronize()
-            rows.append({"B": B, "rows_per_sample": k, "attention_call_us": round(ev0.elapsed_time(ev1) / reps * 1e3, 2)})
-    return {"sweep": "attention call time vs rows per sample, kv_len=512, H=32, D=128, fp16", "results": rows}
-
-
-def per_token_rows_as_samples(b):
-    """Index arrays that present every packed row of `b` as a sample of its own (k = 1) whose cache is
-    its real sample's cache plus the new rows before it -- which must already have been written
-    through to rows kv_len + j.  This is the paper's formulation (Sec. 3.2 with the grid of Appendix
-    D): K/V of all new tokens stored first, then one work item per (head, token)."""
-    import torch
-    k = (b.cu_seqlens[1:] - b.cu_seqlens[:-1]).long()
-    sample = torch.repeat_interleave(torch.arange(b.B, device=k.device), k)
-    pos = torch.arange(b.T, device=k.device) - b.cu_seqlens[:-1].long()[sample]
-    cu = torch.arange(b.T + 1, dtype=torch.int32, device=k.device)
-    kv_start = b.kv_start[sample].to(torch.int32)
-    kv_len = (b.kv_len.long()[sample] + pos).to(torch.int32)
-    return cu, kv_start.contiguous(), kv_len.contiguous()
-
-
-def per_token_grid(args, reps=60):
-    import torch
-    import paper_2405_07542_amd as ems
-    from workloads import make_config
-    dev = "cuda:0"
-    sets = []
-    for v in range(3):
-        b = make_config(4, device=dev, layout=args.layout, with_logits=False, variant=v)
-        cache = ems.kv_cache(b.k_cache, b.v_cache, b.row_stride, b.head_stride, b.rows)
-        ws = torch.empty(ems.ems_attention_workspace_bytes(b.T, b.T, b.H, b.D, b.max_kv_len + b.max_k),
-                         dtype=torch.uint8, device=dev)
-        out = torch.empty_like(b.q)
-        # paper order: the new rows' K/V enter the cache first (one write-through call), then ...
-        ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, b.kv_start, b.kv_len, out,
-                                 max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws,
-                                 write_through=True)
-        shared_out = out.clone()
-        sets.append((b, cache, ws, out, per_token_rows_as_samples(b), shared_out))
-    torch.cuda.synchronize()
-
-    def shared(s):
-        b, cache, ws, out, _, _ = s
-        ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, b.kv_start, b.kv_len, out,
-                                 max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws)
-
-    def per_token(s):
-        b, cache, ws, out, (cu, ks, kl), _ = s
-        ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, cu, ks, kl, out, max_k=1,
-                                 max_kv_len=b.max_kv_len + b.max_k, scale=b.scale, workspace=ws)
-
-    res = {}
-    for name, fn in (("shared_kv", shared), ("per_token", per_token)):
-        for i in range(6):
-            fn(sets[i % 3])
-        torch.cuda.synchronize()
-        ems.ems_profile_enable(reps)
-        for i in range(reps):
-            fn(sets[i % 3])
-        torch.cuda.synchronize()
-        ms, n = ems.ems_profile_read()
-        ems.ems_profile_enable(0)
-        res[name + "_kernel_us"] = round(ms / n * 1e3, 1)
-    # the two formulations agree on every output row (same tolerance as against the oracle)
-    worst = 0.0
-    for s in sets:
-        per_token(s)
-        torch.cuda.synchronize()
-        worst = max(worst, float((s[3].float() - s[5].float()).abs().max()))
-    b = sets[0][0]
-    rows = float(sum(s[0].T for s in sets)) / len(sets)
-    res.update({"mode": "paper's launch shape (one work item per head and packed token) vs shared K/V, config 4 attention",
-                "layout": args.layout, "packed_rows": rows, "max_abs_difference_of_outputs": worst,
-                "slowdown": round(res["per_token_kernel_us"] / res["shared_kv_kernel_us"], 2)})
-    return res
-
-
-def sweep_variants(B=64, L=2048, ks=(1, 2, 4, 6, 8, 12, 16, 32, 64)):
-    """The two formulations of the attention kernel on one HBM-bound shape (config 4's batch and
-    mean cache length, every sample with the same k): kernel time from HIP events around the main
-    kernel, and the algorithmic bandwidth it amounts to.  The matrix-core path costs the same for
-    any k <= 16, ~10 % more for 17..32 (the wider kernel) and ~1.6x for 33..64 (still one stream of the
-    cache, but the wave is then bound by its own arithmetic);
-    the vector-ALU path pays per row."""
-    import torch
-    import paper_2405_07542_amd as ems
-    from workloads import make_batch
-    dev = "cuda:0"
-    out_rows = []
-    for k in ks:
-        sets = []
-        for v in range(3):
-            b = make_batch([L] * B, [k] * B, H=32, D=128, dtype=torch.bfloat16, seed=700 + 10 * k + v,
-                           capacity=L + 16, device=dev)
-            ws = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len),
-                             dtype=torch.uint8, device=dev)
-            sets.append((b, ws, torch.empty_like(b.q),
-                         ems.kv_cache(b.k_cache, b.v_cache, b.row_stride, b.head_stride, b.rows)))
-        alg = attention_algorithmic_bytes(sets[0][0], 2)
-        row = {"rows_per_sample": k, "algorithmic_bytes": alg}
-        for name, variant in (("mfma", ems.EMS_ATTN_MFMA), ("valu", ems.EMS_ATTN_VALU)):
-            if variant == ems.EMS_ATTN_VALU and k > 16:      # beyond 16 rows only the matrix-core kernels exist
-                continue
-            ems.ems_set_attention_variant(variant)
-
-            def call(s):
-                b, ws, out, cache = s
-                ems.ems_verify_attention(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, b.kv_start, b.kv_len, out,
-                                         max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws)
-            for i in range(6):
-                call(sets[i % 3])
-            torch.cuda.synchronize()
-            reps = 60
-            ems.ems_profile_enable(reps)
-            for i in range(reps):
-                call(sets[i % 3])
-            torch.cuda.synchronize()
-            ms, n = ems.ems_profile_read()
-            ems.ems_profile_enable(0)
-            us = ms / n * 1e3
-            row[name + "_kernel_us"] = round(us, 2)
-            row[name + "_gbs"] = round(alg / (us * 1e-6) / 1e9, 1)
-        ems.ems_set_attention_variant(ems.EMS_ATTN_MFMA)
-        out_rows.append(row)
-        del sets
-        torch.cuda.empty_cache()
-    return {"sweep": "attention kernel time, matrix-core vs vector-ALU formulation, B=%d, kv_len=%d, H=32, D=128, bf16"
-                     % (B, L), "results": out_rows}
 
 
 def verify_loop_bench(args, with_logits):
@@ -632,7 +483,7 @@ def verify_loop_bench(args, with_logits):
         run_loop(True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    attn_ms_total, launches = ems.ems_profile_read()
+    attn_ms_total, call_ms_total, launches = ems.ems_profile_read_calls()
     ems.ems_profile_enable(0)
     n_steps = reps * args.loop_steps
     ms_per_step = (t1 - t0) * 1e3 / n_steps
@@ -648,7 +499,9 @@ def verify_loop_bench(args, with_logits):
         L = lens + np.round(grown * frac[s])            # lengths at step s (linear in the step, +-1 row)
         alg += (2 * L.sum() * hd * 2 + 4 * st.T * hd * 2 + (3 * loop.B + 1) * 4) * args.layers
     attn_ms = attn_ms_total / max(1, launches)
+    call_ms = call_ms_total / max(1, launches)
     achieved = alg / (args.loop_steps * args.layers) / (attn_ms * 1e-3) / 1e9
+    achieved_call = alg / (args.loop_steps * args.layers) / (call_ms * 1e-3) / 1e9
     return {
         "metric": "verified tokens/s (32-layer verify loop: attention per layer + greedy accept + KV append)",
         "value": round(accepted / (ms_per_step * args.loop_steps * 1e-3), 1), "unit": "tokens/s",
@@ -657,13 +510,15 @@ def verify_loop_bench(args, with_logits):
         "data": "synthetic",
         "config": {"workload": "BASELINE config 5: %d-layer verify loop, B=128, %d successive steps" %
                    (args.layers, args.loop_steps), "layout": args.layout, "layers": args.layers,
-                   "accepted_per_loop": accepted, "query_rows_per_loop": rows, "logits": with_logits,
+                   "accepted_per_loop": accepted, "query_rows_per_loop": rows,
+                   "logits": LOGITS_NOTE if with_logits else None,
                    "cache_GB": round(2 * args.layers * loop.rows * hd * 2 / 1e9, 1)},
         "query_tokens_per_s": round(rows / (ms_per_step * args.loop_steps * 1e-3), 1),
         "roofline": {"bound": "hbm", "kernel": "verify_attention_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "achieved_call": round(achieved_call, 1), "frac_call": round(achieved_call / HBM_PEAK_GBS, 4),
                      "traffic": None, "algorithmic_bytes_per_launch": alg / (args.loop_steps * args.layers),
-                     "kernel_ms": round(attn_ms, 5), "launches_timed": launches},
+                     "kernel_ms": round(attn_ms, 5), "call_ms": round(call_ms, 5), "launches_timed": launches},
     }
 
 
@@ -694,7 +549,7 @@ def padded_ablation(sets, args, with_logits, unpadded_alg_bytes, unpadded_ms):
             cu=torch.arange(0, Tp + 1, p.k_max, dtype=torch.int32, device=dev),
             cache=ems.kv_cache(p.k_cache, p.v_cache, p.row_stride, p.head_stride, p.rows),
             out=torch.empty_like(p.q_pad),
-            ws=torch.empty(ems.ems_attention_workspace_bytes(p.B, Tp, p.H, p.D, p.l_pad), dtype=torch.uint8, device=dev),
+            ws=torch.empty(ems.ems_workspace_bytes(p.B, Tp, p.H, p.D, p.l_pad), dtype=torch.uint8, device=dev),
             ws_acc=torch.empty(max(8, ems.ems_accept_workspace_bytes(Tp, b.V)), dtype=torch.uint8, device=dev),
             accepted=torch.empty(b.B, dtype=torch.int32, device=dev),
             accepted_cu=torch.empty(b.B + 1, dtype=torch.int32, device=dev),
@@ -746,23 +601,27 @@ def padded_ablation(sets, args, with_logits, unpadded_alg_bytes, unpadded_ms):
     }
 
 
-def cpu_baseline(b, with_logits, budget_s=15.0):
-    """The oracle, as it stands, on the host cores, over the first samples of the batch."""
+def cpu_baseline(st, with_logits, budget_s=15.0, tree=False, write_through=False):
+    """The oracle, as it stands, on the host cores, over the first samples of buffer set `st`'s
+    batch -- timed as the CPU baseline, and compared with what the HIP path left in that same
+    buffer set (its last timed step): returns (cpu_baseline, parity)."""
     import numpy as np
+    import torch
     import oracle
-    from workloads import bits
+    from workloads import arena_view, bits
+    b = st["b"]
     cu = b.cu_seqlens.cpu().numpy()
     ks = b.kv_start.cpu().numpy()
     kl = b.kv_len.cpu().numpy()
-    # token-major view of the sampled caches only (the arena may be tens of GB)
+    Kv = arena_view(b.k_cache, b.layout, b.rows, b.H, b.D)
+    Vv = arena_view(b.v_cache, b.layout, b.rows, b.H, b.D)
+
+    # token-major copies of the sampled caches only (the arena may be tens of GB)
     def run(ns):
         rows = int(cu[ns])
         if rows == 0:
-            return 0.0, 0
-        from workloads import arena_view
-        Kv = arena_view(b.k_cache, b.layout, b.rows, b.H, b.D)
-        Vv = arena_view(b.v_cache, b.layout, b.rows, b.H, b.D)
-        cap = int(max(kl[:ns])) + 16
+            return 0.0, 0, None
+        cap = int(max(kl[:ns])) + int(max(np.diff(cu[:ns + 1]))) + 1
         kc = np.zeros((ns * cap, b.H, b.D), dtype=np.uint16)
         vc = np.zeros((ns * cap, b.H, b.D), dtype=np.uint16)
         for i in range(ns):
@@ -774,35 +633,64 @@ def cpu_baseline(b, with_logits, budget_s=15.0):
         ids = b.input_ids[:rows].cpu().numpy()
         tgt = b.target_ids[:rows].cpu().numpy()
         t0 = time.perf_counter()
-        oracle.verify_attention(q, kn, vn, kc.reshape(-1), vc.reshape(-1), b.H * b.D, b.D, cu[:ns + 1],
-                                starts, kl[:ns], b.H, b.D, b.scale, b.dtype)
+        out = oracle.verify_attention(q, kn, vn, kc.reshape(-1), vc.reshape(-1), b.H * b.D, b.D, cu[:ns + 1],
+                                      starts, kl[:ns], b.H, b.D, b.scale, b.dtype)
         x = oracle.argmax(lg, b.dtype) if with_logits else tgt
-        acc, _, _ = oracle.greedy_accept(x, ids, cu[:ns + 1])
-        oracle.kv_append(kc.reshape(-1), vc.reshape(-1), b.H * b.D, b.D, kn, vn, cu[:ns + 1], acc, starts,
-                         kl[:ns], b.H, b.D)
-        return time.perf_counter() - t0, int(acc.sum())
+        acc, acc_cu, toks = oracle.greedy_accept(x, ids, cu[:ns + 1])
+        new_len = oracle.kv_append(kc.reshape(-1), vc.reshape(-1), b.H * b.D, b.D, kn, vn, cu[:ns + 1], acc,
+                                   starts, kl[:ns], b.H, b.D)
+        dt = time.perf_counter() - t0
+        return dt, int(acc.sum()), dict(out=out, x=x, acc=acc, acc_cu=acc_cu, toks=toks, new_len=new_len, kc=kc,
+                                        vc=vc, cap=cap, rows=rows)
 
     probe = max(1, min(2, b.B))
-    t_probe, _ = run(probe)
+    t_probe, _, _ = run(probe)
     ns = int(max(probe, min(b.B, budget_s / max(t_probe / probe, 1e-6))))
-    t, accepted = run(ns)
+    t, accepted, ref = run(ns)
     reps = 1
     while t < 1.5 and reps < 8:          # ~10-30 s of CPU work over all threads, for a steady figure
-        t2, a2 = run(ns)
+        t2, a2, _ = run(ns)
         t, accepted, reps = t + t2, accepted + a2, reps + 1
     cores = oracle.num_threads()
     # the same on one thread, over an eighth of the samples (context for the figure above)
     oracle.set_num_threads(1)
     try:
         n1 = max(1, ns // 8)
-        t1, a1 = run(n1)
+        t1, a1, _ = run(n1)
     finally:
         oracle.set_num_threads(cores)
-    return {"value": round(accepted / t, 2), "unit": "tokens/s", "cores": cores,
-            "kind": "oracle", "seconds": round(t, 3),
-            "sample": "first %d of %d samples of the same batch, all heads, one layer: fp64 oracle "
-                      "attention + arg-max + accept + append, %d time%s over" % (ns, b.B, reps, "" if reps == 1 else "s"),
-            "one_thread": {"value": round(a1 / t1, 2), "seconds": round(t1, 3), "sample": "first %d samples" % n1}}
+    baseline = {"value": round(accepted / t, 2), "unit": "tokens/s", "cores": cores,
+                "kind": "oracle", "seconds": round(t, 3),
+                "sample": "first %d of %d samples of the same batch, all heads, one layer: fp64 oracle "
+                          "attention + arg-max + accept + append, %d time%s over" % (ns, b.B, reps, "" if reps == 1 else "s"),
+                "one_thread": {"value": round(a1 / t1, 2), "seconds": round(t1, 3), "sample": "first %d samples" % n1}}
+
+    # Parity of the run that was just timed: what the HIP path left in this buffer set against
+    # the oracle on the same inputs (causal verify + append only: the tree and write-through
+    # variants have their own oracle functions and are compared in the tests).
+    parity = None
+    if ref is not None and not tree and not write_through:
+        rows = ref["rows"]
+        got = st["out"][:rows].double().cpu().numpy()
+        err = float(np.abs(got - ref["out"]).max())
+        n_acc = int(ref["acc_cu"][ns])
+        cache_equal = bool(np.array_equal(st["new_len"][:ns].cpu().numpy(), ref["new_len"]))
+        for i in range(ns):                      # the rows the append wrote, in the arena itself
+            a, cap = int(ref["acc"][i]), ref["cap"]
+            lo = int(ks[i] + kl[i])
+            cache_equal &= bool(np.array_equal(bits(Kv[lo:lo + a]), ref["kc"][i * cap + kl[i]:i * cap + kl[i] + a]))
+            cache_equal &= bool(np.array_equal(bits(Vv[lo:lo + a]), ref["vc"][i * cap + kl[i]:i * cap + kl[i] + a]))
+        parity = {
+            "against": "fp64 oracle, same inputs, buffer set 0, first %d of %d samples, %d rows, every element" % (ns, b.B, rows),
+            "attention_max_abs_err": err, "bar": 2e-3, "attention_within_bar": bool(err <= 2e-3),
+            "out_dtype": "bf16" if st["out"].dtype == torch.bfloat16 else "f16",
+            "target_ids_equal": bool(np.array_equal(st["target"][:rows].cpu().numpy(), ref["x"])),
+            "accepted_equal": bool(np.array_equal(st["accepted"][:ns].cpu().numpy(), ref["acc"])),
+            "accepted_cu_equal": bool(np.array_equal(st["accepted_cu"][:ns + 1].cpu().numpy(), ref["acc_cu"])),
+            "out_tokens_equal": bool(np.array_equal(st["out_tokens"][:n_acc].cpu().numpy(), ref["toks"])),
+            "cache_equal": cache_equal,
+        }
+    return baseline, parity
 
 
 if __name__ == "__main__":

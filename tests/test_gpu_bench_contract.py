@@ -38,3 +38,14 @@ def test_a_short_run_prints_one_json_line_with_the_agreed_keys():
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["unit"] == d["unit"] and c["sample"]
     assert d["value"] > 100 * c["value"]          # a sanity bound, not a target
+    # the timed run itself is compared with the oracle, and the figure is in the line
+    p = d["parity"]
+    assert p["attention_within_bar"] and p["attention_max_abs_err"] <= p["bar"] == 2e-3
+    for key in ("target_ids_equal", "accepted_equal", "accepted_cu_equal", "out_tokens_equal", "cache_equal"):
+        assert p[key] is True, key
+    # the whole range of the metric, B = 8 .. 128, is in the same line
+    assert [c["config"] for c in d["all_configs"]] == [2, 3, 5] and [c["B"] for c in d["all_configs"]] == [8, 32, 128]
+    for c in d["all_configs"]:
+        assert c["value"] > 0 and c["ms_per_step"] > 0 and 0.2 < c["roofline"]["frac"] < 1.0
+    src = r["traffic_source"]
+    assert src is None or (src["stale"] is False) == (r["traffic"] is not None)

@@ -157,10 +157,14 @@ def test_tree_entry_points_reject_bad_arguments():
     out = torch.empty_like(b.q)
     ws = torch.empty(ems.ems_attention_workspace_bytes(b.B, b.T, b.H, b.D, b.max_kv_len), dtype=torch.uint8, device="cuda")
     cache = ems.kv_cache(b.k_cache, b.v_cache, b.row_stride, b.head_stride, b.rows)
-    with pytest.raises(ems.EmsError) as e:
+    with pytest.raises(TypeError, match="parent must be a tensor"):      # the binding refuses it ...
         ems.ems_tree_verify_attention(b.q, b.k_new, b.v_new, cache, b.cu_seqlens, None, b.kv_start, b.kv_len, out,
                                       max_k=b.max_k, max_kv_len=b.max_kv_len, scale=b.scale, workspace=ws)
-    assert e.value.status == ems.EMS_ERR_INVALID_ARG
+    import ctypes                                                        # ... and so does the C layer itself
+    assert ems.lib().ems_tree_verify_attention(
+        b.q.data_ptr(), b.k_new.data_ptr(), b.v_new.data_ptr(), ctypes.byref(cache), b.cu_seqlens.data_ptr(), None,
+        b.kv_start.data_ptr(), b.kv_len.data_ptr(), out.data_ptr(), ems.EMS_F16, b.B, b.T, b.H, b.D, b.max_k,
+        b.max_kv_len, b.scale, ems.EMS_F16, ws.data_ptr(), ws.numel(), None) == ems.EMS_ERR_INVALID_ARG
     ems.ems_set_attention_variant(ems.EMS_ATTN_VALU)
     try:
         with pytest.raises(ems.EmsError) as e:

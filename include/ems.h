@@ -162,6 +162,30 @@ EMS_API ems_status ems_kv_advance(
     const int32_t* kv_len, const int32_t* accepted, int32_t* kv_len_out, int B, void* hip_stream);
 
 /*
+ * ems_verify_attention for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors as ems_verify_attention, minus the workspace: the split-KV partials go to a buffer
+ * of EMS_NOALLOC_SCRATCH_BYTES that is part of the library's own device image (each GPU the
+ * library runs on holds its copy from the first call on that GPU until the process ends).
+ * The call allocates and frees nothing.
+ *   Limits: max_k <= EMS_ROWS_PER_GROUP (the 16-row kernel) and a launch whose partials fit
+ *   the buffer (any B <= 8192 at D <= 128 on a GPU of up to 256 compute units); beyond
+ *   either -> EMS_ERR_UNSUPPORTED with the sizes in the message.
+ *   Every call on a GPU shares that GPU's buffer: calls that overlap in time on one GPU
+ *   (two streams, two threads) race on it and give wrong results; calls ordered on one stream
+ *   or otherwise serialised are safe, and a call needs nothing from the call before it (the
+ *   buffer holds no state that must be cleared).
+ */
+#define EMS_NOALLOC_SCRATCH_BYTES (18u << 20)
+EMS_API ems_status ems_verify_attention_noalloc(
+    const void* q, const void* k_new, const void* v_new,
+    const ems_kv_cache* cache,
+    const int32_t* cu_seqlens, const int32_t* kv_start, const int32_t* kv_len,
+    void* out, ems_dtype out_dtype,
+    int B, int T, int H, int D, int max_k, int max_kv_len,
+    float scale, ems_dtype dtype, void* hip_stream);
+
+/*
  * "Unpad input tokens" (Appendix D, Alg. 1): concatenate the input tokens of all samples and
  * keep each sample's count.  The per-sample lists are given as a padded array:
  *   padded_ids  device int32 [B, k_max]: sample i's tokens in its first token_nums[i] slots

@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
                                            ctypes.c_float, i32, vp, sz, vp]
         L.ems_verify_attention_write_through.restype = i32
         L.ems_verify_attention_write_through.argtypes = L.ems_verify_attention.argtypes
+        L.ems_verify_attention_noalloc.restype = i32
+        L.ems_verify_attention_noalloc.argtypes = [vp, vp, vp, ctypes.POINTER(KvCacheStruct), vp, vp, vp,
+                                                   vp, i32, i32, i32, i32, i32, i32, i32,
+                                                   ctypes.c_float, i32, vp]
         L.ems_kv_advance.restype = i32
         L.ems_kv_advance.argtypes = [vp, vp, vp, i32, vp]
         L.ems_tree_verify_attention.restype = i32
@@ -267,6 +271,22 @@ def ems_verify_attention(q, k_new, v_new, cache: KvCacheStruct, cu_seqlens, kv_s
         _ptr(kv_len), _ptr(out), _DT[out.dtype], B, T, H, D, int(max_k), int(max_kv_len),
         float(scale), _DT[q.dtype], _ptr(workspace), workspace.numel() * workspace.element_size(),
         _stream(stream)))
+
+
+def ems_verify_attention_noalloc(q, k_new, v_new, cache: KvCacheStruct, cu_seqlens, kv_start, kv_len,
+                                 out, *, max_k: int, max_kv_len: int, scale: float, stream=None) -> None:
+    """ems_verify_attention without a workspace: the partials go to the library's own device buffer."""
+    _need_packed(q, k_new, v_new, out)
+    T, H, D = q.shape
+    _need("kv_start", kv_start, _I32)
+    B = kv_start.numel()
+    _need("kv_len", kv_len, _I32, numel=B)
+    _need("cu_seqlens", cu_seqlens, _I32, numel=B + 1)
+    _resident()
+    _check(lib().ems_verify_attention_noalloc(
+        _ptr(q), _ptr(k_new), _ptr(v_new), ctypes.byref(cache), _ptr(cu_seqlens), _ptr(kv_start),
+        _ptr(kv_len), _ptr(out), _DT[out.dtype], B, T, H, D, int(max_k), int(max_kv_len),
+        float(scale), _DT[q.dtype], _stream(stream)))
 
 
 def ems_greedy_accept(logits: Optional[torch.Tensor], target_ids, input_ids, cu_seqlens,
@@ -499,6 +519,8 @@ def ems_profile_read_calls():
     return ms.value, ms_call.value, n.value
 
 
-__all__ = ["ems_workspace_bytes", "ems_profile_read_calls", "ems_pack_tokens", "ems_validate_tree", "ems_tree_verify_attention", "ems_tree_accept", "ems_kv_append_rows", "ems_stream_read_probe", "ems_set_attention_variant", "ems_get_attention_variant", "EMS_ATTN_MFMA", "EMS_ATTN_VALU", "ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
+EMS_NOALLOC_SCRATCH_BYTES = 18 << 20
+
+__all__ = ["ems_verify_attention_noalloc", "EMS_NOALLOC_SCRATCH_BYTES", "ems_workspace_bytes", "ems_profile_read_calls", "ems_pack_tokens", "ems_validate_tree", "ems_tree_verify_attention", "ems_tree_accept", "ems_kv_append_rows", "ems_stream_read_probe", "ems_set_attention_variant", "ems_get_attention_variant", "EMS_ATTN_MFMA", "EMS_ATTN_VALU", "ems_verify_attention_write_through", "ems_kv_advance", "ems_padded_verify_attention", "ems_padded_kv_append", "ems_profile_enable", "ems_profile_read", "EmsError", "KvCacheStruct", "kv_cache", "lib", "ems_attention_workspace_bytes",
            "ems_accept_workspace_bytes", "ems_verify_attention", "ems_greedy_accept",
            "ems_kv_append", "ems_validate_inputs", "EMS_F16", "EMS_BF16", "EMS_F32"]

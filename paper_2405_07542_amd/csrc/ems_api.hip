@@ -296,6 +296,63 @@ ems_status ems_verify_attention_write_through(const void* q, const void* k_new, 
                          hip_stream, nullptr, true);
 }
 
+}  // extern "C"
+
+// The buffer of ems_verify_attention_noalloc: part of this library's device image, one copy per
+// GPU.  In host code its name is only a handle for hipGetSymbolAddress; the device address is
+// looked up once per device (with that device current) and kept.  (No `used` attribute: the
+// compiler gives a static device variable a global symbol in the device image exactly when host
+// code refers to it, as noalloc_scratch() does; marked `used` it stays a local symbol there,
+// the runtime cannot find it by name, and the first lookup aborts the process.)
+static __device__ __align__(256) unsigned char scratch[EMS_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+ems_status noalloc_scratch(void** ptr) {
+    static std::atomic<void*> per_device[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail("hipGetDevice", e);
+    if (dev < 0 || dev >= 64) return fail(EMS_ERR_UNSUPPORTED, "device ordinal %d beyond the 64 this call keeps track of", dev);
+    void* p = per_device[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr) return hip_fail("hipGetSymbolAddress(scratch)", e);
+        per_device[dev].store(p, std::memory_order_release);     // (threads that race here store the same address)
+    }
+    *ptr = p;
+    return EMS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ems_status ems_verify_attention_noalloc(const void* q, const void* k_new, const void* v_new,
+                                        const ems_kv_cache* cache, const int32_t* cu_seqlens,
+                                        const int32_t* kv_start, const int32_t* kv_len, void* out,
+                                        ems_dtype out_dtype, int B, int T, int H, int D, int max_k,
+                                        int max_kv_len, float scale, ems_dtype dtype, void* hip_stream) {
+    if (max_k > EMS_ROWS_PER_GROUP)
+        return fail(EMS_ERR_UNSUPPORTED, "ems_verify_attention_noalloc takes max_k <= %d, got %d", EMS_ROWS_PER_GROUP, max_k);
+    // what the launch would need, from the same arithmetic as the call with a workspace
+    if (B >= 1 && B <= kMaxB && H >= 1 && max_kv_len >= 0 && (D == 64 || D == 80 || D == 128)) {
+        const int blocks = attn_blocks_for(tile_upper_bound(B, H, max_kv_len, kRows16, max_k), resident_attn_blocks());
+        const size_t need = attn_ws_bytes_for(blocks, B, D, kRows16);
+        if (need > (size_t)EMS_NOALLOC_SCRATCH_BYTES)
+            return fail(EMS_ERR_UNSUPPORTED, "this launch needs %zu bytes for its partial results, the library's own "
+                        "buffer holds %zu (EMS_NOALLOC_SCRATCH_BYTES)", need, (size_t)EMS_NOALLOC_SCRATCH_BYTES);
+    }
+    void* ptr = nullptr;
+    if (T > 0) {
+        const ems_status st = noalloc_scratch(&ptr);
+        if (st != EMS_OK) return st;
+    }
+    return run_attention(q, k_new, v_new, cache, cu_seqlens, kv_start, kv_len, out, out_dtype, B, T,
+                         H, D, max_k, max_kv_len, scale, dtype, ptr, T > 0 ? (size_t)EMS_NOALLOC_SCRATCH_BYTES : 0,
+                         hip_stream, nullptr);
+}
+
 ems_status ems_tree_verify_attention(const void* q, const void* k_new, const void* v_new,
                                      const ems_kv_cache* cache, const int32_t* cu_seqlens,
                                      const int32_t* parent, const int32_t* kv_start,

@@ -227,3 +227,23 @@ def test_the_header_is_plain_c_and_the_library_is_usable_from_c(tmp_path):
     res = subprocess.run([exe, ems.LIB_PATH], capture_output=True, text=True, timeout=120)
     assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
     assert res.stdout.startswith("ok ")
+
+
+def test_the_noalloc_buffer_is_a_global_symbol_of_the_device_image(tmp_path):
+    """ems_verify_attention_noalloc finds its buffer by name (hipGetSymbolAddress); the runtime
+    aborts the process if the device image holds that name only as a local symbol -- which is
+    what happens when the static device array is not referred to by host code in a way the
+    compiler sees, or carries a `used` attribute.  Compile the API's device side alone and look."""
+    import subprocess
+    hipcc = "/opt/rocm/bin/hipcc"
+    readelf = "/opt/rocm/llvm/bin/llvm-readelf"
+    if not (os.path.exists(hipcc) and os.path.exists(readelf)):
+        pytest.skip("needs the ROCm compilers")
+    obj = str(tmp_path / "api_device.o")
+    subprocess.check_call([hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "--cuda-device-only", "--no-gpu-bundle-output",
+                           "-fPIC", "-fvisibility=hidden", "-c", os.path.join(ROOT, "paper_2405_07542_amd", "csrc", "ems_api.hip"),
+                           "-o", obj], stderr=subprocess.DEVNULL)
+    table = subprocess.run([readelf, "-s", obj], capture_output=True, text=True, check=True).stdout
+    rows = [l.split() for l in table.splitlines() if l.strip().endswith("scratch")]
+    assert rows, table
+    assert all(r[3] == "OBJECT" and r[4] == "GLOBAL" and int(r[2]) == ems.EMS_NOALLOC_SCRATCH_BYTES for r in rows), rows

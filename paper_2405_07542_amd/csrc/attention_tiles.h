@@ -48,6 +48,28 @@ __device__ __forceinline__ int tiles_of_sample_wide64(int k, int L) {
 }
 enum { kPlainLine = 0, kPaddedLine = 1, kWideLine = 2, kWide64Line = 3 };
 
+// prefix[1..B] holds each sample's tile count, prefix[0] = 0: turned into running sums by the
+// block's first wave (64 entries a pass); barriers before and after.
+__device__ __forceinline__ void scan_tile_counts(int32_t* prefix, int B) {
+    const int tid = threadIdx.x;
+    __syncthreads();
+    if (tid < kWave) {
+        int carry = 0;
+        for (int base = 1; base <= B; base += kWave) {
+            const int idx = base + tid;
+            int v = idx <= B ? prefix[idx] : 0;
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                int u = __shfl_up(v, off);
+                if (tid >= off) v += u;
+            }
+            if (idx <= B) prefix[idx] = v + carry;
+            carry += __shfl(v, kWave - 1);
+        }
+    }
+    __syncthreads();
+}
+
 // prefix[i] = H * sum_{j<i} tiles(j), i = 0..B, built by the whole block in LDS.
 template <int LINE>
 __device__ __forceinline__ void build_tile_prefix(const AttnParams& p, int32_t* prefix) {
@@ -58,23 +80,22 @@ __device__ __forceinline__ void build_tile_prefix(const AttnParams& p, int32_t* 
                         : LINE == kWide64Line ? p.H * tiles_of_sample_wide64(p.cu[i + 1] - p.cu[i], p.kv_len[i])
                                             : p.H * tiles_of_sample(p.cu[i + 1] - p.cu[i], p.kv_len[i]);
     if (tid == 0) prefix[0] = 0;
-    __syncthreads();
-    if (tid < kWave) {                        // one wave: inclusive scan, 64 entries a pass
-        int carry = 0;
-        for (int base = 1; base <= p.B; base += kWave) {
-            const int idx = base + tid;
-            int v = idx <= p.B ? prefix[idx] : 0;
-#pragma unroll
-            for (int off = 1; off < kWave; off <<= 1) {
-                int u = __shfl_up(v, off);
-                if (tid >= off) v += u;
-            }
-            if (idx <= p.B) prefix[idx] = v + carry;
-            carry += __shfl(v, kWave - 1);
-        }
-    }
-    __syncthreads();
+    scan_tile_counts(prefix, p.B);
 }
+
+// The tile line is cut into ranges that differ by at most one tile: of `waves` waves
+// (waves <= total, so no range is empty) the first total % waves own total / waves + 1 tiles
+// each, the others total / waves.  Only 32-bit divisions: a 64-bit one costs a wave most of
+// a microsecond before it has asked memory for anything.
+struct LineCut {
+    int q, r;          // tiles per wave (rounded down), waves that own one more
+    __device__ __forceinline__ LineCut(int total, int waves) : q(total / waves), r(total - (total / waves) * waves) {}
+    __device__ __forceinline__ int begin(int wave) const { return wave * q + min(wave, r); }
+    __device__ __forceinline__ int wave_of(int g) const {          // the wave whose range holds tile g
+        const int big = r * (q + 1);
+        return g < big ? g / (q + 1) : r + (g - big) / q;
+    }
+};
 
 // Head dims: 64 and 128 fill every lane; 80 (a row of 160 bytes) is run as a 96-wide
 // score product whose last k-step is half empty (the lane quarters g >= 2 re-read the

@@ -45,6 +45,17 @@ struct AttnParams {
 };
 
 constexpr int kMaxLdsBytes = 160 * 1024;   // LDS a workgroup may use on gfx950
+// LDS at the start of a 16-row attention workgroup: the B+1 tile prefix sums and, for batches of up
+// to kIndexStashMaxB samples, a copy of cu_seqlens, kv_len and kv_start (3B+1 words), so that a
+// wave's step from one sample to the next reads no global memory.
+constexpr int kIndexStashMaxB = 2048;
+constexpr size_t attn_prefix_lds_bytes(int B) { return (((size_t)(B + 1) * 4) + 15) & ~(size_t)15; }
+// (no_stash: the padded ablation, which has no such arrays, and the vector-ALU formulation, which
+// needs the room)
+constexpr size_t attn_stash_lds_bytes(int B, bool no_stash) {
+    return (no_stash || B > kIndexStashMaxB) ? 0 : ((((size_t)(3 * B + 1) * 4) + 15) & ~(size_t)15);
+}
+constexpr size_t attn_index_lds_bytes(int B, bool no_stash) { return attn_prefix_lds_bytes(B) + attn_stash_lds_bytes(B, no_stash); }
 // LDS bytes per workgroup of the vector-ALU formulation (prefix sums + wave-private state), D in {64, 128}
 size_t valu_attention_lds_bytes(int B, int D);
 

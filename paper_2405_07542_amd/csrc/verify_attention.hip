@@ -210,18 +210,34 @@ struct Segment {
 };
 
 // The segment that starts at flat tile index gpos (< gend); `i` is a sample at or before it.
+// `stash`: the workgroup's LDS copy of cu_seqlens [B+1], kv_len [B] and kv_start [B], or nullptr
+// (large batches, padded ablation: the arrays are read from global memory then).
 template <int D, bool PADDED>
-__device__ __forceinline__ Segment make_segment(const AttnParams& p, const int32_t* prefix, int i,
-                                                int gpos, int gend) {
+__device__ __forceinline__ Segment make_segment(const AttnParams& p, const int32_t* prefix,
+                                                const int32_t* stash, int i, int gpos, int gend) {
     Segment s;
     while (uniform(prefix[i + 1]) <= gpos) ++i;
     s.i = i;
+    int cu0 = 0, cu1 = 0, len = 0, start32 = 0;
+    if (!PADDED) {
+        if (stash != nullptr) {
+            cu0 = uniform(stash[i]);
+            cu1 = uniform(stash[i + 1]);
+            len = uniform(stash[p.B + 1 + i]);
+            start32 = uniform(stash[2 * p.B + 1 + i]);
+        } else {
+            cu0 = uniform(p.cu[i]);
+            cu1 = uniform(p.cu[i + 1]);
+            len = uniform(p.kv_len[i]);
+            start32 = uniform(p.kv_start[i]);
+        }
+    }
     // padded ablation: k_max rows and l_pad aligned cache rows for every sample
-    s.cu_i = PADDED ? i * p.k_max : uniform(p.cu[i]);
+    s.cu_i = PADDED ? i * p.k_max : cu0;
     // (never more than the 16 rows one MFMA tile holds, whatever cu_seqlens claims)
-    s.k = min(kMaxRows, PADDED ? p.k_max : uniform(p.cu[i + 1]) - s.cu_i);
-    s.L = PADDED ? p.l_pad : uniform(p.kv_len[i]);
-    const int64_t start = PADDED ? (int64_t)i * p.cap : (int64_t)uniform(p.kv_start[i]);
+    s.k = min(kMaxRows, PADDED ? p.k_max : cu1 - cu0);
+    s.L = PADDED ? p.l_pad : len;
+    const int64_t start = PADDED ? (int64_t)i * p.cap : (int64_t)start32;
     s.k_real = PADDED ? uniform(p.k_valid[i]) : s.k;
     const int nt = s.nt();
     const int rem = gpos - uniform(prefix[i]);
@@ -239,8 +255,8 @@ __device__ __forceinline__ Segment make_segment(const AttnParams& p, const int32
 // only a change of sample reads the index arrays again.
 template <int D, bool PADDED>
 __device__ __forceinline__ Segment next_segment(const AttnParams& p, const int32_t* prefix,
-                                                const Segment& c, int gpos, int gend) {
-    if (c.h + 1 >= p.H) return make_segment<D, PADDED>(p, prefix, c.i + 1, gpos, gend);
+                                                const int32_t* stash, const Segment& c, int gpos, int gend) {
+    if (c.h + 1 >= p.H) return make_segment<D, PADDED>(p, prefix, stash, c.i + 1, gpos, gend);
     Segment s = c;
     s.h = c.h + 1;
     s.t0 = 0;
@@ -263,14 +279,36 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     static_assert(!(VALU && PADDED), "the vector-ALU formulation exists for the unpadded layout only");
     static_assert(!(VALU && D == 80), "the vector-ALU formulation exists for head dims 64 and 128 only");
     typedef TileRegs<D> TR;
-    build_tile_prefix<PADDED ? kPaddedLine : kPlainLine>(p, prefix);
+    // Tile counts per sample and, for batches that fit, the index arrays themselves into LDS: one
+    // round trip to memory for everything a wave will ever need to know about the batch's shape.
+    int32_t* const stash_w = attn_stash_lds_bytes(p.B, PADDED || VALU) != 0
+                                 ? reinterpret_cast<int32_t*>(reinterpret_cast<char*>(prefix) + attn_prefix_lds_bytes(p.B))
+                                 : nullptr;
+    const int32_t* const stash = stash_w;
+    if (PADDED || stash_w == nullptr) {
+        build_tile_prefix<PADDED ? kPaddedLine : kPlainLine>(p, prefix);
+    } else {
+        for (int i = threadIdx.x; i < p.B; i += blockDim.x) {
+            const int c0 = p.cu[i], c1 = p.cu[i + 1], len = p.kv_len[i], start = p.kv_start[i];
+            prefix[i + 1] = p.H * tiles_of_sample(c1 - c0, len);
+            stash_w[i] = c0;
+            if (i == p.B - 1) stash_w[p.B] = c1;
+            stash_w[p.B + 1 + i] = len;
+            stash_w[2 * p.B + 1 + i] = start;
+        }
+        if (threadIdx.x == 0) prefix[0] = 0;
+        scan_tile_counts(prefix, p.B);
+    }
     if (blockIdx.x == 0)       // the merge kernel reads the tile prefix from the workspace header
         for (int i = threadIdx.x; i <= p.B; i += blockDim.x) p.ws_header[i] = prefix[i];
     const int total = prefix[p.B];
-    const int per = (total + p.num_waves - 1) / p.num_waves;
     const int wave = uniform((int)(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)));
-    const int gbeg = wave * per;
-    const int gend = min(total, gbeg + per);
+    // (a line of fewer tiles than waves is cut for as many waves as it has tiles, so that the
+    // waves that hold tiles are always the first ones, with no empty range in between)
+    const int num_waves = min(p.num_waves, total);
+    const LineCut cut(total, max(num_waves, 1));
+    const int gbeg = wave < num_waves ? uniform(cut.begin(wave)) : 0;
+    const int gend = wave < num_waves ? uniform(cut.begin(wave + 1)) : 0;
     const int lane = threadIdx.x & 63;
     const int n = lane & 15;       // query row (MFMA column) of this lane
     const int g = lane >> 4;       // which quarter of the k-slots / key rows
@@ -279,11 +317,11 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     // flags per wave: bit 0 = this wave parked the partial of the pair it continues, bit 1 =
     // that pair ends inside this wave's range.
     const int lw = uniform((int)(threadIdx.x >> 6));
-    float* const fold_lds = reinterpret_cast<float*>(reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15));
+    float* const fold_lds = reinterpret_cast<float*>(reinterpret_cast<char*>(prefix) + attn_index_lds_bytes(p.B, PADDED || VALU));
     int32_t* const fold_flags = reinterpret_cast<int32_t*>(fold_lds + (kWavesPerBlock - 1) * FoldSlot<D>::floats);
     const bool wg_fold = !VALU && p.wg_fold != 0;      // (the host leaves it off for very short walks)
     if (wg_fold && lane == 0) fold_flags[lw] = 0;
-    if (gbeg >= gend) {            // (only past the end of a short line) nothing to walk, nothing to merge
+    if (gbeg >= gend) {            // (only when the line has fewer tiles than there are waves) nothing to walk, nothing to merge
         if (wg_fold) __syncthreads();
         return;
     }
@@ -301,10 +339,10 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     // `nxt` the one after it (its index arrays are fetched a whole segment ahead); the loads
     // of flat tile c+1 -- possibly the first tile of `nxt` -- are issued before tile c is
     // consumed, so the stream of loads does not drain at a pair boundary.
-    Segment cur = make_segment<D, PADDED>(p, prefix, uniform(lo), gbeg, gend);
+    Segment cur = make_segment<D, PADDED>(p, prefix, stash, uniform(lo), gbeg, gend);
     int cur_end = gbeg + (cur.t1 - cur.t0);            // flat index one past cur's last tile
     Segment nxt = cur;
-    if (cur_end < gend) nxt = next_segment<D, PADDED>(p, prefix, cur, cur_end, gend);
+    if (cur_end < gend) nxt = next_segment<D, PADDED>(p, prefix, stash, cur, cur_end, gend);
 
     u32x4 qb[KS];                // Q^T of `cur` as the B operand of S^T = K Q^T
     u32x4 qn[KS];                // the same for `nxt`, fetched a whole segment ahead
@@ -313,7 +351,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
     int par_n = -1;              // token trees: parent of row n of `nxt`, fetched with its Q
     // vector-ALU formulation: per-row state in registers, Q rows and P in wave-private LDS
     ValuState vs;
-    char* const vlds = reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15) +
+    char* const vlds = reinterpret_cast<char*>(prefix) + attn_index_lds_bytes(p.B, PADDED || VALU) +
                        (threadIdx.x >> 6) * ValuLds<D>::bytes;
     float* const acc_lds = reinterpret_cast<float*>(vlds + ValuLds<D>::q_bytes + ValuLds<D>::p_bytes);
 
@@ -563,7 +601,7 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_kernel(AttnP
                 use_q(qn, cur.k);
                 begin_segment(cur);
                 if (cur_end < gend) {
-                    nxt = next_segment<D, PADDED>(p, prefix, cur, cur_end, gend);
+                    nxt = next_segment<D, PADDED>(p, prefix, stash, cur, cur_end, gend);
                     load_q(qn, nxt.new_off, nxt.k);
                     load_parent(nxt.cu_i, nxt.k);
                 }
@@ -638,10 +676,11 @@ __global__ __launch_bounds__(Combine<D>::threads) void combine_partials_kernel(A
     const int first = p.ws_header[i];
     const int next = p.ws_header[i + 1];
     if (k <= 0) return;
-    const int per = (total + p.num_waves - 1) / p.num_waves;
+    const int num_waves = min(p.num_waves, total);     // (as the attention kernel cuts the line)
     const int nt = (next - first) / p.H;
     const int g0 = first + h * nt;
-    const int w0 = g0 / per, w1 = (g0 + nt - 1) / per;
+    const LineCut cut(total, max(num_waves, 1));
+    const int w0 = cut.wave_of(g0), w1 = cut.wave_of(g0 + nt - 1);
     if (w0 == w1) return;                  // one wave saw the whole pair and wrote `out` itself
     // With the in-workgroup merge only the first wave of the pair and the first wave of every
     // later workgroup it reaches have written a slot; a pair inside one workgroup is done.
@@ -705,14 +744,14 @@ static hipError_t launch_typed(const AttnParams& params, int blocks, bool valu, 
     valu = valu && !PADDED && D != 80;      // the vector-ALU formulation exists for these only
     AttnParams p = params;
     if (valu) p.wg_fold = 0;
-    size_t lds = (size_t)(p.B + 1) * sizeof(int32_t);
+    size_t lds = attn_index_lds_bytes(p.B, PADDED || valu);     // (the vector-ALU build needs its LDS for per-row state)
     hipError_t e;
     if (ev_start && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
     bool launched = false;
-    if (p.wg_fold) lds = ((lds + 15) & ~(size_t)15) + fold_lds_bytes<D>();     // at most 32 KiB + 26 KiB
+    if (p.wg_fold) lds += fold_lds_bytes<D>();     // at most 32 KiB of tile prefix (24 KiB of index arrays) + 26 KiB
     if constexpr (!PADDED && D != 80) {
         if (valu) {
-            lds = ((lds + 15) & ~(size_t)15) + (size_t)kWavesPerBlock * ValuLds<D>::bytes;
+            lds += (size_t)kWavesPerBlock * ValuLds<D>::bytes;
             // prefix sums + 4 x 36 KiB (D = 128) of wave-private state: well above the 64 KiB a
             // kernel may use by default on some HIP platforms, so ask for the device's 160 KiB
             if (lds > kMaxLdsBytes) return hipErrorInvalidValue;   // (the API layer rejects such B first)
@@ -749,8 +788,7 @@ static hipError_t launch_layout(const AttnParams& p, int blocks, int D, bool bf1
 }
 
 size_t valu_attention_lds_bytes(int B, int D) {
-    const size_t prefix = (((size_t)(B + 1) * sizeof(int32_t)) + 15) & ~(size_t)15;
-    return prefix + (size_t)kWavesPerBlock * (D == 128 ? ValuLds<128>::bytes : ValuLds<64>::bytes);
+    return attn_index_lds_bytes(B, true) + (size_t)kWavesPerBlock * (D == 128 ? ValuLds<128>::bytes : ValuLds<64>::bytes);
 }
 
 hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool bf16, bool padded,

@@ -1,5 +1,5 @@
 /* Host layer of the C ABI under -fsanitize=address,undefined, without a GPU: this program is
- * linked with csrc/ems_api.hip compiled for the host only and with launch_stubs.cpp in place of
+ * linked with csrc/ems_api.hip (its host side instrumented) and with launch_stubs.cpp in place of
  * the kernels.  It walks every entry point down both its refusals (bad scalars, NULL or
  * misaligned pointers, small workspaces) and its accepted paths (to the launch, which the
  * stubs count), with host arrays sized exactly.  Device pointers are never dereferenced by

@@ -1,6 +1,6 @@
 // Stand-ins for the kernel launchers of libems, so that the host layer of the C ABI (argument
-// validation, launch sizing, parameter marshalling: csrc/ems_api.hip compiled for the host
-// only) can run to the end of every entry point on a machine without a GPU, under the address
+// validation, launch sizing, parameter marshalling: the host side of csrc/ems_api.hip)
+// can run to the end of every entry point on a machine without a GPU, under the address
 // and undefined-behaviour sanitizers.  Nothing is launched; each stand-in checks the few
 // facts a real launch relies on and counts the call.  Test infrastructure only.
 #include <cstdlib>

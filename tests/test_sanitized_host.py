@@ -5,7 +5,7 @@ undefined-behaviour sanitizers (no GPU, no GPU code instrumented).
   drive every oracle function over ragged inputs in exactly-sized buffers;
 * the oracle's pin tests run against a copy of the oracle built with -fsanitize=undefined
   (no recovery: any undefined operation aborts the child process);
-* tests/c_abi/api_host_sanitized.c + csrc/ems_api.hip compiled for the host only + launch stubs,
+* tests/c_abi/api_host_sanitized.c + csrc/ems_api.hip with its host side instrumented + launch stubs,
   built with the ROCm clang's sanitizers, walk every entry point's refusals and accepted paths.
 """
 import os
@@ -65,12 +65,14 @@ def test_api_host_layer_is_memory_safe_down_to_every_launch(tmp_path):
     api_o, stubs_o, drv_o, exe = (str(tmp_path / n) for n in ("api_host.o", "stubs.o", "driver.o", "api_host_sanitized"))
     api_src = os.path.join(ROOT, "paper_2405_07542_amd", "csrc", "ems_api.hip")
     for cmd in (
-        [hipcc, "-O1", "-g", "-std=c++17", "--cuda-host-only"] + host_san + ["-c", api_src, "-o", api_o],
+        # (host code instrumented, device image left as it is: the API's translation unit carries the
+        # static device buffer of ems_verify_attention_noalloc, which its host side registers)
+        [hipcc, "-O1", "-g", "-std=c++17", "--offload-arch=gfx950"] + host_san + ["-c", api_src, "-o", api_o],
         [hipcc, "-O1", "-g", "-std=c++17", "-x", "hip", "--cuda-host-only"] + host_san +
         ["-c", os.path.join(C_ABI, "launch_stubs.cpp"), "-o", stubs_o],
         [clang, "-O1", "-g", "-std=c11", "-Wall", "-Wextra", "-Werror"] + SAN +
         ["-I", os.path.join(ROOT, "include"), "-c", os.path.join(C_ABI, "api_host_sanitized.c"), "-o", drv_o],
-        [clang + "++"] + SAN + ["-o", exe, drv_o, stubs_o, api_o, "-L", os.path.join(ROCM, "lib"), "-lamdhip64",
+        [hipcc] + host_san + ["-o", exe, drv_o, stubs_o, api_o, "-L", os.path.join(ROCM, "lib"), "-lamdhip64",
                                 "-Wl,-rpath," + os.path.join(ROCM, "lib")],
     ):
         rc, out, err = run(cmd)

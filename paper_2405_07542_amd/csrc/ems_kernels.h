@@ -82,7 +82,8 @@ struct AcceptParams {
     const void* logits;        // [T, V] or nullptr
     int logits_dtype;          // 0 = fp16, 1 = bf16, 2 = fp32
     int V;
-    int slices;                // row slices of the first pass
+    int rows_in_lds;           // set by the launcher: the scan block keeps cu_seqlens and all rows' ids in LDS
+    int slices;                // row slices of the first pass (at most 16)
     int slice_len;             // columns per slice (multiple of 8)
     ArgmaxPartial* partial;    // [T, slices]
     int32_t* target_ids;

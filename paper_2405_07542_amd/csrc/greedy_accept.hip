@@ -114,7 +114,6 @@ __global__ __launch_bounds__(kArgmaxThreads) void argmax_partial_kernel(AcceptPa
     }
 }
 
-constexpr int kMaxAcceptB = 8192;
 
 // Acceptance along a token tree, one wave per sample (k <= 64 rows, lane j = row j): from row
 // 0, step to the lowest-indexed child of the current row whose token equals the target's
@@ -140,23 +139,53 @@ __device__ __forceinline__ int tree_walk(const AcceptParams& p, int base, int k,
     return a;
 }
 
+// LDS of the scan block: the accepted counts of all samples, and -- when they fit (rows_in_lds) --
+// cu_seqlens and the target and input ids of all rows, so that after the first pass over the
+// partials nothing is read from global memory twice or in a dependent chain.
+constexpr int kMaxSlices = 16;
+
 __global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParams p) {
-    __shared__ int32_t acc_s[kMaxAcceptB];
+    extern __shared__ int32_t accept_lds[];
     __shared__ int32_t wave_tot[kAcceptThreads / kWave];
+    int32_t* const acc_s = accept_lds;                         // [B]
+    int32_t* const cu_s = acc_s + p.B;                         // [B + 1]   (rows_in_lds)
+    int32_t* const tgt_s = cu_s + p.B + 1;                     // [T]       (rows_in_lds)
+    int32_t* const ids_s = tgt_s + p.T;                        // [T]       (rows_in_lds)
+    const bool in_lds = p.rows_in_lds != 0;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wid = tid >> 6;
 
-    if (p.logits != nullptr) {
-        for (int r = tid; r < p.T; r += kAcceptThreads) {
+    if (in_lds)
+        for (int i = tid; i <= p.B; i += kAcceptThreads) cu_s[i] = p.cu[i];
+    for (int r = tid; r < p.T; r += kAcceptThreads) {
+        int32_t arg;
+        if (p.logits != nullptr) {
+            // all slices of the row are asked for at once (a loop over a run-time count would
+            // wait for each load before asking for the next)
             const ArgmaxPartial* part = p.partial + (int64_t)r * p.slices;
-            float best = part[0].value;
-            int32_t arg = part[0].index;
-            for (int s = 1; s < p.slices; ++s) take_better(best, arg, part[s].value, part[s].index);
+            ArgmaxPartial got[kMaxSlices];
+#pragma unroll
+            for (int s = 0; s < kMaxSlices; ++s)
+                if (s < p.slices) got[s] = part[s];
+            float best = got[0].value;
+            arg = got[0].index;
+#pragma unroll
+            for (int s = 1; s < kMaxSlices; ++s)
+                if (s < p.slices) take_better(best, arg, got[s].value, got[s].index);
             p.target_ids[r] = arg;
+        } else {
+            arg = p.target_ids[r];
         }
-        __threadfence_block();
-        __syncthreads();
+        if (in_lds) {
+            tgt_s[r] = arg;
+            ids_s[r] = p.input_ids[r];
+        }
     }
+    if (p.logits != nullptr) __threadfence_block();      // (the tree walk and the fallback read target_ids back from memory)
+    __syncthreads();
+    auto cu_at = [&](int i) { return in_lds ? cu_s[i] : p.cu[i]; };
+    auto tgt_at = [&](int r) { return in_lds ? tgt_s[r] : p.target_ids[r]; };
+    auto ids_at = [&](int r) { return in_lds ? ids_s[r] : p.input_ids[r]; };
 
     const bool tree = p.parent != nullptr;
     if (tree) {
@@ -178,14 +207,13 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParam
         for (int i0 = 0; i0 < p.B; i0 += kAcceptThreads / 16) {
             const int i = i0 + (tid >> 4);
             const bool live = i < p.B;
-            const int base = live ? p.cu[i] : 0;
-            const int k = live ? p.cu[i + 1] - base : 0;
+            const int base = live ? cu_at(i) : 0;
+            const int k = live ? cu_at(i + 1) - base : 0;
             int m = 0;
             bool done = k <= 1;
             for (int c0 = 0;; c0 += 16) {
                 const int j = c0 + l16;
-                const bool match = !done && j < k - 1 &&
-                                   p.target_ids[base + j] == p.input_ids[base + j + 1];
+                const bool match = !done && j < k - 1 && tgt_at(base + j) == ids_at(base + j + 1);
                 const uint32_t mine = (uint32_t)(__builtin_amdgcn_ballot_w64(match) >> (16 * sub)) & 0xffffu;
                 if (!done) {
                     const uint32_t miss = ~mine & 0xffffu;      // a row past the last draft counts as a miss
@@ -232,8 +260,8 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParam
         if (tree) {
             acc_s[i] = run;                     // the walk below needs the sample's offset
         } else if (p.out_tokens != nullptr) {
-            const int base = p.cu[i];
-            for (int j = 0; j < a; ++j) p.out_tokens[run + j] = p.target_ids[base + j];
+            const int base = cu_at(i);
+            for (int j = 0; j < a; ++j) p.out_tokens[run + j] = tgt_at(base + j);
         }
         run += a;
         if (i == p.B - 1) p.accepted_cu[p.B] = run;
@@ -267,7 +295,11 @@ hipError_t launch_greedy_accept(const AcceptParams& p, hipStream_t stream) {
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(accept_scan_kernel, dim3(1), dim3(kAcceptThreads), 0, stream, p);
+    AcceptParams q = p;
+    const size_t small = sizeof(int32_t) * (size_t)p.B;
+    const size_t large = sizeof(int32_t) * ((size_t)2 * p.B + 1 + (size_t)2 * p.T);
+    q.rows_in_lds = large <= 60 * 1024 ? 1 : 0;      // (a kernel may use 64 KiB of LDS without asking for more)
+    hipLaunchKernelGGL(accept_scan_kernel, dim3(1), dim3(kAcceptThreads), q.rows_in_lds ? large : small, stream, q);
     return hipGetLastError();
 }
 

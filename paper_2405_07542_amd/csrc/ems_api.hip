@@ -9,7 +9,6 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <atomic>
 #include <vector>
@@ -241,7 +240,6 @@ ems_status run_attention(const void* q, const void* k_new, const void* v_new,
     p.scale_log2 = scale * 1.4426950408889634f;
     p.write_through = write_through ? 1 : 0;
     p.multi = (int)shape;
-    if (shape == kRows64 && std::getenv("EMS_WIDE64_PARKED") != nullptr) p.multi = 4;    // (A/B while both forms exist)
     // The in-workgroup merge of partials saves HBM writes in the middle of the read stream and
     // costs a barrier and a fold at the end of the walk (~1 us): measured break-even at ~13 tiles
     // per wave (B = 16, 1024 cached tokens), a loss of 1.5 us at 6, gains from 25 on.

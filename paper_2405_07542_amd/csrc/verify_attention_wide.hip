@@ -1136,7 +1136,7 @@ hipError_t launch_verify_attention_wide(const AttnParams& p, int blocks, int D, 
     // all 64 rows of a pair on one stream of the cache: two waves per SIMD fed through LDS (head
     // dims 80 and 128), or one wave with two of its four blocks parked in LDS (head dim 64)
     if (p.multi == 2 && D != 64) return launch_duo(p, blocks, D, bf16, stream, ev_start, ev_stop);
-    if (p.multi == 2 || p.multi == 4) return launch_wide_blocks<4>(p, blocks, D, bf16, stream, ev_start, ev_stop);
+    if (p.multi == 2) return launch_wide_blocks<4>(p, blocks, D, bf16, stream, ev_start, ev_stop);
     return launch_wide_blocks<2>(p, blocks, D, bf16, stream, ev_start, ev_stop);
 }
 

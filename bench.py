@@ -131,7 +131,7 @@ def attention_algorithmic_bytes(b, out_elem_bytes):
 
 
 KERNEL_SOURCES = ("attention_tiles.h", "ems_device.h", "ems_kernels.h", "verify_attention.hip",
-                  "verify_attention_wide.hip")
+                  "verify_attention_wide.hip", "verify_attention_staged.hip")
 
 
 def kernel_source_digest():

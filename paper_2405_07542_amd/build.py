@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libems.so")
-SOURCES = ["ems_api.hip", "verify_attention.hip", "verify_attention_wide.hip", "greedy_accept.hip", "kv_append.hip", "pack_tokens.hip", "stream_probe.hip"]
+SOURCES = ["ems_api.hip", "verify_attention.hip", "verify_attention_wide.hip", "verify_attention_staged.hip", "greedy_accept.hip", "kv_append.hip", "pack_tokens.hip", "stream_probe.hip"]
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -25,6 +25,7 @@ inline hipError_t allow_max_lds(const void* kernel, std::atomic<uint64_t>& done)
 
 constexpr int kTileKeys = 32;
 constexpr int kMaxRows = 16;             // query rows per MFMA column block
+constexpr float kMaxSlack = 6.f;         // lazy softmax reference: P entries stay below 2^6, exact in fp32, far inside fp16 / bf16 range
 constexpr int kMaxRowsWide = 64;         // query rows per sample in the wide kernel (two pairs of two blocks)
 constexpr int kAttnThreads = 256;
 constexpr int kWavesPerBlock = kAttnThreads / kWave;

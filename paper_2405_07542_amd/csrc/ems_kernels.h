@@ -70,6 +70,12 @@ hipError_t launch_verify_attention(const AttnParams& p, int blocks, int D, bool 
 // wave, partial slots of 32 rows; p.multi = 2: pairs of up to 64 rows, partial slots of 64 rows).
 // wide_rows64_fits: whether LDS can hold p.multi = 2 at this batch size.
 bool wide_rows64_fits(int B, int D);
+// The staged kernel (17..64 rows, head dims 80 and 128): tile streams per workgroup, the LDS a
+// launch needs (all ones for other head dims), and the launch of its main kernel (p.num_waves
+// counts streams there).
+constexpr int kStagedStreams = 2;
+size_t staged_attention_lds_bytes(int B, int D);
+hipError_t launch_verify_attention_staged(const AttnParams& p, int blocks, int D, bool bf16, hipStream_t stream);
 hipError_t launch_verify_attention_wide(const AttnParams& p, int blocks, int D, bool bf16,
                                         hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 

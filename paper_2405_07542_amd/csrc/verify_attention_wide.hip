@@ -100,7 +100,6 @@ __device__ __forceinline__ WideSegment<NB> next_wide_segment(const AttnParams& p
     return s;
 }
 
-constexpr float kMaxSlack = 6.f;     // P entries stay below 2^6: exact in fp32, far inside fp16 / bf16 range
 
 // One tile against the (up to two) blocks of query rows of a pair.  Cache tile: `lim` visible keys (the same
 // for every row; MASKED when < 32).  Tile of new tokens (NEW): vis[b] = this lane's row of
@@ -583,390 +582,6 @@ __global__ __launch_bounds__(kAttnThreads, 1) void verify_attention_wide_kernel(
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// 33..64 rows per sample, second form: TWO waves per SIMD share one stream of the cache.
-// With one wave per SIMD holding all 64 rows, the wave is bound by its own instruction stream
-// (about 800 vector and 96 matrix instructions per 32-key tile, half of the vector ones moves
-// between register files and to and from the parked blocks): 4.4 us per tile against the 2.6 us
-// a tile takes to arrive.  Here a workgroup has eight waves: waves w and w + 4 (one SIMD) walk the
-// same tile range of the same (sample, head) pairs; wave w keeps rows 0..31 in registers, wave
-// w + 4 rows 32..63, each as two blocks of 16, with no parked state and no exchange.  The tile is
-// staged through LDS by direct loads (global_load ... lds: memory to LDS without passing through
-// registers): wave w fetches the K pieces, wave w + 4 the V pieces, each lane's 16 bytes landing
-// in its own slot, i.e. in exactly the per-lane layout in which either wave would have loaded
-// them into registers; one workgroup barrier per tile makes them visible, and both waves read the
-// whole tile from LDS as MFMA operands.  A wave holds no tile buffer at all and needs fewer
-// than 256 registers, so two fit a SIMD, and while one runs its softmax the other's matrix
-// products proceed.  Two tile buffers per stream: the loads of tile t + 1 are issued right
-// after the barrier of tile t (when every wave is done with tile t - 1, whose buffer they
-// overwrite) and land while tile t is consumed.
-// Every wave of the workgroup runs the same number of loop steps (the largest range on the
-// line), so every barrier is reached by all eight waves.  Head dims 80 and 128 (the pieces of a
-// V row are 16 bytes there, the size a direct load moves).
-constexpr int kDuoThreads = 512;
-constexpr int kDuoUnits = 4;             // tile ranges (streams) per workgroup, two waves each
-constexpr int kDuoBlocks = 2;            // blocks of 16 rows per wave
-
-// One 32-key tile in LDS, one 16-byte slot per lane (so every access is 64 consecutive slots):
-// 2 KS slot rows of K pieces (keys n and 16 + n of lane (n, g)), then 8 slot rows of V pieces.
-template <int D> struct DuoTile {
-    static_assert(TileRegs<D>::VW == 8, "V pieces of 16 bytes");
-    static constexpr int k_slots = 2 * TileRegs<D>::KS;
-    static constexpr int v_slots = 8;
-    static constexpr int slots = (k_slots + v_slots) * kWave;         // in 16-byte units
-    static constexpr int bytes = slots * (int)sizeof(u32x4);
-};
-template <int D> constexpr size_t duo_lds_bytes(int B) {
-    return ((((size_t)(B + 1) * sizeof(int32_t)) + 15) & ~(size_t)15) + (size_t)kDuoUnits * 2 * DuoTile<D>::bytes;
-}
-
-// 16 bytes per lane from memory (base + this lane's offset) into 64 consecutive LDS slots starting
-// at `dst` (wave-uniform), lane l into slot l; non-temporal like the register loads of the
-// cache.  Completion is counted like any load of the wave (vmcnt).
-__device__ __forceinline__ void load_to_lds(uint64_t base, uint32_t off, u32x4* dst) {
-    __builtin_amdgcn_global_load_lds(reinterpret_cast<const __attribute__((address_space(1))) void*>(base + off),
-                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 2 /* nt */);
-}
-
-// One staged tile against the (up to two) blocks of a wave: as compute_tile_wide, with the K
-// pieces read from LDS where they are used, the V pieces when the scores are done, and Q in
-// registers.  kt / vt: this lane's slot in the first K / V slot row.
-// vis[b]: bit j set = this lane's row of block b sees key j of the tile (all ones for a full
-// tile of cached keys, a prefix for the cache's last tile, the row's own set for new rows).  One
-// form for all three kinds of tile: the eight bit tests cost less than three copies of this code.
-template <typename ET, int D>
-__device__ __forceinline__ void compute_tile_duo(const u32x4* kt, const u32x4* vt, const u32x4* q,
-                                                 SoftmaxState<ET, D>* st, float scale_log2,
-                                                 const uint32_t* vis, int g) {
-    constexpr int KS = TileRegs<D>::KS;
-    constexpr int VW = TileRegs<D>::VW;
-    constexpr bool kSplitP = PSplit<ET>::value;
-    // Both blocks always run (straight-line code keeps the register allocation tight): a block
-    // the pair has no rows for has zeros for Q, so its scores are zeros, its state stays finite
-    // and is never written anywhere.
-    f32x4 sa[kDuoBlocks], sb[kDuoBlocks];
-    u32x4 pb[kDuoBlocks], pl[kDuoBlocks];
-#pragma unroll
-    for (int b = 0; b < kDuoBlocks; ++b) sa[b] = sb[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        const u32x4 ka = kt[s * kWave], kb = kt[(KS + s) * kWave];
-#pragma unroll
-        for (int b = 0; b < kDuoBlocks; ++b) {
-            sa[b] = mfma16x16x32(ET{}, ka, q[b * KS + s], sa[b]);
-            sb[b] = mfma16x16x32(ET{}, kb, q[b * KS + s], sb[b]);
-        }
-    }
-    // (one phase, and one block, at a time: left alone, the scheduler interleaves the blocks and
-    // hoists the operand reads, and the temporaries of everything at once do not fit)
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int b = 0; b < kDuoBlocks; ++b) {
-        float x[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            x[i] = sa[b][i] * scale_log2;
-            x[4 + i] = sb[b][i] * scale_log2;
-            if (((vis[b] >> (4 * g + i)) & 1u) == 0) x[i] = -INFINITY;
-            if (((vis[b] >> (16 + 4 * g + i)) & 1u) == 0) x[4 + i] = -INFINITY;
-        }
-        const float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                               fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        // lazy running reference, as in compute_tile_wide
-        const float m_tile = quad_max(mx);
-        const float m_new = m_tile > st[b].m + kMaxSlack ? m_tile : st[b].m;
-        const float m_sub = m_new == -INFINITY ? 0.f : m_new;   // nothing visible yet
-        const float alpha = fast_exp2(st[b].m - m_sub);
-        float psum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            x[i] = fast_exp2(x[i] - m_sub);
-            psum += x[i];
-        }
-        st[b].l = st[b].l * alpha + psum;
-        st[b].m = m_new;
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-            for (int c = 0; c < VW; ++c) st[b].acc[c] *= alpha;
-        }
-        pb[b][0] = pack2(ET{}, x[0], x[1]);
-        pb[b][1] = pack2(ET{}, x[2], x[3]);
-        pb[b][2] = pack2(ET{}, x[4], x[5]);
-        pb[b][3] = pack2(ET{}, x[6], x[7]);
-        if (kSplitP) {                           // bf16: P as hi + lo, as in the 16-row kernel
-#pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] -= round16(ET{}, x[i]);
-            pl[b][0] = pack2(ET{}, x[0], x[1]);
-            pl[b][1] = pack2(ET{}, x[2], x[3]);
-            pl[b][2] = pack2(ET{}, x[4], x[5]);
-            pl[b][3] = pack2(ET{}, x[6], x[7]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    // every V^T operand is built once and serves both blocks
-    u32x4 v[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = vt[e * kWave];
-#pragma unroll
-    for (int c = 0; c < VW; ++c) {
-        u32x4 va;
-#pragma unroll
-        for (int pr = 0; pr < 4; ++pr) {
-            const uint32_t w0 = v[2 * pr][c >> 1];
-            const uint32_t w1 = v[2 * pr + 1][c >> 1];
-            va[pr] = (c & 1) ? pair_hi(w0, w1) : pair_lo(w0, w1);
-        }
-#pragma unroll
-        for (int b = 0; b < kDuoBlocks; ++b) {
-            st[b].acc[c] = mfma16x16x32(ET{}, va, pb[b], st[b].acc[c]);
-            if (kSplitP) st[b].acc[c] = mfma16x16x32(ET{}, va, pl[b], st[b].acc[c]);
-        }
-        if (c & 1) __builtin_amdgcn_sched_barrier(0);
-    }
-}
-
-template <typename ET, int D>
-__global__ __launch_bounds__(kDuoThreads, 1) void verify_attention_duo_kernel(AttnParams p) {
-    extern __shared__ int32_t prefix[];
-    constexpr int KS = TileRegs<D>::KS;
-    constexpr int VW = TileRegs<D>::VW;
-    constexpr int kSlotRows = 4 * kMaxRows;       // rows of one partial slot
-    typedef TileRegs<D> TR;
-    typedef WideSegment<4> Seg;
-    typedef DuoTile<D> DT;
-    typedef typename TileRegs<D>::vrow_t vrow_t;
-    build_tile_prefix<kWide64Line>(p, prefix);
-    if (blockIdx.x == 0)       // the merge kernel reads the tile prefix from the workspace header
-        for (int i = threadIdx.x; i <= p.B; i += blockDim.x) p.ws_header[i] = prefix[i];
-    const int total = uniform(prefix[p.B]);
-    const int per = (total + p.num_waves - 1) / p.num_waves;     // (num_waves counts streams here)
-    const int lw = uniform((int)(threadIdx.x >> 6));             // 0..7
-    const int ul = lw & (kDuoUnits - 1);                          // stream of this wave inside the workgroup
-    const int half = lw >> 2;                                     // 0: rows 0..31 and the K loads, 1: rows 32..63 and the V loads
-    const int unit = uniform((int)(blockIdx.x * kDuoUnits + ul));
-    const int gbeg = min(total, unit * per);
-    const int gend = min(total, gbeg + per);
-    const int lane = threadIdx.x & 63;
-    const int n = lane & 15;
-    const int g = lane >> 4;
-    // this stream's two tile buffers (wave-uniform address: the direct loads take it as their base)
-    u32x4* const tiles = reinterpret_cast<u32x4*>(reinterpret_cast<char*>(prefix) + (((p.B + 1) * 4 + 15) & ~15)) +
-                         ul * 2 * DT::slots;
-    const uint32_t new_row_bytes = (uint32_t)p.H * (D * 2);
-    const uint32_t cache_row_bytes = (uint32_t)p.row_stride_b;
-    const bool live = gbeg < gend;
-
-    Seg cur, nxt;
-    int cur_end = gbeg, con_t = 0;
-    if (live) {
-        int lo = 0, hi = p.B;          // invariant: prefix[lo] <= gbeg < prefix[hi]
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (prefix[mid] <= gbeg) lo = mid; else hi = mid;
-        }
-        cur = make_wide_segment<D, 4>(p, prefix, uniform(lo), gbeg, gend);
-        cur_end = gbeg + (cur.t1 - cur.t0);
-        nxt = cur;
-        if (cur_end < gend) nxt = next_wide_segment<D, 4>(p, prefix, cur, cur_end, gend);
-        con_t = cur.t0;
-    }
-
-    u32x4 q[kDuoBlocks * KS];              // Q^T of this wave's two blocks, B operands of S^T = K Q^T
-    SoftmaxState<ET, D> st[kDuoBlocks];
-    uint64_t vis[kDuoBlocks];              // this lane's row of block b: visible new rows of the sample
-
-    // blocks of this wave that hold rows of the pair (0, 1 or 2)
-    auto my_blocks = [&](const Seg& s) { return max(0, min(kDuoBlocks, s.blocks() - kDuoBlocks * half)); };
-    const int row_base = kWideRows * half;
-
-    auto begin_segment = [&](const Seg& s) __attribute__((always_inline)) {
-        const uint64_t qaddr = uniform_addr(p.q + s.new_off);
-        int par = -1;
-        if (p.parent != nullptr)
-            par = gload<int32_t>(uniform_addr(p.parent + s.cu_i), (uint32_t)min(lane, s.ktot - 1) * 4u);
-#pragma unroll
-        for (int b = 0; b < kDuoBlocks; ++b) {
-            const int row = min(row_base + kMaxRows * b + n, s.ktot - 1);     // rows beyond the last repeat it, zeroed below
-            const bool real = row_base + kMaxRows * b + n < s.ktot;
-            const uint32_t qoff = (uint32_t)row * new_row_bytes;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const u32x4 z = {0u, 0u, 0u, 0u};
-                const u32x4 qv = gload<u32x4>(qaddr, qoff + TR::piece(ks, g));
-                q[b * KS + ks] = (real && TR::piece_valid(ks, g)) ? qv : z;
-            }
-#pragma unroll
-            for (int c = 0; c < VW; ++c) st[b].acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-            st[b].m = -INFINITY;
-            st[b].l = 0.f;
-            // among the new rows a row sees itself and the rows before it; in a token tree,
-            // itself and its ancestors
-            vis[b] = row >= 63 ? ~0ull : (1ull << (row + 1)) - 1;
-            if (p.parent != nullptr) vis[b] = tree_visibility64(par, lane, s.ktot, row);
-        }
-    };
-
-    // this wave's half of tile `tile` of a pair, from memory straight into LDS buffer `buf`
-    auto issue = [&](int buf, int tile, int L, int ktot, int64_t cache_off, int64_t new_off) __attribute__((always_inline)) {
-        const int ntc = (L + kTileKeys - 1) / kTileKeys;
-        const bool is_new = tile >= ntc;                               // wave-uniform
-        const uint32_t row_bytes = is_new ? new_row_bytes : cache_row_bytes;
-        const int n0 = is_new ? (tile - ntc) * kTileKeys : tile * kTileKeys;
-        const int last = is_new ? ktot - 1 : L - 1;
-        u32x4* const kt = tiles + buf * DT::slots;
-        if (half == 0) {
-            const uint64_t kbase = uniform_addr(is_new ? p.k_new + new_off : p.k_cache + cache_off);
-            const uint32_t ra = (uint32_t)min(n0 + n, last) * row_bytes;
-            const uint32_t rb = (uint32_t)min(n0 + 16 + n, last) * row_bytes;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                load_to_lds(kbase, ra + TR::piece(s, g), kt + s * kWave);
-                load_to_lds(kbase, rb + TR::piece(s, g), kt + (KS + s) * kWave);
-            }
-        } else {
-            const uint64_t vbase = uniform_addr(is_new ? p.v_new + new_off : p.v_cache + cache_off);
-            const uint32_t vcol = (uint32_t)min(n, TR::kVLanes - 1) * (VW * 2);
-            u32x4* const vt = kt + DT::k_slots * kWave;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int key = n0 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
-                load_to_lds(vbase, (uint32_t)min(key, last) * row_bytes + vcol, vt + e * kWave);
-            }
-        }
-    };
-
-    // the tile in LDS buffer `buf` against this wave's blocks; a tile of new rows is also stored
-    // into the cache when the call asks for the paper's order (Sec. 3.2): K by the wave that
-    // fetched K, V by the wave that fetched V, each lane the pieces in its own slots
-    auto consume = [&](int buf, const Seg& s, int tile) __attribute__((always_inline)) {
-        const u32x4* const kt = tiles + buf * DT::slots + lane;
-        const u32x4* const vt = kt + DT::k_slots * kWave;
-        const int nb = my_blocks(s);
-        const bool is_new = tile >= s.ntc();
-        const int key0 = is_new ? kTileKeys * (tile - s.ntc()) : 0;   // first new row of a tile of new rows
-        if (nb != 0) {                          // (0: the pair has at most 32 rows, nothing for the second wave)
-            const int lim = s.L - tile * kTileKeys;                     // visible keys of a cache tile
-            const uint32_t cached = lim >= kTileKeys ? ~0u : (1u << max(lim, 0)) - 1u;
-            uint32_t v32[kDuoBlocks];
-#pragma unroll
-            for (int b = 0; b < kDuoBlocks; ++b) v32[b] = is_new ? (uint32_t)(vis[b] >> key0) : cached;
-            compute_tile_duo<ET, D>(kt, vt, q, st, p.scale_log2, v32, g);
-        }
-        if (!is_new) return;
-        if (!p.write_through) return;
-        if (half == 0) {
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const int key = key0 + 16 * hf + n;
-                if (key < s.ktot) {
-                    char* kdst = const_cast<char*>(p.k_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + key) * cache_row_bytes;
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks)
-                        if (TR::piece_valid(ks, g))
-                            *reinterpret_cast<u32x4*>(kdst + TR::piece(ks, g)) = kt[(hf * KS + ks) * kWave];
-                }
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int kl = e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4);
-                if (key0 + kl < s.ktot && n < TR::kVLanes) {
-                    char* vdst = const_cast<char*>(p.v_cache) + s.cache_off + (uint64_t)(uint32_t)(s.L + key0 + kl) * cache_row_bytes + n * (VW * 2);
-                    *reinterpret_cast<u32x4*>(vdst) = vt[e * kWave];
-                }
-            }
-        }
-    };
-
-    // this wave's blocks normalised into `out`, or as its rows of the stream's partial slot
-    // (slot 2u holds a partial that continues a pair begun by an earlier stream, slot 2u+1 one
-    // that starts a pair and leaves its end to later streams; 64 rows per slot)
-    auto finish_segment = [&](const Seg& s) __attribute__((always_inline)) {
-        const bool whole = s.t0 == 0 && s.t1 == s.nt();
-        const int slot = 2 * unit + (s.t0 == 0 ? 1 : 0);
-        const int nb = my_blocks(s);
-#pragma unroll
-        for (int b = 0; b < kDuoBlocks; ++b) {
-            if (b >= nb) continue;
-            const float l = quad_sum(st[b].l);         // the four lanes of a row hold disjoint shares
-            const int r_in_pair = row_base + kMaxRows * b + n;
-            if (r_in_pair >= s.k) continue;
-            if (whole) {
-                const float inv = 1.0f / l;
-                const int64_t row = ((int64_t)(s.cu_i + r_in_pair) * p.H + s.h) * D;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (4 * g + r >= TR::kVLanes) continue;
-                    const int d0 = (4 * g + r) * VW;
-                    float o[VW];
-#pragma unroll
-                    for (int c = 0; c < VW; ++c) o[c] = st[b].acc[c][r] * inv;
-                    if (p.out_f32) {
-                        float* dst = reinterpret_cast<float*>(p.out) + row + d0;
-#pragma unroll
-                        for (int c = 0; c < VW; c += 4)
-                            *reinterpret_cast<f32x4*>(dst + c) = f32x4{o[c], o[c + 1], o[c + 2], o[c + 3]};
-                    } else {
-                        uint16_t* dst = reinterpret_cast<uint16_t*>(p.out) + row + d0;
-                        vrow_t pk;
-#pragma unroll
-                        for (int c = 0; c < VW; c += 2) pk[c >> 1] = pack2(ET{}, o[c], o[c + 1]);
-                        *reinterpret_cast<vrow_t*>(dst) = pk;
-                    }
-                }
-            } else {
-                float* dst = p.ws + ((int64_t)slot * kSlotRows + r_in_pair) * (D + kPartialPad);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (4 * g + r >= TR::kVLanes) continue;
-                    const int d0 = (4 * g + r) * VW;
-#pragma unroll
-                    for (int c = 0; c < VW; c += 4)
-                        *reinterpret_cast<f32x4*>(dst + d0 + c) =
-                            f32x4{st[b].acc[c][r], st[b].acc[c + 1][r], st[b].acc[c + 2][r], st[b].acc[c + 3][r]};
-                }
-                if (g == 0) {
-                    dst[D] = st[b].m;
-                    dst[D + 1] = l;
-                }
-            }
-        }
-    };
-
-    if (live) {
-        issue(0, cur.t0, cur.L, cur.ktot, cur.cache_off, cur.new_off);
-        begin_segment(cur);
-    }
-    // `per` steps for every wave of the workgroup, whatever its own range holds.  Step t: this
-    // wave's loads of tile gbeg + t have landed (the wait), so have everybody's, and everybody
-    // is done with tile gbeg + t - 1 (the barrier); the loads of tile gbeg + t + 1 go out, into the
-    // buffer tile gbeg + t - 1 was in; tile gbeg + t is consumed.
-#pragma unroll 1
-    for (int t = 0; t < per; ++t) {
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        if (gbeg + t < gend) {                              // wave-uniform
-            if (gbeg + t + 1 < gend) {
-                const bool same = con_t + 1 < cur.t1;        // else: first tile of the next pair
-                issue((t + 1) & 1, same ? con_t + 1 : nxt.t0, same ? cur.L : nxt.L, same ? cur.ktot : nxt.ktot,
-                      same ? cur.cache_off : nxt.cache_off, same ? cur.new_off : nxt.new_off);
-            }
-            consume(t & 1, cur, con_t);
-            ++con_t;
-            if (con_t == cur.t1) {
-                finish_segment(cur);
-                if (gbeg + t + 1 < gend) {
-                    cur = nxt;
-                    con_t = cur.t0;
-                    cur_end = gbeg + t + 1 + (cur.t1 - cur.t0);
-                    begin_segment(cur);
-                    if (cur_end < gend) nxt = next_wide_segment<D, 4>(p, prefix, cur, cur_end, gend);
-                }
-            }
-        }
-    }
-}
-
 // Merge of the partials of pairs shared by several waves, as in the 16-row kernels, with 16 NB
 // rows per slot and, with NB = 2, up to two pairs per (sample, head).
 template <int D> struct WideCombine {
@@ -1095,48 +710,49 @@ static hipError_t launch_wide_blocks(const AttnParams& p, int blocks, int D, boo
                 : launch_wide_typed<F16, 64, NB>(p, blocks, stream, ev_start, ev_stop);
 }
 
+// The staged kernel (verify_attention_staged.hip) and the merge of its partials: 32-row slots and
+// one pair per head when the call said at most 32 rows, 64-row slots otherwise.
 template <typename ET, int D>
-static hipError_t launch_duo_typed(const AttnParams& params, int blocks, hipStream_t stream,
-                                   hipEvent_t ev_start, hipEvent_t ev_stop) {
+static hipError_t launch_staged_and_merge(const AttnParams& params, int blocks, bool bf16, hipStream_t stream,
+                                          hipEvent_t ev_start, hipEvent_t ev_stop) {
     AttnParams p = params;
-    p.wg_fold = 0;                     // partials of 64 rows go through the workspace
-    const size_t lds = duo_lds_bytes<D>(p.B);          // tile prefix sums + four double-buffered tiles: ~135 KiB at D = 128
-    if (lds > (size_t)kMaxLdsBytes) return hipErrorInvalidValue;     // (the API layer picks the two-pair form first)
+    p.wg_fold = 0;                               // partials go through the workspace
+    p.num_waves = blocks * kStagedStreams;       // the tile line is cut per stream
     hipError_t e;
-    static std::atomic<uint64_t> raised{0};
-    e = allow_max_lds(reinterpret_cast<const void*>(&verify_attention_duo_kernel<ET, D>), raised);
-    if (e != hipSuccess) return e;
     if (ev_start && (e = hipEventRecord(ev_start, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((verify_attention_duo_kernel<ET, D>), dim3(blocks), dim3(kDuoThreads), lds, stream, p);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if ((e = launch_verify_attention_staged(p, blocks, D, bf16, stream)) != hipSuccess) return e;
     if (ev_stop && (e = hipEventRecord(ev_stop, stream)) != hipSuccess) return e;
-    hipLaunchKernelGGL((combine_wide_partials_kernel<ET, D, 4>), dim3(p.H, p.B),
-                       dim3(WideCombine<D>::threads), 0, stream, p);
+    if (p.multi == 2)
+        hipLaunchKernelGGL((combine_wide_partials_kernel<ET, D, 4>), dim3(p.H, p.B), dim3(WideCombine<D>::threads), 0, stream, p);
+    else
+        hipLaunchKernelGGL((combine_wide_partials_kernel<ET, D, 2>), dim3(p.H, p.B), dim3(WideCombine<D>::threads), 0, stream, p);
     return hipGetLastError();
 }
 
-static hipError_t launch_duo(const AttnParams& p, int blocks, int D, bool bf16, hipStream_t stream,
-                             hipEvent_t ev_start, hipEvent_t ev_stop) {
-    if (D == 128) return bf16 ? launch_duo_typed<BF16, 128>(p, blocks, stream, ev_start, ev_stop)
-                              : launch_duo_typed<F16, 128>(p, blocks, stream, ev_start, ev_stop);
-    return bf16 ? launch_duo_typed<BF16, 80>(p, blocks, stream, ev_start, ev_stop)
-                : launch_duo_typed<F16, 80>(p, blocks, stream, ev_start, ev_stop);
-}
-
+// Whether all 64 rows of a sample can share one stream of the cache at this batch size (else a
+// sample of more than 32 rows is two pairs per head): head dims 80 and 128 ask the staged kernel's
+// LDS, head dim 64 the one-wave form's with two parked blocks.
 bool wide_rows64_fits(int B, int D) {
-    const size_t lds = D == 128 ? duo_lds_bytes<128>(B) : D == 80 ? duo_lds_bytes<80>(B) : 0;
-    const size_t lds4 = D == 128 ? wide_lds_bytes<128, 4>(B, false) : D == 80 ? wide_lds_bytes<80, 4>(B, false)
-                                                                                : wide_lds_bytes<64, 4>(B, false);
-    return lds <= (size_t)kMaxLdsBytes && lds4 <= (size_t)kMaxLdsBytes;
+    if (D != 64) return staged_attention_lds_bytes(B, D) <= (size_t)kMaxLdsBytes;
+    return wide_lds_bytes<64, 4>(B, false) <= (size_t)kMaxLdsBytes;
 }
 
 hipError_t launch_verify_attention_wide(const AttnParams& p, int blocks, int D, bool bf16,
                                         hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    // all 64 rows of a pair on one stream of the cache: two waves per SIMD fed through LDS (head
-    // dims 80 and 128), or one wave with two of its four blocks parked in LDS (head dim 64)
-    if (p.multi == 2 && D != 64) return launch_duo(p, blocks, D, bf16, stream, ev_start, ev_stop);
-    if (p.multi == 2) return launch_wide_blocks<4>(p, blocks, D, bf16, stream, ev_start, ev_stop);
+    // Head dims 80 and 128: the staged kernel, 17..64 rows, while its LDS fits (then p.multi = 1
+    // means that the call said at most 32 rows, since above 32 rows the API layer sets p.multi = 2
+    // exactly when wide_rows64_fits).
+    if (D != 64 && staged_attention_lds_bytes(p.B, D) <= (size_t)kMaxLdsBytes) {
+        if (D == 128) return bf16 ? launch_staged_and_merge<BF16, 128>(p, blocks, bf16, stream, ev_start, ev_stop)
+                                  : launch_staged_and_merge<F16, 128>(p, blocks, bf16, stream, ev_start, ev_stop);
+        return bf16 ? launch_staged_and_merge<BF16, 80>(p, blocks, bf16, stream, ev_start, ev_stop)
+                    : launch_staged_and_merge<F16, 80>(p, blocks, bf16, stream, ev_start, ev_stop);
+    }
+    // Head dim 64, or a batch too large for the staged kernel's LDS: one wave per SIMD holds 32
+    // rows (a sample of more is two pairs per head) or, head dim 64 only, 64 rows with two of its
+    // four blocks parked in LDS.
+    if (p.multi == 2) return bf16 ? launch_wide_typed<BF16, 64, 4>(p, blocks, stream, ev_start, ev_stop)
+                                  : launch_wide_typed<F16, 64, 4>(p, blocks, stream, ev_start, ev_stop);
     return launch_wide_blocks<2>(p, blocks, D, bf16, stream, ev_start, ev_stop);
 }
 

@@ -1,7 +1,8 @@
-"""GPU parity with more than 16 rows per sample (up to 64): the attention calls then run the wide
-kernel, which holds 32 rows per (sample, head) pair and makes two pairs of a sample with more;
-every pair streams the cache and up to two tiles of new tokens.  Causal and tree masks,
-write-through, accept and append, against the oracle on the same seeded inputs."""
+"""GPU parity with more than 16 rows per sample (up to 64): the attention calls then run the staged
+kernel (head dims 80 and 128: tiles staged through LDS by requesting waves, four computing waves
+of 16 rows each per stream) or the one-wave wide kernel (head dim 64, very large batches), which
+holds 32 rows per (sample, head) pair and makes two pairs of a sample with more.  Causal and tree
+masks, write-through, accept and append, against the oracle on the same seeded inputs."""
 import numpy as np
 import pytest
 import torch
@@ -105,11 +106,10 @@ def test_limits_of_the_other_variants():
 @pytest.mark.parametrize("B,dtype,D,layout", [(8192, torch.bfloat16, 128, TOKEN_MAJOR), (8192, torch.float16, 80, HEAD_MAJOR),
                                                (7000, torch.float16, 128, HEAD_MAJOR), (5000, torch.bfloat16, 128, TOKEN_MAJOR)])
 def test_very_large_batches_through_the_wide_kernel(B, dtype, D, layout):
-    """Thousands of samples, a few of them with more than 16 rows.  With 33..64 rows the wave keeps
-    all rows of a pair while LDS has room for its parked blocks beside the tile prefix sums
-    (B = 5000 at D = 128: 152 KiB); beyond that (B = 7000, 8192) the library falls back to two
-    pairs of 32 rows per head, which these cases are here to cover: causal, tree and
-    write-through."""
+    """Thousands of samples, a few of them with more than 16 rows.  The staged kernel runs while LDS
+    has room for its tile rings beside the tile prefix sums (B = 5000 and 7000: 128 KiB + 4 B per
+    sample); beyond that (B = 8192) the library falls back to the one-wave kernel with two pairs of
+    32 rows per head, which these cases are here to cover: causal, tree and write-through."""
     rng = np.random.default_rng(159 + B)
     kv = rng.integers(0, 41, B).tolist()
     k = rng.integers(0, 4, B).tolist()

@@ -21,17 +21,17 @@
 //     and accumulators as in the 16-row kernel; each tells through its own counter which tiles it
 //     is done with.  A pair of 17..32 rows keeps two of them busy, 33..48 three, 49..64 four.
 // No barrier in the walk.  Every wave's waits end: a counter is polled a bounded number of times.
-// Measured (B = 64, 2048 cached tokens per sample, H = 32, D = 128, bf16; same box, one run
-// after the other; the forms this one replaces in parentheses): 352 us at 17 rows (388),
-// 372 at 32 (404), 388 at 33 (464), 404 at 48 (473), 442 at 64 (487); loads alone 378 us.  At 64
-// rows the four computing waves of a stream are the limit (1.7 us per tile against 1.45 us for
-// its transfer); up to 48 rows the kernel runs at the rate of its loads.
+// Measured (B = 64, 2048 cached tokens per sample, H = 32, D = 128, bf16; one box, the two
+// libraries one after the other; the one-wave-per-SIMD and two-waves-per-SIMD forms this one
+// replaced in parentheses): 352 us at 17 rows (388), 372 at 32 (404), 399 at 33 (464), 410 at 48
+// (473), 448 at 64 (487); its loads alone (no arithmetic) take 378 us.  At 64 rows the four
+// computing waves of a stream are the limit (1.7 us per tile against 1.45 us for its transfer);
+// up to 48 rows the kernel runs at the rate of its loads.
 // What was tried on the way (none kept): the same four-waves-per-stream split with every wave
 // requesting a quarter of the tile and one barrier per tile (531 us at 64 rows: the blocked
 // requests are on every wave's critical path); requesting waves in lock-step with the
 // computing ones through that barrier (499); the scores of tile t + 1 computed among the
-// exponentials of tile t (no gain: the wave is not short of independent work but of issue
-// slots it shares with its SIMD's other waves).
+// exponentials of tile t (no gain, and slower once that tile must have landed first).
 #include "attention_tiles.h"
 
 namespace ems {
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(kStagedThreads, 1) void verify_attention_staged_ker
         if (p.parent != nullptr) vis = tree_visibility64(par, lane, s.ktot, row);
     };
 
-    // this wave's quarter of tile `tile` of pair s, from memory straight into ring slot `buf`
+    // (requesting wave) tile `tile` of pair s, all its pieces, from memory straight into ring slot `buf`
     auto issue = [&](int buf, const Seg& s, int tile) __attribute__((always_inline)) {
         const int ntc = s.ntc();
         const bool is_new = tile >= ntc;                               // wave-uniform
@@ -332,7 +332,8 @@ __global__ __launch_bounds__(kStagedThreads, 1) void verify_attention_staged_ker
         }
         if (!is_new) return;
         if (!p.write_through) return;
-        // the paper's order (Sec. 3.2): the new rows go into the cache, each wave the slot rows it fetched
+        // the paper's order (Sec. 3.2): the new rows go into the cache (rows beyond the cached length,
+        // which nobody reads in this call), each computing wave a quarter of the tile's slot rows
 #pragma unroll
         for (int o = 0; o < kOps; ++o) {
             if ((o & 3) != blk) continue;

@@ -1,6 +1,9 @@
 // Packed multi-token attention for samples that bring MORE than 16 rows per step (up to 64:
-// token trees commonly have 32-64 nodes).  Same tile line, same loads, same two tile buffers,
-// same partial format as verify_attention.hip; what changes:
+// token trees commonly have 32-64 nodes), in the forms where ONE wave per SIMD holds a pair's rows
+// in registers -- what head dim 64 runs, and what very large batches fall back to; head dims 80
+// and 128 run the staged kernel of verify_attention_staged.hip, which this file launches and
+// whose partials it merges.  Same tile line, same loads, same two tile buffers, same partial
+// format as verify_attention.hip; what changes:
 //   * a wave keeps TWO blocks of 16 query rows of its pair in flight: two B operands (in
 //     wave-private LDS, in exactly the per-lane layout the MFMA wants, re-read for every tile)
 //     and two sets of accumulators.  Per tile, the scores and the online softmax run block
@@ -10,13 +13,14 @@
 //     tried: the allocator runs out of the 256 non-accumulator registers and spills, and
 //     both ways out, one tile buffer instead of two or spilling, were slower than two
 //     streams of two blocks.)
-//   * a sample with more than 32 rows: (NB = 4, the default above 32 rows) the wave keeps the
+//   * a sample with more than 32 rows: (NB = 4, head dim 64) the wave keeps the
 //     state of all four blocks, two of them in registers and two parked in wave-private LDS,
 //     and per tile runs the two resident blocks, swaps the two pairs (16 LDS reads and writes
 //     per lane) and runs the other two on the same tile registers, so the cache is still
 //     streamed once; the pair that ran last stays resident for the next tile.  (NB = 2, used
-//     when LDS cannot hold the parked states -- very large batches -- : two pairs per head,
-//     (sample, head, half), rows 0..31 and 32..63, each streaming the cache once.)
+//     when LDS can hold neither the parked states nor the staged kernel's tile rings -- very
+//     large batches -- : two pairs per head, (sample, head, half), rows 0..31 and 32..63, each
+//     streaming the cache once.)
 //   * a sample's new tokens take ceil(k/32) tiles after the cache tiles; the visible set of
 //     a row among the new rows is a 64-bit set (a causal prefix, or the row's ancestors in
 //     a token tree), of which every new-token tile uses its 32 bits (the first half never

@@ -75,6 +75,8 @@ def parse_args():
     ap.add_argument("--sweep-variants", action="store_true",
                     help="instead of the bench: attention kernel time of the matrix-core and the vector-ALU "
                          "formulation vs rows per sample, B=64, 2048 cached tokens each, bf16")
+    ap.add_argument("--separate-accept-append", action="store_true",
+                    help="acceptance and append as two calls (three launches) instead of ems_greedy_accept_append")
     ap.add_argument("--no-all-configs", action="store_true",
                     help="config 4 only: skip the brief runs of configs 2, 3 and 5 that fill `all_configs`")
     ap.add_argument("--source-digest", action="store_true",
@@ -246,10 +248,19 @@ def step_functions(args, with_logits):
         ems.ems_kv_append([b.k_new], [b.v_new], [st["cache"]], b.cu_seqlens, st["accepted"], b.kv_start,
                           b.kv_len, st["new_len"])
 
+    def accept_append(st):
+        b = st["b"]
+        ems.ems_greedy_accept_append(b.logits if with_logits else None, st["target"], b.input_ids, b.cu_seqlens,
+                                     st["accepted"], st["accepted_cu"], st["out_tokens"], [b.k_new], [b.v_new],
+                                     [st["cache"]], b.kv_start, b.kv_len, st["new_len"], workspace=st["ws_acc"])
+
     def step(st):
         attention(st)
-        accept(st)
-        append(st)
+        if args.tree or args.write_through or args.separate_accept_append:
+            accept(st)
+            append(st)
+        else:
+            accept_append(st)       # the same two steps, the counts and the copy in one launch
 
     return attention, accept, append, step
 
@@ -386,6 +397,8 @@ def main():
                    "query_rows_per_step": fig["rows_per_step"], "accepted_per_step": fig["accepted_per_step"],
                    "logits": LOGITS_NOTE if with_logits else None, "buffer_sets": len(sets),
                    "variant": "write-through + advance" if args.write_through else "verify + append",
+                   "accept_and_append": "two calls" if (args.tree or args.write_through or args.separate_accept_append)
+                   else "one call (ems_greedy_accept_append)",
                    "attention_variant": args.attention_variant, "tree": args.tree,
                    "tree_rows": args.tree_rows or None},
         "query_tokens_per_s": round(fig["query_tokens_per_s"], 1),

@@ -252,6 +252,29 @@ EMS_API ems_status ems_kv_append(
     int B, int T, int H, int D, ems_dtype dtype, void* hip_stream);
 
 /*
+ * ems_greedy_accept and then ems_kv_append of the counts it found (Appendix A, then Sec. 3.2
+ * "Unpad KV cache"), as one call: the arguments are those of the two calls, in their order
+ * (logits_dtype describes the logits, dtype the K/V tensors), every output is what the two calls
+ * give, bit for bit, and no other byte is written.  Why it exists: the step around the
+ * attention call is launch-bound, and here the kernel that finds the counts also copies the
+ * rows (each copying workgroup derives its sample's count itself), one launch less.  Where one
+ * launch cannot do both -- kv_len_out aliasing kv_len, more than EMS_MAX_LAYERS_PER_CALL layers,
+ * T == 0 -- the two calls simply run one after the other.
+ * Errors: those of ems_greedy_accept and ems_kv_append; nothing is enqueued when one is
+ * returned.
+ */
+EMS_API ems_status ems_greedy_accept_append(
+    const void* logits, ems_dtype logits_dtype, int V,
+    int32_t* target_ids, const int32_t* input_ids,
+    const int32_t* cu_seqlens, int B, int T,
+    int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens,
+    void* workspace, size_t workspace_bytes,
+    const void* const* k_new_layers, const void* const* v_new_layers,
+    const ems_kv_cache* caches, int n_layers,
+    const int32_t* kv_start, const int32_t* kv_len, int32_t* kv_len_out,
+    int H, int D, ems_dtype dtype, void* hip_stream);
+
+/*
  * Ablation: the padded "vanilla" method of Sec. 3.1, same kernels, same library.
  * Inputs are padded to k_max rows per sample ([B, k_max, H, D]; rows j >= k_valid[i] are
  * padding); the caches are aligned: sample i owns arena rows i*cap .. i*cap + l_pad - 1,

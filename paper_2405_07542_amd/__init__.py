@@ -93,6 +93,11 @@ def lib() -> ctypes.CDLL:
         L.ems_kv_append.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp),
                                     ctypes.POINTER(KvCacheStruct), i32, vp, vp, vp, vp, vp,
                                     i32, i32, i32, i32, i32, vp]
+        L.ems_greedy_accept_append.restype = i32
+        L.ems_greedy_accept_append.argtypes = [vp, i32, i32, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz,
+                                               ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                               ctypes.POINTER(KvCacheStruct), i32, vp, vp, vp,
+                                               i32, i32, i32, vp]
         L.ems_validate_inputs.restype = i32
         L.ems_validate_inputs.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, vp]
         L.ems_padded_verify_attention.restype = i32
@@ -324,6 +329,38 @@ def ems_kv_append(k_new_layers: Sequence[torch.Tensor], v_new_layers: Sequence[t
     _check(lib().ems_kv_append(karr, varr, carr, n, _ptr(cu_seqlens), _ptr(accepted),
                                _ptr(kv_start), _ptr(kv_len), _ptr(kv_len_out), B, T, H, D,
                                _DT[k_new_layers[0].dtype], _stream(stream)))
+
+
+def ems_greedy_accept_append(logits: Optional[torch.Tensor], target_ids, input_ids, cu_seqlens,
+                             accepted, accepted_cu, out_tokens: Optional[torch.Tensor],
+                             k_new_layers: Sequence[torch.Tensor], v_new_layers: Sequence[torch.Tensor],
+                             caches: Sequence[KvCacheStruct], kv_start, kv_len,
+                             kv_len_out: Optional[torch.Tensor], *,
+                             workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """ems_greedy_accept and ems_kv_append of the counts it found, as one call."""
+    _need_accept(logits, target_ids, input_ids, cu_seqlens, accepted, accepted_cu, out_tokens, workspace)
+    B = accepted.numel()
+    T = input_ids.numel()
+    V = logits.shape[1] if logits is not None else 0
+    dt = _DT[logits.dtype] if logits is not None else EMS_F16
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    n = len(caches)
+    _need_layers(k_new_layers, v_new_layers, n)
+    Tk, H, D = k_new_layers[0].shape
+    if Tk != T:
+        _refuse(ValueError, "k_new_layers hold %d rows, input_ids %d" % (Tk, T))
+    _need("kv_start", kv_start, _I32, numel=B)
+    _need("kv_len", kv_len, _I32, numel=B)
+    _need("kv_len_out", kv_len_out, _I32, numel=B, optional=True)
+    karr = (ctypes.c_void_p * n)(*[t.data_ptr() for t in k_new_layers])
+    varr = (ctypes.c_void_p * n)(*[t.data_ptr() for t in v_new_layers])
+    carr = (KvCacheStruct * n)(*caches)
+    _resident()
+    _check(lib().ems_greedy_accept_append(
+        _ptr(logits), dt, V, _ptr(target_ids), _ptr(input_ids), _ptr(cu_seqlens), B, T,
+        _ptr(accepted), _ptr(accepted_cu), _ptr(out_tokens), _ptr(workspace), ws_bytes,
+        karr, varr, carr, n, _ptr(kv_start), _ptr(kv_len), _ptr(kv_len_out), H, D,
+        _DT[k_new_layers[0].dtype], _stream(stream)))
 
 
 def ems_tree_verify_attention(q, k_new, v_new, cache: KvCacheStruct, cu_seqlens, parent, kv_start,

@@ -415,11 +415,12 @@ size_t ems_accept_workspace_bytes(int T, int V) {
 namespace {
 
 // Shared by ems_greedy_accept (parent == nullptr) and ems_tree_accept.
-ems_status run_accept(const void* logits, ems_dtype dtype, int V, int32_t* target_ids,
-                      const int32_t* input_ids, const int32_t* parent, const int32_t* cu_seqlens,
-                      int B, int T, int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens,
-                      int32_t* accepted_rows, void* workspace, size_t workspace_bytes,
-                      void* hip_stream) {
+// Checks the arguments of an acceptance call and fills its kernel parameters.
+ems_status prepare_accept(const void* logits, ems_dtype dtype, int V, int32_t* target_ids,
+                          const int32_t* input_ids, const int32_t* parent, const int32_t* cu_seqlens,
+                          int B, int T, int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens,
+                          int32_t* accepted_rows, void* workspace, size_t workspace_bytes,
+                          ems::AcceptParams* out) {
     if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
     if (T < 0) return fail(EMS_ERR_INVALID_ARG, "T = %d, need T >= 0", T);
     if (V < 0) return fail(EMS_ERR_INVALID_ARG, "V = %d, need V >= 0", V);
@@ -429,7 +430,7 @@ ems_status run_accept(const void* logits, ems_dtype dtype, int V, int32_t* targe
         return fail(EMS_ERR_INVALID_ARG, "cu_seqlens, accepted and accepted_cu must not be NULL");
     if (T > 0 && (!target_ids || !input_ids))
         return fail(EMS_ERR_INVALID_ARG, "target_ids and input_ids must not be NULL");
-    ems::AcceptParams p;
+    ems::AcceptParams& p = *out;
     std::memset(&p, 0, sizeof p);
     if (logits != nullptr) {
         if (!dtype16(dtype) && dtype != EMS_F32)
@@ -458,11 +459,30 @@ ems_status run_accept(const void* logits, ems_dtype dtype, int V, int32_t* targe
     p.out_tokens = out_tokens;
     p.parent = parent;
     p.accepted_rows = accepted_rows;
+    return EMS_OK;
+}
+
+ems_status run_accept(const void* logits, ems_dtype dtype, int V, int32_t* target_ids,
+                      const int32_t* input_ids, const int32_t* parent, const int32_t* cu_seqlens,
+                      int B, int T, int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens,
+                      int32_t* accepted_rows, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+    ems::AcceptParams p;
+    const ems_status st = prepare_accept(logits, dtype, V, target_ids, input_ids, parent, cu_seqlens, B, T, accepted,
+                                         accepted_cu, out_tokens, accepted_rows, workspace, workspace_bytes, &p);
+    if (st != EMS_OK) return st;
     hipError_t e = ems::launch_greedy_accept(p, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return hip_fail("accept launch", e);
     return EMS_OK;
 }
 
+ems_status check_append(const void* const* k_new_layers, const void* const* v_new_layers,
+                        const ems_kv_cache* caches, int n_layers, const int32_t* kv_start,
+                        const int32_t* kv_len, int B, int T, int H, int D, ems_dtype dtype);
+void fill_append(ems::AppendParams& p, const void* const* k_new_layers, const void* const* v_new_layers,
+                 const ems_kv_cache* caches, int l0, int n, const int32_t* cu_seqlens, const int32_t* accepted,
+                 const int32_t* rows, const int32_t* rows_cu, const int32_t* kv_start, const int32_t* kv_len,
+                 int32_t* kv_len_out, int B, int T, int H, int D);
 // Shared by ems_kv_append (rows == nullptr) and ems_kv_append_rows (cu_seqlens, accepted unused).
 ems_status run_append(const void* const* k_new_layers, const void* const* v_new_layers,
                       const ems_kv_cache* caches, int n_layers, const int32_t* cu_seqlens,
@@ -503,6 +523,39 @@ ems_status ems_kv_append(const void* const* k_new_layers, const void* const* v_n
                       nullptr, kv_start, kv_len, kv_len_out, B, T, H, D, dtype, hip_stream);
 }
 
+ems_status ems_greedy_accept_append(const void* logits, ems_dtype logits_dtype, int V, int32_t* target_ids,
+                                    const int32_t* input_ids, const int32_t* cu_seqlens, int B, int T,
+                                    int32_t* accepted, int32_t* accepted_cu, int32_t* out_tokens,
+                                    void* workspace, size_t workspace_bytes,
+                                    const void* const* k_new_layers, const void* const* v_new_layers,
+                                    const ems_kv_cache* caches, int n_layers, const int32_t* kv_start,
+                                    const int32_t* kv_len, int32_t* kv_len_out, int H, int D,
+                                    ems_dtype dtype, void* hip_stream) {
+    // every argument is checked before anything is launched
+    ems::AcceptParams pa;
+    ems_status st = prepare_accept(logits, logits_dtype, V, target_ids, input_ids, nullptr, cu_seqlens, B, T,
+                                   accepted, accepted_cu, out_tokens, nullptr, workspace, workspace_bytes, &pa);
+    if (st != EMS_OK) return st;
+    st = check_append(k_new_layers, v_new_layers, caches, n_layers, kv_start, kv_len, B, T, H, D, dtype);
+    if (st != EMS_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // One launch finds the counts and copies the rows, unless the lengths are updated in place
+    // (the copying blocks still read them), the layers need several launches, or there is nothing
+    // to copy: then the two calls run one after the other.
+    if (T == 0 || n_layers > ems::kMaxLayersPerLaunch || kv_len_out == kv_len) {
+        hipError_t e = ems::launch_greedy_accept(pa, stream);
+        if (e != hipSuccess) return hip_fail("accept launch", e);
+        return run_append(k_new_layers, v_new_layers, caches, n_layers, cu_seqlens, accepted, nullptr, nullptr,
+                          kv_start, kv_len, kv_len_out, B, T, H, D, dtype, hip_stream);
+    }
+    ems::AppendParams pp;
+    fill_append(pp, k_new_layers, v_new_layers, caches, 0, n_layers, cu_seqlens, nullptr, nullptr, nullptr,
+                kv_start, kv_len, kv_len_out, B, T, H, D);
+    hipError_t e = ems::launch_accept_append(pa, pp, stream);
+    if (e != hipSuccess) return hip_fail("accept and append launch", e);
+    return EMS_OK;
+}
+
 ems_status ems_kv_append_rows(const void* const* k_new_layers, const void* const* v_new_layers,
                               const ems_kv_cache* caches, int n_layers, const int32_t* accepted_rows,
                               const int32_t* accepted_cu, const int32_t* kv_start,
@@ -518,11 +571,9 @@ ems_status ems_kv_append_rows(const void* const* k_new_layers, const void* const
 
 namespace {
 
-ems_status run_append(const void* const* k_new_layers, const void* const* v_new_layers,
-                      const ems_kv_cache* caches, int n_layers, const int32_t* cu_seqlens,
-                      const int32_t* accepted, const int32_t* rows, const int32_t* rows_cu,
-                      const int32_t* kv_start, const int32_t* kv_len, int32_t* kv_len_out, int B,
-                      int T, int H, int D, ems_dtype dtype, void* hip_stream) {
+ems_status check_append(const void* const* k_new_layers, const void* const* v_new_layers,
+                        const ems_kv_cache* caches, int n_layers, const int32_t* kv_start,
+                        const int32_t* kv_len, int B, int T, int H, int D, ems_dtype dtype) {
     if (n_layers < 1) return fail(EMS_ERR_INVALID_ARG, "n_layers = %d, need n_layers >= 1", n_layers);
     if (B < 1) return fail(EMS_ERR_INVALID_ARG, "B = %d, need B >= 1", B);
     if (B > 65535 * 32) return fail(EMS_ERR_UNSUPPORTED, "B = %d is too large", B);
@@ -543,6 +594,45 @@ ems_status run_append(const void* const* k_new_layers, const void* const* v_new_
         if (c.row_stride < D || c.head_stride < D || (c.row_stride & 7) || (c.head_stride & 7))
             return fail(EMS_ERR_INVALID_ARG, "layer %d: cache strides must be multiples of 8 elements and at least D", l);
     }
+    return EMS_OK;
+}
+
+// The parameters of one append launch: layers l0 .. l0 + n - 1.
+void fill_append(ems::AppendParams& p, const void* const* k_new_layers, const void* const* v_new_layers,
+                 const ems_kv_cache* caches, int l0, int n, const int32_t* cu_seqlens, const int32_t* accepted,
+                 const int32_t* rows, const int32_t* rows_cu, const int32_t* kv_start, const int32_t* kv_len,
+                 int32_t* kv_len_out, int B, int T, int H, int D) {
+    std::memset(&p, 0, sizeof p);
+    p.n_layers = n;
+    for (int l = 0; l < n; ++l) {
+        ems::AppendLayer& ly = p.layer[l];
+        ly.k_new = static_cast<const char*>(k_new_layers[l0 + l]);
+        ly.v_new = static_cast<const char*>(v_new_layers[l0 + l]);
+        ly.k_cache = static_cast<char*>(caches[l0 + l].k);
+        ly.v_cache = static_cast<char*>(caches[l0 + l].v);
+        ly.row_stride_b = caches[l0 + l].row_stride * 2;
+        ly.head_stride_b = caches[l0 + l].head_stride * 2;
+    }
+    p.cu = cu_seqlens;
+    p.accepted = accepted;
+    p.rows = rows;
+    p.rows_cu = rows_cu;
+    p.T = T;
+    p.kv_start = kv_start;
+    p.kv_len = kv_len;
+    p.kv_len_out = kv_len_out;
+    p.B = B;
+    p.H = H;
+    p.vec_per_head = D / 8;
+}
+
+ems_status run_append(const void* const* k_new_layers, const void* const* v_new_layers,
+                      const ems_kv_cache* caches, int n_layers, const int32_t* cu_seqlens,
+                      const int32_t* accepted, const int32_t* rows, const int32_t* rows_cu,
+                      const int32_t* kv_start, const int32_t* kv_len, int32_t* kv_len_out, int B,
+                      int T, int H, int D, ems_dtype dtype, void* hip_stream) {
+    const ems_status st = check_append(k_new_layers, v_new_layers, caches, n_layers, kv_start, kv_len, B, T, H, D, dtype);
+    if (st != EMS_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     // kv_len_out is written by the first copy launch unless it aliases kv_len
     bool lengths_pending = kv_len_out != nullptr;
@@ -550,28 +640,9 @@ ems_status run_append(const void* const* k_new_layers, const void* const* v_new_
     if (T > 0) {
         for (int l0 = 0; l0 < n_layers; l0 += ems::kMaxLayersPerLaunch) {
             ems::AppendParams p;
-            std::memset(&p, 0, sizeof p);
-            p.n_layers = std::min(ems::kMaxLayersPerLaunch, n_layers - l0);
-            for (int l = 0; l < p.n_layers; ++l) {
-                ems::AppendLayer& ly = p.layer[l];
-                ly.k_new = static_cast<const char*>(k_new_layers[l0 + l]);
-                ly.v_new = static_cast<const char*>(v_new_layers[l0 + l]);
-                ly.k_cache = static_cast<char*>(caches[l0 + l].k);
-                ly.v_cache = static_cast<char*>(caches[l0 + l].v);
-                ly.row_stride_b = caches[l0 + l].row_stride * 2;
-                ly.head_stride_b = caches[l0 + l].head_stride * 2;
-            }
-            p.cu = cu_seqlens;
-            p.accepted = accepted;
-            p.rows = rows;
-            p.rows_cu = rows_cu;
-            p.T = T;
-            p.kv_start = kv_start;
-            p.kv_len = kv_len;
-            p.kv_len_out = (lengths_pending && !in_place) ? kv_len_out : nullptr;
-            p.B = B;
-            p.H = H;
-            p.vec_per_head = D / 8;
+            fill_append(p, k_new_layers, v_new_layers, caches, l0, std::min(ems::kMaxLayersPerLaunch, n_layers - l0),
+                        cu_seqlens, accepted, rows, rows_cu, kv_start, kv_len,
+                        (lengths_pending && !in_place) ? kv_len_out : nullptr, B, T, H, D);
             hipError_t e = ems::launch_kv_append(p, stream);
             if (e != hipSuccess) return hip_fail("ems_kv_append launch", e);
             if (!in_place) lengths_pending = false;

@@ -145,6 +145,9 @@ struct PaddedAppendParams {
 };
 
 hipError_t launch_kv_append(const AppendParams& p, hipStream_t stream);
+// ems_greedy_accept's launches with the append folded into the second one (tree == nullptr,
+// pp.rows == nullptr, pp.kv_len_out not aliasing pp.kv_len, pp.accepted unused)
+hipError_t launch_accept_append(const AcceptParams& pa, const AppendParams& pp, hipStream_t stream);
 hipError_t launch_padded_kv_append(const PaddedAppendParams& p, hipStream_t stream);
 // kv_len_out[i] = kv_len[i] + accepted[i], or + (rows_cu[i+1] - rows_cu[i]) when accepted is null
 hipError_t launch_advance_kv_len(const int32_t* kv_len, const int32_t* accepted, const int32_t* rows_cu,

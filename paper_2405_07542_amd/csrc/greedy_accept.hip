@@ -16,6 +16,7 @@
 // reports which packed rows form the accepted path.
 #include "ems_device.h"
 #include "ems_kernels.h"
+#include "kv_append_rows.h"
 
 namespace ems {
 
@@ -144,8 +145,7 @@ __device__ __forceinline__ int tree_walk(const AcceptParams& p, int base, int k,
 // partials nothing is read from global memory twice or in a dependent chain.
 constexpr int kMaxSlices = 16;
 
-__global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParams p) {
-    extern __shared__ int32_t accept_lds[];
+__device__ __forceinline__ void accept_scan_block(const AcceptParams& p, int32_t* accept_lds) {
     __shared__ int32_t wave_tot[kAcceptThreads / kWave];
     int32_t* const acc_s = accept_lds;                         // [B]
     int32_t* const cu_s = acc_s + p.B;                         // [B + 1]   (rows_in_lds)
@@ -283,7 +283,78 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParam
     }
 }
 
-hipError_t launch_greedy_accept(const AcceptParams& p, hipStream_t stream) {
+__global__ __launch_bounds__(kAcceptThreads) void accept_scan_kernel(AcceptParams p) {
+    extern __shared__ int32_t accept_lds[];
+    accept_scan_block(p, accept_lds);
+}
+
+// The accepted count of sample i, found by a whole block of kAcceptThreads threads from the same
+// inputs and by the same rule as accept_scan_block, so that both give the same number: 64 rows a
+// pass, 16 threads per row finish its arg-max over the slices (or one reads target_ids), the
+// first wave counts the leading matches.
+__device__ __forceinline__ int block_acceptance(const AcceptParams& p, int i) {
+    __shared__ int32_t match_s[kWave];
+    __shared__ int32_t lead_s;
+    const int tid = threadIdx.x;
+    const int base = p.cu[i];
+    const int k = p.cu[i + 1] - base;
+    if (k <= 0) return 0;
+    int m = 0;
+    for (int c0 = 0; c0 < k - 1; c0 += kWave) {          // rows c0 .. c0 + 63 against the drafts after them
+        const int j = c0 + (tid >> 4);
+        const int s = tid & 15;
+        int32_t arg = 0x7fffffff;
+        if (j < k - 1) {
+            if (p.logits != nullptr) {
+                float best = -INFINITY;
+                if (s < p.slices) {
+                    const ArgmaxPartial got = p.partial[(int64_t)(base + j) * p.slices + s];
+                    best = got.value;
+                    arg = got.index;
+                }
+                // (a slice that does not exist holds (-inf, max index): it never wins, since every real
+                // slice reports an index below V even when all its values are -inf)
+#pragma unroll
+                for (int off = 8; off >= 1; off >>= 1) {
+                    const float ov = __shfl_xor(best, off);
+                    const int32_t oi = __shfl_xor(arg, off);
+                    take_better(best, arg, ov, oi);
+                }
+            } else {
+                arg = p.target_ids[base + j];
+            }
+        }
+        if (s == 0) match_s[tid >> 4] = (j < k - 1 && arg == p.input_ids[base + j + 1]) ? 1 : 0;
+        __syncthreads();
+        if (tid < kWave) {
+            const uint64_t miss = ~__builtin_amdgcn_ballot_w64(match_s[tid] != 0);   // (a row past the last draft is a miss)
+            if (tid == 0) lead_s = miss != 0 ? __builtin_ctzll(miss) : kWave;
+        }
+        __syncthreads();
+        const int lead = lead_s;
+        m += lead;
+        if (lead < kWave) break;                          // (block-uniform)
+    }
+    return m + 1;
+}
+
+// Acceptance and append in one launch (Appendix A, then Sec. 3.2 "Unpad KV cache"): block
+// (B, 0, 0) is the scan block of accept_scan_kernel and writes every output of the acceptance;
+// block (i, y, 0) with i < B finds sample i's accepted count by itself (it cannot wait for the
+// scan block) and appends that many rows of layer y / 2's K or V.  The blocks (B, y > 0) have
+// nothing to do.
+__global__ __launch_bounds__(kAcceptThreads) void accept_append_kernel(AcceptParams pa, AppendParams pp) {
+    extern __shared__ int32_t accept_lds[];
+    if (blockIdx.x == (unsigned)pa.B) {
+        if (blockIdx.y == 0) accept_scan_block(pa, accept_lds);
+        return;
+    }
+    const int i = blockIdx.x;
+    const int acc = block_acceptance(pa, i);
+    append_sample_rows(pp, i, acc, blockIdx.y, 0, 1);
+}
+
+static hipError_t launch_argmax_partial(const AcceptParams& p, hipStream_t stream) {
     if (p.logits != nullptr && p.T > 0) {
         dim3 grid(p.slices, p.T);
         if (p.logits_dtype == 1)
@@ -292,14 +363,37 @@ hipError_t launch_greedy_accept(const AcceptParams& p, hipStream_t stream) {
             hipLaunchKernelGGL(argmax_partial_kernel<F32>, grid, dim3(kArgmaxThreads), 0, stream, p);
         else
             hipLaunchKernelGGL(argmax_partial_kernel<F16>, grid, dim3(kArgmaxThreads), 0, stream, p);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+        return hipGetLastError();
     }
+    return hipSuccess;
+}
+
+// LDS of the scan block: the small form (accepted counts only) or, when it fits in `limit`
+// bytes, the large one (rows_in_lds)
+static size_t scan_lds_bytes(AcceptParams& q, size_t limit) {
+    const size_t small = sizeof(int32_t) * (size_t)q.B;
+    const size_t large = sizeof(int32_t) * ((size_t)2 * q.B + 1 + (size_t)2 * q.T);
+    q.rows_in_lds = large <= limit ? 1 : 0;
+    return q.rows_in_lds ? large : small;
+}
+
+hipError_t launch_greedy_accept(const AcceptParams& p, hipStream_t stream) {
+    hipError_t e = launch_argmax_partial(p, stream);
+    if (e != hipSuccess) return e;
     AcceptParams q = p;
-    const size_t small = sizeof(int32_t) * (size_t)p.B;
-    const size_t large = sizeof(int32_t) * ((size_t)2 * p.B + 1 + (size_t)2 * p.T);
-    q.rows_in_lds = large <= 60 * 1024 ? 1 : 0;      // (a kernel may use 64 KiB of LDS without asking for more)
-    hipLaunchKernelGGL(accept_scan_kernel, dim3(1), dim3(kAcceptThreads), q.rows_in_lds ? large : small, stream, q);
+    const size_t lds = scan_lds_bytes(q, 60 * 1024);      // (a kernel may use 64 KiB of LDS without asking for more)
+    hipLaunchKernelGGL(accept_scan_kernel, dim3(1), dim3(kAcceptThreads), lds, stream, q);
+    return hipGetLastError();
+}
+
+hipError_t launch_accept_append(const AcceptParams& pa, const AppendParams& pp, hipStream_t stream) {
+    hipError_t e = launch_argmax_partial(pa, stream);
+    if (e != hipSuccess) return e;
+    AcceptParams q = pa;
+    // every block of the launch gets the scan block's LDS: keep it small when there are many
+    // appending blocks, so that it does not limit how many of them a CU holds
+    const size_t lds = scan_lds_bytes(q, (int64_t)pp.B * 2 * pp.n_layers > 1024 ? 8 * 1024 : 60 * 1024);
+    hipLaunchKernelGGL(accept_append_kernel, dim3(pa.B + 1, 2 * pp.n_layers, 1), dim3(kAcceptThreads), lds, stream, q, pp);
     return hipGetLastError();
 }
 

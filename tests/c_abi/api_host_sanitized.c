@@ -105,6 +105,31 @@ int main(void) {
     CHECK(ems_stub_launches == before + 4);
     CHECK(ems_kv_append_rows(knew, vnew, caches, LAYERS, FAKE32, FAKE32, FAKE32, FAKE32, NULL, 64, 384, 32, 128,
                              EMS_BF16, NULL) == EMS_OK);
+    /* acceptance and append as one call: one launch for up to 32 layers with lengths written elsewhere;
+       the two calls one after the other (1 + 3 launches, + 1 for lengths in place) beyond that */
+    before = ems_stub_launches;
+    CHECK(ems_greedy_accept_append(NULL, EMS_F16, 0, FAKE32, FAKE32, FAKE32, 64, 384, FAKE32, FAKE32, NULL, NULL, 0,
+                                   knew, vnew, caches, 32, FAKE32, FAKE32, FAKE32 + 64, 32, 128, EMS_F16, NULL) == EMS_OK);
+    CHECK(ems_stub_launches == before + 1);
+    before = ems_stub_launches;
+    CHECK(ems_greedy_accept_append(FAKE, EMS_BF16, 50272, FAKE32, FAKE32, FAKE32, 64, 384, FAKE32, FAKE32, FAKE32, FAKE,
+                                   ems_accept_workspace_bytes(384, 50272), knew, vnew, caches, LAYERS, FAKE32, FAKE32,
+                                   FAKE32 + 64, 32, 128, EMS_F16, NULL) == EMS_OK);
+    CHECK(ems_stub_launches == before + 4);
+    before = ems_stub_launches;
+    CHECK(ems_greedy_accept_append(NULL, EMS_F16, 0, FAKE32, FAKE32, FAKE32, 64, 384, FAKE32, FAKE32, NULL, NULL, 0,
+                                   knew, vnew, caches, 1, FAKE32, FAKE32, FAKE32, 32, 128, EMS_F16, NULL) == EMS_OK);
+    CHECK(ems_stub_launches == before + 3);
+    before = ems_stub_launches;      /* a refused call launches nothing, whichever half refuses */
+    CHECK(ems_greedy_accept_append(FAKE, EMS_BF16, 50272, FAKE32, FAKE32, FAKE32, 64, 384, FAKE32, FAKE32, FAKE32, FAKE, 8,
+                                   knew, vnew, caches, 1, FAKE32, FAKE32, NULL, 32, 128, EMS_F16, NULL) == EMS_ERR_WORKSPACE);
+    CHECK(ems_greedy_accept_append(NULL, EMS_F16, 0, FAKE32, FAKE32, FAKE32, 64, 384, FAKE32, FAKE32, NULL, NULL, 0,
+                                   knew, vnew, caches, 1, FAKE32, NULL, NULL, 32, 128, EMS_F16, NULL) == EMS_ERR_INVALID_ARG);
+    CHECK(ems_greedy_accept_append(NULL, EMS_F16, 0, FAKE32, FAKE32, FAKE32, 64, 384, FAKE32, FAKE32, NULL, NULL, 0,
+                                   knew, vnew, caches, 1, FAKE32, FAKE32, NULL, 32, 100, EMS_F16, NULL) == EMS_ERR_INVALID_ARG);
+    CHECK(ems_greedy_accept_append(NULL, EMS_F16, 0, FAKE32, FAKE32, NULL, 64, 384, FAKE32, FAKE32, NULL, NULL, 0,
+                                   knew, vnew, caches, 1, FAKE32, FAKE32, NULL, 32, 128, EMS_F16, NULL) == EMS_ERR_INVALID_ARG);
+    CHECK(ems_stub_launches == before);
     knew[LAYERS - 1] = NULL;
     CHECK(ems_kv_append(knew, vnew, caches, LAYERS, FAKE32, FAKE32, FAKE32, FAKE32, NULL, 64, 384, 32, 128, EMS_F16,
                         NULL) == EMS_ERR_INVALID_ARG);

@@ -44,6 +44,13 @@ hipError_t launch_kv_append(const AppendParams& p, hipStream_t) {
     ++ems_stub_launches;
     return hipSuccess;
 }
+hipError_t launch_accept_append(const AcceptParams& pa, const AppendParams& pp, hipStream_t) {
+    STUB_CHECK(pa.B >= 1 && pa.T >= 1 && pa.B == pp.B && pa.parent == nullptr && pa.cu == pp.cu);
+    STUB_CHECK(pp.n_layers >= 1 && pp.n_layers <= kMaxLayersPerLaunch && pp.rows == nullptr && pp.kv_len_out != pp.kv_len);
+    for (int l = 0; l < pp.n_layers; ++l) STUB_CHECK(pp.layer[l].k_new && pp.layer[l].k_cache && pp.layer[l].row_stride_b > 0);
+    ++ems_stub_launches;
+    return hipSuccess;
+}
 hipError_t launch_padded_kv_append(const PaddedAppendParams& p, hipStream_t) {
     STUB_CHECK(p.n_layers >= 1 && p.n_layers <= kMaxLayersPerLaunch && p.tau_max >= 1);
     ++ems_stub_launches;

@@ -111,6 +111,29 @@ def test_append_binding_refuses_wrong_layers_and_index_types():
         call()
 
 
+def test_accept_append_binding_checks_both_halves():
+    B, T = 2, 6
+    cache = ems.KvCacheStruct(16, 16, 128, 64, 32)
+
+    def call(rows=6, **over):
+        a = dict(target_ids=i32(T), input_ids=i32(T), cu_seqlens=i32(B + 1), accepted=i32(B), accepted_cu=i32(B + 1),
+                 kv_start=i32(B), kv_len=i32(B), kv_len_out=i32(B))
+        a.update(over)
+        ems.ems_greedy_accept_append(None, a["target_ids"], a["input_ids"], a["cu_seqlens"], a["accepted"],
+                                     a["accepted_cu"], None, [packed(rows)], [packed(rows)], [cache],
+                                     a["kv_start"], a["kv_len"], a["kv_len_out"])
+    with pytest.raises(TypeError, match="input_ids must have dtype torch.int32"):
+        call(input_ids=torch.zeros(T, dtype=torch.int64))
+    with pytest.raises(TypeError, match="kv_len must have dtype torch.int32"):
+        call(kv_len=torch.zeros(B, dtype=torch.int64))
+    with pytest.raises(ValueError, match="kv_start must hold 2 elements"):
+        call(kv_start=i32(3))
+    with pytest.raises(ValueError, match="k_new_layers hold 8 rows, input_ids 6"):
+        call(rows=8)
+    with pytest.raises(ValueError, match="must live in GPU memory"):
+        call()
+
+
 def test_kv_cache_refuses_mismatched_arenas():
     with pytest.raises(TypeError, match="k arena must have dtype"):
         ems.kv_cache(torch.zeros(64, dtype=torch.float32), torch.zeros(64, dtype=torch.float32), 64, 64, 1)

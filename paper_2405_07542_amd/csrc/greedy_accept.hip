@@ -14,6 +14,10 @@
 // With a parent array (token trees) step 2 walks from each sample's row 0 to the child
 // that carries the target's token instead of counting leading matches, and also
 // reports which packed rows form the accepted path.
+// accept_append_kernel is step 2 and the append of the accepted rows (Sec. 3.2 "Unpad KV cache")
+// in one launch: one workgroup is the scan block above, the others each find their own sample's
+// accepted count from the same partials and copy that many rows, so that no workgroup waits for
+// another.  The step around the attention call is bound by launches, not by bytes.
 #include "ems_device.h"
 #include "ems_kernels.h"
 #include "kv_append_rows.h"

@@ -15,7 +15,10 @@ set 0 against the oracle: max-abs error of the attention output, equality of ids
 offsets and appended cache rows) and `all_configs` (brief runs of configs 2, 3 and 5, so
 that B = 8, 32, 64 and 128 are all in the line).
 
-    python bench.py [--steps K] [--warmup W] [--config 2|3|4|5] [--layout token_major|head_major]
+    python bench.py [--steps K] [--warmup W] [--config 2|3|4|5] [--layout head_major|token_major]
+
+The cache arenas are head-major ([H, R, D]) unless --layout says otherwise: both layouts are the
+library's (a strided view), head-major is the one it reads 1-3 % faster.
 
 Side modes (sweeps, the paper's launch shape, dynamic batching) live in bench_modes.py.
 """
@@ -38,7 +41,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=4, help="BASELINE config number (2..5)")
-    ap.add_argument("--layout", default="token_major", choices=["token_major", "head_major"])
+    ap.add_argument("--layout", default="head_major", choices=["token_major", "head_major"],
+                    help="cache arena [H, R, D] (default: a 32-key tile of one head is 8 KiB contiguous) or [R, H, D]")
     ap.add_argument("--sets", type=int, default=0,
                     help="independent buffer sets rotated between steps so that no step finds its K/V in the "
                          "last-level cache; 0 (default) = as many as make the rotated K/V at least 2 GiB, "

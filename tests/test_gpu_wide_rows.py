@@ -103,6 +103,17 @@ def test_limits_of_the_other_variants():
     assert e.value.status == ems.EMS_ERR_UNSUPPORTED
 
 
+def test_staged_attention_is_deterministic():
+    """The requesting and the computing waves of the staged kernel meet through counters, in an
+    order that differs from run to run; what each wave adds up, and in which order partials are
+    merged, does not: the output bits are the same every time."""
+    from helpers import hip_attention
+    b = to_device(make_batch([900, 1200, 31, 2000], [40, 64, 17, 33], H=8, D=128, dtype=torch.bfloat16, seed=48))
+    first = hip_attention(b, out_dtype=torch.float32)
+    for _ in range(4):
+        assert torch.equal(hip_attention(b, out_dtype=torch.float32).view(torch.int32), first.view(torch.int32))
+
+
 @pytest.mark.parametrize("B,dtype,D,layout", [(8192, torch.bfloat16, 128, TOKEN_MAJOR), (8192, torch.float16, 80, HEAD_MAJOR),
                                                (7000, torch.float16, 128, HEAD_MAJOR), (5000, torch.bfloat16, 128, TOKEN_MAJOR)])
 def test_very_large_batches_through_the_wide_kernel(B, dtype, D, layout):
